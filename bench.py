@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the CentroidKV hot path on one MI355X.
+
+A step = one pass of the whole path over one batch of synthetic input that is already resident
+in HBM: ckv_compress of a full-model KV cache (all layers folded into the batch dimension, one
+launch per kernel per round) followed by one decode step of attention over the compressed cache
+(one ckv_decode_attn call per layer, as a model would issue them).
+
+Prints ONE JSON line.  `value` = context tokens pushed through the whole step per second.
+`roofline` describes the kernel with the largest share of GPU time (per-kernel times come from
+HIP events the library records on the launch stream during the timed steps); `kernels` lists the
+same figures for every hot kernel.  `cpu_baseline` is the numpy oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+
+WORKLOADS = {
+    # benchmark configs[2]: full-model prefill compression, Llama-3-8B KV shape, 128k tokens
+    "config3": dict(layers=32, kv_heads=8, q_heads=32, dim=128, seq=131072, chunk=1024, retain=0.25,
+                    alpha=0.9, n_outlier=4, desc="llama3-8b 32Lx8KVx128 bf16, seq 131072, chunk 1024, "
+                    "retain 25% (rounds [1,1]) + 1 GQA decode step (32 q heads) over the compressed cache"),
+    # benchmark configs[1]: one layer, 32k tokens (small: one launch is a few microseconds)
+    "config2": dict(layers=1, kv_heads=8, q_heads=32, dim=128, seq=32768, chunk=1024, retain=0.25,
+                    alpha=0.9, n_outlier=4, desc="llama3-8b single layer 8KVx128 bf16, seq 32768, chunk 1024, "
+                    "retain 25% + 1 GQA decode step"),
+}
+
+
+def algorithmic_work(cfg, plan):
+    """Algorithmic bytes / flops of one step, per kernel (whole launch set of that kernel)."""
+    n_bh = cfg["layers"] * cfg["kv_heads"]
+    d, e, c = cfg["dim"], 2, cfg["chunk"]
+    work = {"match_bf16": 0.0, "merge_bf16": 0.0, "attn_partial_bf16": 0.0}
+    for j, r in enumerate(plan.round_r):
+        s_in, s_out = plan.round_len[j], plan.round_len[j + 1]
+        full, tail = divmod(s_in, c)
+        flops = full * 2 * (c // 2) * (c // 2) * d + 2 * ((tail + 1) // 2) * (tail // 2) * d
+        work["match_bf16"] += n_bh * flops                                   # 2*|A|*|B|*d per chunk
+        n_src = full * (c // 2) + (tail + 1) // 2
+        deg_in = 0 if j == 0 else 4
+        work["merge_bf16"] += n_bh * (s_in * (2 * d * e + deg_in + 4) + n_src * 8 + s_out * (2 * d * e + 4))
+    work["attn_partial_bf16"] = n_bh * plan.out_seq * (2 * d * e + 4)        # K', V' rows + degree
+    return work
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config3", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=2024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists).",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2506_11418_amd as ckv
+    from synth import kv_device
+
+    cfg = WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    Ly, H, Hq, D, S = cfg["layers"], cfg["kv_heads"], cfg["q_heads"], cfg["dim"], cfg["seq"]
+
+    # ---- inputs, resident in HBM --------------------------------------------------------------
+    n_sets = 1 if Ly >= 8 else 8          # small workloads rotate over distinct buffers (MALL is 256 MB)
+    sets = []
+    for i in range(n_sets):
+        K = torch.empty((Ly, H, S, D), dtype=torch.bfloat16, device=dev)
+        V = torch.empty_like(K)
+        for l in range(Ly):
+            kv_device(args.seed + i, H, S, D, "bf16", cfg["alpha"], cfg["n_outlier"], layer=l, device=dev,
+                      out_k=K[l], out_v=V[l])
+        sets.append((K, V))
+    gen = torch.Generator(device=dev).manual_seed(args.seed + 99)
+    q = torch.randn((Ly, 1, Hq, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+    lay = ckv.layout_of(sets[0][0])
+    params = ckv.make_params(cfg["chunk"], cfg["retain"])
+    plan = ckv.plan(lay, params)
+    L2 = plan.out_seq
+    K_out = torch.empty((Ly, H, L2, D), dtype=torch.bfloat16, device=dev)
+    V_out = torch.empty_like(K_out)
+    deg_out = torch.empty((Ly, H, L2), dtype=torch.int32, device=dev)
+    assign = torch.empty((Ly, H, S), dtype=torch.int32, device=dev)
+    ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+    attn_lay = ckv.layout_of(K_out[0:1])
+    attn_ws = torch.empty(ckv.decode_attn_workspace(attn_lay, Hq), dtype=torch.uint8, device=dev)
+    o = torch.empty((Ly, 1, Hq, D), dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * args.steps)]
+
+    def step(i, timed):
+        K, V = sets[i % n_sets]
+        if timed:
+            ev[3 * i].record()
+        ckv.compress(K, V, cfg["chunk"], retain_ratio=cfg["retain"], out=(K_out, V_out, deg_out, assign),
+                     workspace=ws)
+        if timed:
+            ev[3 * i + 1].record()
+        for l in range(Ly):
+            ckv.decode_attn(q[l], K_out[l:l + 1], V_out[l:l + 1], deg=deg_out[l:l + 1], out=o[l], workspace=attn_ws)
+        if timed:
+            ev[3 * i + 2].record()
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    ckv.timing_reset()
+    ckv.timing_enable(True)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ckv.timing_enable(False)
+    ktimes = ckv.timing_read()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    comp_ms = float(np.mean([ev[3 * i].elapsed_time(ev[3 * i + 1]) for i in range(args.steps)]))
+    dec_ms = float(np.mean([ev[3 * i + 1].elapsed_time(ev[3 * i + 2]) for i in range(args.steps)]))
+
+    # ---- per-kernel roofline figures ------------------------------------------------------------
+    work = algorithmic_work(cfg, plan)
+    kernels = {}
+    for name, (tot_ms, launches) in ktimes.items():
+        per_step_ms = tot_ms / args.steps
+        ent = {"ms_per_step": round(per_step_ms, 4), "launches_per_step": launches / args.steps,
+               "avg_launch_us": round(tot_ms * 1e3 / max(launches, 1), 2)}
+        if name == "match_bf16":
+            ach = work[name] / (per_step_ms * 1e-3) / 1e12
+            ent.update(bound="mfma", achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                       frac=round(ach / PEAK_BF16_TFLOPS, 4))
+        elif name in work:
+            ach = work[name] / (per_step_ms * 1e-3) / 1e9
+            ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                       frac=round(ach / PEAK_HBM_GBS, 4))
+        kernels[name] = ent
+    hot = [k for k in kernels if k in work]
+    dom = max(hot, key=lambda k: kernels[k]["ms_per_step"])
+    roofline = {"kernel": dom, **{k: kernels[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")},
+                "traffic": None}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample ---------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        n_heads = 2
+        Kh = sets[0][0][0, :n_heads].to("cpu").to(torch.float64).numpy()
+        Vh = sets[0][1][0, :n_heads].to("cpu").to(torch.float64).numpy()
+        qh = q[0, 0, : n_heads * (Hq // H)].to("cpu").to(torch.float64).numpy()
+        c0 = time.perf_counter()
+        outs = [oracle.compress(Kh[h], Vh[h], cfg["chunk"], plan.round_r, "bf16") for h in range(n_heads)]
+        oracle.app_attn(qh, np.stack([x["K"] for x in outs]), np.stack([x["V"] for x in outs]),
+                        np.stack([x["deg"] for x in outs]))
+        c1 = time.perf_counter()
+        frac_of_model = n_heads / (Ly * H)
+        cpu = {"value": round(S * frac_of_model / (c1 - c0), 2), "unit": "tokens/s", "cores": int(cores),
+               "kind": "oracle",
+               "sample": f"{n_heads} of {Ly * H} (layer, KV head) sequences of {S} tokens: oracle.compress "
+                         f"(rounds {plan.round_r}) + oracle.app_attn, {c1 - c0:.1f} s; scaled to whole-model tokens"}
+
+    dec_bytes = work["attn_partial_bf16"]
+    out = {
+        "metric": "KV tokens compressed/sec + decode-attn HBM GB/s (fraction of MI355X peak)",
+        "value": round(S / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {cfg['desc']}", "layers": Ly, "kv_heads": H, "q_heads": Hq,
+                   "head_dim": D, "seq_len": S, "chunk": cfg["chunk"], "retain_ratio": cfg["retain"],
+                   "rounds": plan.round_r, "compressed_len": L2, "parallelism": "1 GPU"},
+        "compress_ms": round(comp_ms, 4), "decode_ms": round(dec_ms, 4),
+        "compress_tokens_per_s": round(S / (comp_ms * 1e-3), 1),
+        "compress_head_tokens_per_s": round(S * Ly * H / (comp_ms * 1e-3), 1),
+        "decode_attn_GBps_wall": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

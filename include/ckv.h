@@ -1,0 +1,143 @@
+/*
+ * ckv.h - C ABI of libckv: CentroidKV's KV-cache compression (Chunked Soft Matching +
+ * degree-weighted merge) and decode attention over the compressed cache, as hand-written
+ * gfx950 (MI355X) HIP kernels.  Paper: arXiv 2506.11418.
+ *
+ * Conventions for every function
+ *   - returns CKV_OK (0) or a negative ckv_status; never throws, aborts or prints;
+ *   - pointers named K, V, q, o, deg, lens, assign, dst, score, workspace are DEVICE pointers
+ *     (HIP global memory of the current device); ckv_layout / ckv_params / ckv_plan_t and
+ *     other struct pointers are HOST pointers;
+ *   - the caller owns every buffer; the library allocates and frees no device memory;
+ *   - work is enqueued on `hip_stream` (a hipStream_t, NULL = the default stream) and the call
+ *     returns without synchronising; argument errors are detected on the host before any launch;
+ *   - inputs are never written; outputs and workspace must not overlap inputs (CKV_EINVAL);
+ *   - base pointers and row strides (in bytes) of K/V tensors are multiples of 16 (CKV_EALIGN).
+ *
+ * Tensor layout ("layout"): element (b, h, t, :) of a [batch, heads, seq, dim] tensor lives at
+ * base + b*stride_b + h*stride_h + t*stride_s (strides in ELEMENTS); dim is contiguous.  This
+ * covers [B,H,S,D] and [B,S,H,D] storage.  `heads` are KV heads; layers are folded into batch
+ * or heads by the caller, every (batch, head) sequence is compressed independently (Sec. 3:
+ * the method is stated per attention head).
+ */
+#ifndef CKV_H
+#define CKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CKV_OK = 0,
+  CKV_EINVAL = -1,       /* null pointer, bad enum, bad ratio, overlapping buffers            */
+  CKV_ESHAPE = -2,       /* non-positive size, stride smaller than the extent it spans         */
+  CKV_EALIGN = -3,       /* pointer or row stride not a multiple of 16 bytes                   */
+  CKV_EWORKSPACE = -4,   /* workspace smaller than ckv_plan / ckv_decode_attn_workspace said   */
+  CKV_EUNSUPPORTED = -5, /* valid request this build has no kernel for (see each function)     */
+  CKV_EHIP = -6          /* a HIP call failed; the HIP error state has been cleared            */
+} ckv_status;
+
+typedef enum { CKV_F32 = 0, CKV_BF16 = 1 } ckv_dtype;
+
+typedef struct {
+  int32_t batch, heads, seq, dim;
+  int64_t stride_b, stride_h, stride_s; /* in elements */
+  int32_t dtype;                        /* ckv_dtype */
+} ckv_layout;
+
+#define CKV_MAX_ROUNDS 8
+
+/* Parameters of CentroidKV(K, V, N, s, n1, n2, r, c) (Algorithm 1, Sec. 5). */
+typedef struct {
+  int32_t chunk;        /* c: chunk size in tokens, even, 2..2048 (Sec. 5.2)                     */
+  float retain_ratio;   /* rho in (0,1]: fraction of tokens kept; used when n_rounds == 0.
+                           Schedule: J = ceil(log2(1/rho)) rounds (a round removes at most half,
+                           Sec. 5.1), r = 1 for the first J-1 and r = 2(1 - rho*2^(J-1)) last.  */
+  int32_t n_rounds;     /* > 0: run exactly these rounds with merge fractions r[0..n_rounds)     */
+  float r[CKV_MAX_ROUNDS]; /* r_j in [0,1]: fraction of a chunk's candidate edges merged (5.3)   */
+  int32_t n_sink, n_recent; /* n1, n2 of Algorithm 1: reserved, must be 0 (CKV_EUNSUPPORTED)     */
+} ckv_params;
+
+typedef struct {
+  int32_t out_seq;                       /* tokens per (batch, head) after the last round        */
+  int32_t n_rounds;
+  int32_t round_len[CKV_MAX_ROUNDS + 1]; /* round_len[0] = seq, round_len[j+1] after round j     */
+  float round_r[CKV_MAX_ROUNDS];         /* the merge fraction each round uses                   */
+  size_t workspace_bytes;                /* device scratch ckv_compress needs                    */
+} ckv_plan_t;
+
+const char* ckv_version(void);
+const char* ckv_strerror(int status);
+
+/* Host only.  Resolves the rounds schedule and the sequence length after every round.
+ * One round (Sec. 5.2-5.3): chunks of `chunk` consecutive tokens (last may be shorter); inside a
+ * chunk of L tokens set A = 1st, 3rd, ... token (ceil(L/2) sources), B = 2nd, 4th, ...; the
+ * m = floor(r*|A| + 1e-9) best edges are merged, so the chunk keeps L - m tokens (a chunk with
+ * L < 2 keeps all).  Lengths depend only on (seq, chunk, schedule), never on data. */
+int ckv_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan);
+
+/* Similarity + matching stage alone (Sec. 5.2; Eq. 2): for every A token its most similar B
+ * token of the same chunk under cosine similarity of the keys (lowest B index on ties).
+ *   dst   [batch, heads, n_src] int32: position in the sequence of the matched B token (-1 when the
+ *         chunk has no B token);  n_src = number of A tokens = sum over chunks of ceil(L/2),
+ *         sources ordered by position.
+ *   score [batch, heads, n_src] fp32: cosine similarity of that edge.
+ * bf16 keys: dot products of the stored values on bf16 MFMA with fp32 accumulation, inverse norms
+ * in fp32 applied afterwards (keys are not re-rounded).  Supported: bf16 dim 64 or 128; fp32 dim
+ * 16..128 multiple of 16. */
+int ckv_match(const void* K, const ckv_layout* in, int32_t chunk, int32_t* dst, float* score,
+              void* hip_stream);
+
+/* Compress a KV cache (Algorithm 1, the loop after prefill; Sec. 5.2-5.3).
+ *   K, V     inputs, layout `in`;  deg_in [batch, heads, seq] int32 cluster degrees or NULL (= 1).
+ *   K_out, V_out  layout `out` (same batch/heads/dim/dtype; out->seq >= plan.out_seq); rows
+ *            [0, plan.out_seq) of every (batch, head) are written: the retained tokens in their
+ *            original order, each B token replaced by the degree-weighted mean of itself and the
+ *            A tokens merged into it (keys and values alike), rounded to nearest-even.
+ *   deg_out  [batch, heads, out->seq] int32 degrees of the output tokens.
+ *   assign   [batch, heads, seq] int32 or NULL: output index of the centroid each INPUT token
+ *            ended up in (composition over rounds).
+ *   workspace  >= plan.workspace_bytes, 256-byte aligned.
+ * Every round re-chunks the current sequence with the same chunk size. */
+int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_layout* in,
+                 const ckv_params* p, void* K_out, void* V_out, int32_t* deg_out,
+                 const ckv_layout* out, int32_t* assign, void* workspace, size_t workspace_bytes,
+                 void* hip_stream);
+
+/* Scratch bytes ckv_decode_attn needs for this cache shape and number of query heads. */
+int ckv_decode_attn_workspace(const ckv_layout* kv, int32_t q_heads, size_t* bytes);
+
+/* One decode step of attention over a (compressed) cache (Eq. 3; Algorithm 1 decode line):
+ *   o[b,h,:] = softmax( q[b,h,:] . K[b,kvh,t,:] * scale + ln deg[b,kvh,t] ) . V[b,kvh,t,:],
+ *   t < lens[b], kvh = h / (q_heads / kv->heads).
+ *   q [batch, q_heads, dim] contiguous, same dtype as the cache; lens [batch] int32 (each
+ *   <= kv->seq; 0 gives a zero output) or NULL (= kv->seq); deg [batch, heads, kv->seq] int32
+ *   (>= 1) or NULL (= 1: plain attention, Eq. 1); scale <= 0 selects 1/sqrt(dim);
+ *   o [batch, q_heads, dim] contiguous in o_dtype.  Arithmetic is fp32.
+ * Supported: q_heads / kv->heads in {1,2,4,8}; bf16 dim 64/128; fp32 dim 32/64/128. */
+int ckv_decode_attn(const void* q, int32_t q_heads, const void* K, const void* V,
+                    const ckv_layout* kv, const int32_t* lens, const int32_t* deg, float scale,
+                    void* o, int32_t o_dtype, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+/* Per-kernel timing for benchmarks.  When enabled, every kernel launch of the calling process
+ * is bracketed by HIP events on its stream (a few microseconds of host overhead per launch).
+ * ckv_timing_read synchronises with the recorded events, then fills up to `max` entries with the
+ * accumulated time per kernel since the last reset and returns the number of kernels (or a
+ * negative status).  Not thread-safe; meant for a single benchmarking thread. */
+typedef struct {
+  char name[48];
+  double total_ms;
+  int64_t launches;
+} ckv_kernel_time;
+int ckv_timing_enable(int on);
+int ckv_timing_reset(void);
+int ckv_timing_read(ckv_kernel_time* out, int max);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKV_H */

@@ -1,0 +1,214 @@
+"""Thin Python binding of libckv (C ABI in include/ckv.h).
+
+Only argument marshalling happens here: torch tensors provide device memory and the current HIP
+stream; every step of the path runs in the library's kernels.  There is no CPU fallback: if the
+shared library has not been built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libckv.so")
+MAX_ROUNDS = 8
+F32, BF16 = 0, 1
+_DT = {torch.float32: F32, torch.bfloat16: BF16}
+
+
+class CkvError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {lib().ckv_strerror(status).decode()} (status {status})")
+        self.status = status
+
+
+class Layout(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("heads", C.c_int32), ("seq", C.c_int32), ("dim", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_s", C.c_int64),
+                ("dtype", C.c_int32)]
+
+
+class Params(C.Structure):
+    _fields_ = [("chunk", C.c_int32), ("retain_ratio", C.c_float), ("n_rounds", C.c_int32),
+                ("r", C.c_float * MAX_ROUNDS), ("n_sink", C.c_int32), ("n_recent", C.c_int32)]
+
+
+class PlanT(C.Structure):
+    _fields_ = [("out_seq", C.c_int32), ("n_rounds", C.c_int32),
+                ("round_len", C.c_int32 * (MAX_ROUNDS + 1)), ("round_r", C.c_float * MAX_ROUNDS),
+                ("workspace_bytes", C.c_size_t)]
+
+
+class KernelTime(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("total_ms", C.c_double), ("launches", C.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libckv.so (built in-tree by paper_2506_11418_amd.build); fail loudly if missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2506_11418_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32 = C.c_void_p, C.c_int32
+        L.ckv_version.restype = C.c_char_p
+        L.ckv_strerror.restype = C.c_char_p
+        L.ckv_strerror.argtypes = [C.c_int]
+        L.ckv_plan.argtypes = [C.POINTER(Layout), C.POINTER(Params), C.POINTER(PlanT)]
+        L.ckv_match.argtypes = [vp, C.POINTER(Layout), i32, vp, vp, vp]
+        L.ckv_compress.argtypes = [vp, vp, vp, C.POINTER(Layout), C.POINTER(Params), vp, vp, vp,
+                                   C.POINTER(Layout), vp, vp, C.c_size_t, vp]
+        L.ckv_decode_attn_workspace.argtypes = [C.POINTER(Layout), i32, C.POINTER(C.c_size_t)]
+        L.ckv_decode_attn.argtypes = [vp, i32, vp, vp, C.POINTER(Layout), vp, vp, C.c_float, vp, i32,
+                                      vp, C.c_size_t, vp]
+        L.ckv_timing_enable.argtypes = [C.c_int]
+        L.ckv_timing_read.argtypes = [C.POINTER(KernelTime), C.c_int]
+        _lib = L
+    return _lib
+
+
+def version() -> str:
+    return lib().ckv_version().decode()
+
+
+def layout_of(t: torch.Tensor) -> Layout:
+    """Layout of a [batch, heads, seq, dim] tensor (any strides, dim contiguous)."""
+    if t.dim() != 4 or t.stride(3) != 1 or t.dtype not in _DT:
+        raise ValueError("expected a [batch, heads, seq, dim] float32/bfloat16 tensor with contiguous dim")
+    return Layout(t.shape[0], t.shape[1], t.shape[2], t.shape[3], t.stride(0), t.stride(1), t.stride(2),
+                  _DT[t.dtype])
+
+
+def make_params(chunk: int, retain_ratio: float = 1.0, rounds: Optional[Sequence[float]] = None) -> Params:
+    p = Params()
+    p.chunk, p.retain_ratio, p.n_sink, p.n_recent = chunk, retain_ratio, 0, 0
+    if rounds is not None:
+        if not 0 < len(rounds) <= MAX_ROUNDS:
+            raise ValueError("rounds must have 1..8 entries")
+        p.n_rounds = len(rounds)
+        for j, r in enumerate(rounds):
+            p.r[j] = r
+    return p
+
+
+@dataclass
+class Plan:
+    out_seq: int
+    round_len: list
+    round_r: list
+    workspace_bytes: int
+
+
+def plan(lay: Layout, params: Params) -> Plan:
+    pt = PlanT()
+    st = lib().ckv_plan(C.byref(lay), C.byref(params), C.byref(pt))
+    if st != 0:
+        raise CkvError(st, "ckv_plan")
+    return Plan(pt.out_seq, list(pt.round_len[: pt.n_rounds + 1]), list(pt.round_r[: pt.n_rounds]),
+                pt.workspace_bytes)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def match(K: torch.Tensor, chunk: int):
+    """ckv_match: (dst positions int32 [B,H,n_src], scores fp32 [B,H,n_src])."""
+    lay = layout_of(K)
+    s = K.shape[2]
+    n_src = (s // chunk) * (chunk // 2) + ((s % chunk) + 1) // 2
+    dst = torch.empty((K.shape[0], K.shape[1], n_src), dtype=torch.int32, device=K.device)
+    score = torch.empty((K.shape[0], K.shape[1], n_src), dtype=torch.float32, device=K.device)
+    st = lib().ckv_match(_ptr(K), C.byref(lay), chunk, _ptr(dst), _ptr(score), _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_match")
+    return dst, score
+
+
+def compress(K: torch.Tensor, V: torch.Tensor, chunk: int, retain_ratio: float = 1.0,
+             rounds: Optional[Sequence[float]] = None, deg: Optional[torch.Tensor] = None,
+             want_assign: bool = True, out: Optional[tuple] = None,
+             workspace: Optional[torch.Tensor] = None):
+    """ckv_compress: returns (K', V', deg', assign or None).  K, V: [B,H,S,D] on the GPU.
+
+    `out` may pass preallocated (K_out, V_out, deg_out, assign) and `workspace` a uint8 tensor, so
+    that a timed loop allocates nothing."""
+    lay = layout_of(K)
+    if layout_of(V).dtype != lay.dtype or V.shape != K.shape:
+        raise ValueError("K and V must have the same shape and dtype")
+    params = make_params(chunk, retain_ratio, rounds)
+    pl = plan(lay, params)
+    B, H, S, D = K.shape
+    if out is None:
+        K_out = torch.empty((B, H, pl.out_seq, D), dtype=K.dtype, device=K.device)
+        V_out = torch.empty_like(K_out)
+        deg_out = torch.empty((B, H, pl.out_seq), dtype=torch.int32, device=K.device)
+        assign = torch.empty((B, H, S), dtype=torch.int32, device=K.device) if want_assign else None
+    else:
+        K_out, V_out, deg_out, assign = out
+    if workspace is None:
+        workspace = torch.empty(max(pl.workspace_bytes, 256), dtype=torch.uint8, device=K.device)
+    olay = layout_of(K_out)
+    st = lib().ckv_compress(_ptr(K), _ptr(V), _ptr(deg), C.byref(lay), C.byref(params), _ptr(K_out),
+                            _ptr(V_out), _ptr(deg_out), C.byref(olay), _ptr(assign), _ptr(workspace),
+                            workspace.numel(), _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_compress")
+    return K_out, V_out, deg_out, assign
+
+
+def decode_attn_workspace(lay: Layout, q_heads: int) -> int:
+    n = C.c_size_t(0)
+    st = lib().ckv_decode_attn_workspace(C.byref(lay), q_heads, C.byref(n))
+    if st != 0:
+        raise CkvError(st, "ckv_decode_attn_workspace")
+    return n.value
+
+
+def decode_attn(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, lens: Optional[torch.Tensor] = None,
+                deg: Optional[torch.Tensor] = None, scale: float = 0.0, out_dtype=None,
+                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """ckv_decode_attn: q [B,Hq,D], K/V [B,Hkv,L,D], lens [B] int32, deg [B,Hkv,L] int32 -> o [B,Hq,D]."""
+    lay = layout_of(K)
+    if not q.is_contiguous() or q.dim() != 3 or q.dtype != K.dtype:
+        raise ValueError("q must be a contiguous [batch, q_heads, dim] tensor of the cache dtype")
+    if deg is not None and not deg.is_contiguous():
+        raise ValueError("deg must be contiguous [batch, heads, seq]")
+    q_heads = q.shape[1]
+    if out is None:
+        out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(decode_attn_workspace(lay, q_heads), dtype=torch.uint8, device=q.device)
+    st = lib().ckv_decode_attn(_ptr(q), q_heads, _ptr(K), _ptr(V), C.byref(lay), _ptr(lens), _ptr(deg),
+                               scale, _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(),
+                               _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_decode_attn")
+    return out
+
+
+def timing_enable(on: bool) -> None:
+    lib().ckv_timing_enable(1 if on else 0)
+
+
+def timing_reset() -> None:
+    lib().ckv_timing_reset()
+
+
+def timing_read() -> dict:
+    buf = (KernelTime * 32)()
+    n = lib().ckv_timing_read(buf, 32)
+    if n < 0:
+        raise CkvError(n, "ckv_timing_read")
+    return {buf[i].name.decode(): (buf[i].total_ms, buf[i].launches) for i in range(min(n, 32))}

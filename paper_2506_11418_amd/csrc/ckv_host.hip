@@ -1,0 +1,334 @@
+// Host driver of libckv: argument validation, the rounds schedule (Algorithm 1's loop after
+// prefill), workspace carving, kernel sequencing and optional per-kernel timing.
+#include <math.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "ckv_internal.h"
+
+namespace ckv {
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+int elem_bytes(int dtype) { return dtype == CKV_BF16 ? 2 : 4; }
+
+int check_layout(const ckv_layout* l) {
+  if (!l) return CKV_EINVAL;
+  if (l->dtype != CKV_F32 && l->dtype != CKV_BF16) return CKV_EINVAL;
+  if (l->batch <= 0 || l->heads <= 0 || l->seq <= 0 || l->dim <= 0) return CKV_ESHAPE;
+  if (l->stride_s < l->dim || l->stride_h < l->dim || l->stride_b < l->dim) return CKV_ESHAPE;
+  if ((int64_t)l->batch * l->heads > (1 << 24)) return CKV_ESHAPE;
+  const int e = elem_bytes(l->dtype);
+  if ((l->stride_s * e) % 16 || (l->stride_h * e) % 16 || (l->stride_b * e) % 16 || (l->dim * e) % 16)
+    return CKV_EALIGN;
+  return CKV_OK;
+}
+
+// bytes spanned by a tensor with this layout, from its base pointer
+size_t extent_bytes(const ckv_layout* l, int seq) {
+  const int64_t last = (int64_t)(l->batch - 1) * l->stride_b + (int64_t)(l->heads - 1) * l->stride_h +
+                       (int64_t)(seq - 1) * l->stride_s + l->dim;
+  return (size_t)last * elem_bytes(l->dtype);
+}
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + nb && y < x + na;
+}
+
+bool dims_supported(int dtype, int dim) {
+  if (dtype == CKV_BF16) return dim == 64 || dim == 128;
+  return dim == 16 || dim == 32 || dim == 64 || dim == 128;
+}
+
+TensorView view_of(const ckv_layout* l) { return TensorView{l->stride_b, l->stride_h, l->stride_s, l->heads}; }
+TensorView compact_view(int heads, int len, int dim) {
+  return TensorView{(int64_t)heads * len * dim, (int64_t)len * dim, (int64_t)dim, heads};
+}
+
+int seq_after_round(int len, int chunk, float r) {
+  const int full = len / chunk, tail = len % chunk;
+  return full * chunk_out(chunk, r) + chunk_out(tail, r);
+}
+
+struct Workspace {
+  size_t dst, score, map, K[2], V[2], deg[2], total;
+};
+
+Workspace carve(const ckv_layout* in, const ckv_plan_t* plan, int chunk) {
+  Workspace w{};
+  const size_t n_bh = (size_t)in->batch * in->heads;
+  const size_t e = elem_bytes(in->dtype);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  const size_t n_src0 = n_sources(in->seq, chunk);
+  w.dst = take(n_bh * n_src0 * 4);
+  w.score = take(n_bh * n_src0 * 4);
+  const int inter = plan->n_rounds - 1;   // intermediate caches
+  if (inter >= 1) w.map = take(n_bh * (size_t)plan->round_len[1] * 4);
+  for (int k = 0; k < 2 && k < inter; ++k) {
+    const size_t len = plan->round_len[k + 1];
+    w.K[k] = take(n_bh * len * in->dim * e);
+    w.V[k] = take(n_bh * len * in->dim * e);
+    w.deg[k] = take(n_bh * len * 4);
+  }
+  w.total = off;
+  return w;
+}
+
+int make_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan) {
+  int st = check_layout(in);
+  if (st != CKV_OK) return st;
+  if (!p || !plan) return CKV_EINVAL;
+  if (p->chunk < 2 || p->chunk > 2048 || (p->chunk & 1)) return CKV_EINVAL;
+  if (p->n_sink != 0 || p->n_recent != 0) return CKV_EUNSUPPORTED;
+  if (p->n_rounds < 0 || p->n_rounds > CKV_MAX_ROUNDS) return CKV_EINVAL;
+  memset(plan, 0, sizeof(*plan));
+  if (p->n_rounds > 0) {
+    plan->n_rounds = p->n_rounds;
+    for (int j = 0; j < p->n_rounds; ++j) {
+      if (!(p->r[j] >= 0.f && p->r[j] <= 1.f)) return CKV_EINVAL;
+      plan->round_r[j] = p->r[j];
+    }
+  } else {
+    const double rho = (double)p->retain_ratio;
+    if (!(rho > 0.0 && rho <= 1.0)) return CKV_EINVAL;
+    int J = 0;
+    while (ldexp(1.0, -J) > rho * (1.0 + 1e-6)) ++J;
+    if (J > CKV_MAX_ROUNDS) return CKV_EINVAL;
+    plan->n_rounds = J;
+    for (int j = 0; j < J; ++j) plan->round_r[j] = 1.0f;
+    if (J > 0) plan->round_r[J - 1] = (float)(2.0 * (1.0 - rho * ldexp(1.0, J - 1)));
+  }
+  plan->round_len[0] = in->seq;
+  for (int j = 0; j < plan->n_rounds; ++j)
+    plan->round_len[j + 1] = seq_after_round(plan->round_len[j], p->chunk, plan->round_r[j]);
+  plan->out_seq = plan->round_len[plan->n_rounds];
+  plan->workspace_bytes = carve(in, plan, p->chunk).total;
+  return CKV_OK;
+}
+
+int hip_status(hipError_t e) {
+  if (e == hipSuccess) return CKV_OK;
+  (void)hipGetLastError();
+  return (e == hipErrorInvalidValue) ? CKV_EUNSUPPORTED : CKV_EHIP;
+}
+
+// ---- timing --------------------------------------------------------------------------------
+struct TimedLaunch {
+  const char* name;
+  hipEvent_t a, b;
+};
+bool g_timing = false;
+std::vector<TimedLaunch> g_launches;
+std::vector<std::pair<std::string, std::pair<double, int64_t>>> g_totals;
+
+void fold_launches() {
+  for (auto& t : g_launches) {
+    float ms = 0.f;
+    if (hipEventSynchronize(t.b) == hipSuccess && hipEventElapsedTime(&ms, t.a, t.b) == hipSuccess) {
+      bool found = false;
+      for (auto& kv : g_totals)
+        if (kv.first == t.name) { kv.second.first += ms; kv.second.second += 1; found = true; break; }
+      if (!found) g_totals.push_back({t.name, {ms, 1}});
+    }
+    (void)hipEventDestroy(t.a);
+    (void)hipEventDestroy(t.b);
+  }
+  g_launches.clear();
+  (void)hipGetLastError();
+}
+
+}  // namespace
+
+void timing_begin(const char* name, hipStream_t st) {
+  if (!g_timing) return;
+  TimedLaunch t{name, nullptr, nullptr};
+  if (hipEventCreate(&t.a) != hipSuccess || hipEventCreate(&t.b) != hipSuccess) return;
+  (void)hipEventRecord(t.a, st);
+  g_launches.push_back(t);
+}
+
+void timing_end(hipStream_t st) {
+  if (!g_timing || g_launches.empty()) return;
+  (void)hipEventRecord(g_launches.back().b, st);
+}
+
+}  // namespace ckv
+
+using namespace ckv;
+
+extern "C" {
+
+const char* ckv_version(void) { return "ckv 0.1 (gfx950)"; }
+
+const char* ckv_strerror(int status) {
+  switch (status) {
+    case CKV_OK: return "ok";
+    case CKV_EINVAL: return "invalid argument";
+    case CKV_ESHAPE: return "invalid shape or stride";
+    case CKV_EALIGN: return "pointer or stride not 16-byte aligned";
+    case CKV_EWORKSPACE: return "workspace too small";
+    case CKV_EUNSUPPORTED: return "unsupported configuration";
+    case CKV_EHIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int ckv_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan) { return make_plan(in, p, plan); }
+
+int ckv_match(const void* K, const ckv_layout* in, int32_t chunk, int32_t* dst, float* score, void* hip_stream) {
+  int st = check_layout(in);
+  if (st != CKV_OK) return st;
+  if (!K || !dst || !score) return CKV_EINVAL;
+  if (chunk < 2 || chunk > 2048 || (chunk & 1)) return CKV_EINVAL;
+  if (((uintptr_t)K) % 16 || ((uintptr_t)dst) % 4 || ((uintptr_t)score) % 4) return CKV_EALIGN;
+  if (!dims_supported(in->dtype, in->dim)) return CKV_EUNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int n_bh = in->batch * in->heads;
+  hipError_t e = launch_match(K, in->dtype, in->dim, view_of(in), n_bh, in->seq, chunk, dst, score, s);
+  if (e != hipSuccess) return hip_status(e);
+  return hip_status(launch_dst_positions(dst, dst, n_bh, in->seq, chunk, s));
+}
+
+int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_layout* in, const ckv_params* p,
+                 void* K_out, void* V_out, int32_t* deg_out, const ckv_layout* out, int32_t* assign,
+                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+  ckv_plan_t plan;
+  int st = make_plan(in, p, &plan);
+  if (st != CKV_OK) return st;
+  st = check_layout(out);
+  if (st != CKV_OK) return st;
+  if (!K || !V || !K_out || !V_out || !deg_out) return CKV_EINVAL;
+  if (out->batch != in->batch || out->heads != in->heads || out->dim != in->dim || out->dtype != in->dtype)
+    return CKV_ESHAPE;
+  if (out->seq < plan.out_seq) return CKV_ESHAPE;
+  if (((uintptr_t)K) % 16 || ((uintptr_t)V) % 16 || ((uintptr_t)K_out) % 16 || ((uintptr_t)V_out) % 16 ||
+      ((uintptr_t)deg_out) % 4 || ((uintptr_t)deg_in) % 4 || ((uintptr_t)assign) % 4)
+    return CKV_EALIGN;
+  if (!dims_supported(in->dtype, in->dim)) return CKV_EUNSUPPORTED;
+  if (plan.workspace_bytes > 0) {
+    if (!workspace) return CKV_EINVAL;
+    if (((uintptr_t)workspace) % 256) return CKV_EALIGN;
+    if (workspace_bytes < plan.workspace_bytes) return CKV_EWORKSPACE;
+  }
+  {
+    const size_t in_b = extent_bytes(in, in->seq), out_b = extent_bytes(out, plan.out_seq);
+    const void* ins[2] = {K, V};
+    const void* outs[2] = {K_out, V_out};
+    for (auto o : outs) {
+      for (auto i : ins)
+        if (overlaps(o, out_b, i, in_b)) return CKV_EINVAL;
+      if (plan.workspace_bytes && overlaps(o, out_b, workspace, plan.workspace_bytes)) return CKV_EINVAL;
+    }
+    if (overlaps(K_out, out_b, V_out, out_b)) return CKV_EINVAL;
+    if (plan.workspace_bytes)
+      for (auto i : ins)
+        if (overlaps(workspace, plan.workspace_bytes, i, in_b)) return CKV_EINVAL;
+  }
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int n_bh = in->batch * in->heads;
+  const int e = in->dtype == CKV_BF16 ? 2 : 4;
+  if (plan.n_rounds == 0) {
+    hipError_t err = launch_copy_rows(K, view_of(in), K_out, view_of(out), n_bh, in->seq, in->dim * e, e, s);
+    if (err == hipSuccess)
+      err = launch_copy_rows(V, view_of(in), V_out, view_of(out), n_bh, in->seq, in->dim * e, e, s);
+    if (err == hipSuccess) err = launch_fill_deg(deg_in, deg_out, out->seq, assign, n_bh, in->seq, s);
+    return hip_status(err);
+  }
+
+  const Workspace w = carve(in, &plan, p->chunk);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  int32_t* dst = reinterpret_cast<int32_t*>(ws + w.dst);
+  float* score = reinterpret_cast<float*>(ws + w.score);
+  const void* curK = K;
+  const void* curV = V;
+  const int32_t* curDeg = deg_in;
+  TensorView curView = view_of(in);
+  for (int j = 0; j < plan.n_rounds; ++j) {
+    const int len = plan.round_len[j], next = plan.round_len[j + 1];
+    const bool last = (j == plan.n_rounds - 1);
+    hipError_t err = launch_match(curK, in->dtype, in->dim, curView, n_bh, len, p->chunk, dst, score, s);
+    if (err != hipSuccess) return hip_status(err);
+    void* oK = last ? K_out : ws + w.K[j & 1];
+    void* oV = last ? V_out : ws + w.V[j & 1];
+    int32_t* oDeg = last ? deg_out : reinterpret_cast<int32_t*>(ws + w.deg[j & 1]);
+    const TensorView oView = last ? view_of(out) : compact_view(in->heads, next, in->dim);
+    const int64_t oDegStride = last ? out->seq : next;
+    int32_t* map = nullptr;
+    if (assign) map = (j == 0) ? assign : reinterpret_cast<int32_t*>(ws + w.map);
+    err = launch_merge(curK, curV, curDeg, in->dtype, in->dim, curView, n_bh, len, p->chunk, plan.round_r[j],
+                       dst, score, oK, oV, oDeg, oView, oDegStride, next, map, s);
+    if (err != hipSuccess) return hip_status(err);
+    if (assign && j > 0) {
+      err = launch_compose(assign, map, n_bh, in->seq, len, s);
+      if (err != hipSuccess) return hip_status(err);
+    }
+    curK = oK; curV = oV; curDeg = oDeg; curView = oView;
+  }
+  return CKV_OK;
+}
+
+int ckv_decode_attn_workspace(const ckv_layout* kv, int32_t q_heads, size_t* bytes) {
+  int st = check_layout(kv);
+  if (st != CKV_OK) return st;
+  if (!bytes) return CKV_EINVAL;
+  if (q_heads <= 0 || q_heads % kv->heads) return CKV_ESHAPE;
+  *bytes = align_up(attn_workspace_bytes(kv->batch, kv->heads, q_heads, kv->dim, kv->seq), 256);
+  return CKV_OK;
+}
+
+int ckv_decode_attn(const void* q, int32_t q_heads, const void* K, const void* V, const ckv_layout* kv,
+                    const int32_t* lens, const int32_t* deg, float scale, void* o, int32_t o_dtype,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  size_t need = 0;
+  int st = ckv_decode_attn_workspace(kv, q_heads, &need);
+  if (st != CKV_OK) return st;
+  if (!q || !K || !V || !o || !workspace) return CKV_EINVAL;
+  if (o_dtype != CKV_F32 && o_dtype != CKV_BF16) return CKV_EINVAL;
+  if (((uintptr_t)q) % 16 || ((uintptr_t)K) % 16 || ((uintptr_t)V) % 16 || ((uintptr_t)o) % 4 ||
+      ((uintptr_t)workspace) % 16 || ((uintptr_t)lens) % 4 || ((uintptr_t)deg) % 4)
+    return CKV_EALIGN;
+  if (workspace_bytes < need) return CKV_EWORKSPACE;
+  const int G = q_heads / kv->heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return CKV_EUNSUPPORTED;
+  if (kv->dtype == CKV_BF16 ? !(kv->dim == 64 || kv->dim == 128)
+                            : !(kv->dim == 32 || kv->dim == 64 || kv->dim == 128))
+    return CKV_EUNSUPPORTED;
+  if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)kv->dim);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  return hip_status(launch_decode_attn(q, q_heads, K, V, kv->dtype, kv->dim, view_of(kv), kv->batch, kv->heads,
+                                       kv->seq, lens, deg, scale, o, o_dtype, workspace, s));
+}
+
+int ckv_timing_enable(int on) {
+  if (!on) fold_launches();
+  g_timing = on != 0;
+  return CKV_OK;
+}
+
+int ckv_timing_reset(void) {
+  fold_launches();
+  g_totals.clear();
+  return CKV_OK;
+}
+
+int ckv_timing_read(ckv_kernel_time* out, int max) {
+  fold_launches();
+  int n = 0;
+  for (auto& kv : g_totals) {
+    if (out && n < max) {
+      memset(&out[n], 0, sizeof(out[n]));
+      strncpy(out[n].name, kv.first.c_str(), sizeof(out[n].name) - 1);
+      out[n].total_ms = kv.second.first;
+      out[n].launches = kv.second.second;
+    }
+    ++n;
+  }
+  return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Internal declarations shared by the host driver and the kernel translation units of libckv.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ckv.h"
+
+namespace ckv {
+
+// Strides (in elements) of one [batch*heads] x seq x dim tensor as the kernels see it.
+struct TensorView {
+  int64_t stride_b, stride_h, stride_s;
+  int32_t heads;  // to split a flat (batch*heads) index
+  __host__ __device__ inline int64_t seq_base(int bh) const {
+    return (int64_t)(bh / heads) * stride_b + (int64_t)(bh % heads) * stride_h;
+  }
+};
+
+inline __host__ __device__ int div_up(int a, int b) { return (a + b - 1) / b; }
+
+// Number of A tokens (sources) in a sequence of `seq` tokens cut into chunks of `chunk` (even).
+inline __host__ __device__ int n_sources(int seq, int chunk) {
+  int full = seq / chunk, tail = seq % chunk;
+  return full * (chunk / 2) + (tail + 1) / 2;
+}
+
+// floor(r * n_a + 1e-9) with r widened from float: edges merged in a chunk with n_a sources.
+inline __host__ __device__ int merge_count(float r, int n_a) {
+  return (int)((double)r * (double)n_a + 1e-9);
+}
+
+// Tokens a chunk of L tokens keeps after one round with merge fraction r.
+inline __host__ __device__ int chunk_out(int L, float r) {
+  return (L < 2) ? L : L - merge_count(r, (L + 1) / 2);
+}
+
+// ---- kernel launchers (each returns hipGetLastError() after the launch) ------------------------
+// Similarity + per-source argmax.  dst_local[bh, i] = index within the chunk's B set, score fp32.
+hipError_t launch_match(const void* K, int dtype, int dim, TensorView kv, int n_bh, int seq,
+                        int chunk, int32_t* dst_local, float* score, hipStream_t st);
+
+// Turn chunk-local B indices into sequence positions (for ckv_match's public output).
+hipError_t launch_dst_positions(const int32_t* dst_local, int32_t* dst_pos, int n_bh, int seq,
+                                int chunk, hipStream_t st);
+
+// Per-chunk top-r selection + degree-weighted merge + order-preserving compaction.
+// map_out[bh, t] (t < seq) = output index of the centroid input token t joined; may be NULL.
+hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int dtype, int dim,
+                        TensorView in, int n_bh, int seq, int chunk, float r,
+                        const int32_t* dst_local, const float* score, void* K_out, void* V_out,
+                        int32_t* deg_out, TensorView out, int64_t deg_out_stride, int out_seq,
+                        int32_t* map_out, hipStream_t st);
+
+// assign[bh, t] = map[bh, assign[bh, t]] for t < seq0.
+hipError_t launch_compose(int32_t* assign, const int32_t* map, int n_bh, int seq0, int map_len,
+                          hipStream_t st);
+
+// Plain strided copy of [n_bh, seq, dim] rows (used when the schedule has zero rounds).
+hipError_t launch_copy_rows(const void* src, TensorView in, void* dst, TensorView out, int n_bh,
+                            int seq, int row_bytes, int elem_bytes, hipStream_t st);
+hipError_t launch_fill_deg(const int32_t* deg_in, int32_t* deg_out, int64_t out_stride, int32_t* assign,
+                           int n_bh, int seq, hipStream_t st);
+
+// Decode attention: split-K partials then combine.
+int attn_splits(int n_b, int kv_heads, int seq);
+size_t attn_workspace_bytes(int n_b, int kv_heads, int q_heads, int dim, int seq);
+hipError_t launch_decode_attn(const void* q, int q_heads, const void* K, const void* V, int dtype,
+                              int dim, TensorView kv, int n_b, int kv_heads, int seq,
+                              const int32_t* lens, const int32_t* deg, float scale, void* o,
+                              int o_dtype, void* workspace, hipStream_t st);
+
+// ---- timing hooks ----------------------------------------------------------------------------
+void timing_begin(const char* name, hipStream_t st);
+void timing_end(hipStream_t st);
+struct ScopedTimer {
+  hipStream_t st;
+  ScopedTimer(const char* name, hipStream_t s) : st(s) { timing_begin(name, s); }
+  ~ScopedTimer() { timing_end(st); }
+};
+
+}  // namespace ckv

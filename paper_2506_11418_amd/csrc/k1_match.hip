@@ -1,0 +1,358 @@
+// Similarity + matching stage of Chunked Soft Matching (Sec. 5.2, Eq. 2) for gfx950.
+//
+// Per chunk of L tokens: A = tokens at even offsets (sources), B = odd offsets (destinations).
+// For every A token i:  j*(i) = argmax_j  k_i.k_j / (|k_i||k_j|)  (lowest j on ties) and that
+// maximum.  The |A| x |B| similarity matrix lives only in MFMA accumulators.
+//
+// bf16 kernel: one workgroup = (sequence, chunk, block of 256 A rows); 4 waves x 64 A rows.  The
+// A rows are staged once through LDS into registers in MFMA operand order; the chunk's B rows
+// stream through two LDS panels of 128 rows (global -> registers -> LDS, one barrier per panel).
+// Inverse norms come from the same staged bytes (v_dot2 on the packed pairs).  The MFMA computes
+// S^T (B index on the M side) so that a lane's 16 accumulators of a 32x32 tile all belong to ONE
+// A row: the running maximum costs one multiply (by 1/|k_j|) and half a max3 per element, and the
+// exact index is only resolved for tiles that raise some lane's maximum.
+#include "ckv_internal.h"
+
+namespace ckv {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kRowsPerWave = 64;                 // two 32-row MFMA tiles
+constexpr int kABlock = kWaves * kRowsPerWave;   // A rows per workgroup
+constexpr int kPanel = 128;                      // B rows per LDS panel
+
+union Piece {   // 16 bytes = 8 bf16
+  uint4 u;
+  bf16x8 v;
+  bf16x2 p[4];
+};
+
+__device__ inline float sumsq8(const Piece& x) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_fdot2_f32_bf16(x.p[i], x.p[i], s, false);
+  return s;
+}
+
+__device__ inline float inv_norm(float ss) { return ss > 0.f ? 1.0f / sqrtf(ss) : 0.f; }
+
+// Map dispatch order to logical work so that the 8 XCDs (which receive consecutive workgroup ids
+// round-robin) each walk a contiguous range: neighbours in the range (the A blocks of one chunk,
+// adjacent chunks) then share an L2.
+__device__ inline int xcd_remap(int id, int per_xcd) { return (id & 7) * per_xcd + (id >> 3); }
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
+    const __bf16* __restrict__ K, TensorView kv, int seq, int chunk, int n_chunks, int a_blocks,
+    int total_work, int per_xcd, int32_t* __restrict__ dst_local, float* __restrict__ score) {
+  constexpr int OCT = D / 8;                       // 16-byte pieces per key row
+  constexpr int ROWB = D * 2;                      // bytes per row
+  constexpr int KEYSHIFT = (ROWB == 256) ? 0 : 1;  // rows per 256 B of LDS = 1 << KEYSHIFT
+  constexpr int KSTEPS = D / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* panel0 = smem;                                // 2 panels of kPanel rows; the A
+  float* invb = reinterpret_cast<float*>(smem + 2 * kPanel * ROWB);  // block is staged over both
+  float* inva = invb + 2 * kPanel;
+
+  const int w = xcd_remap(blockIdx.x, per_xcd);
+  if (w >= total_work) return;
+  const int ab = w % a_blocks;
+  const int g = (w / a_blocks) % n_chunks;
+  const int bh = w / (a_blocks * n_chunks);
+  const int g0 = g * chunk;
+  const int L = min(chunk, seq - g0);
+  const int nA = (L + 1) >> 1, nB = L >> 1;
+  const int a0 = ab * kABlock;
+  if (a0 >= nA) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_src = n_sources(seq, chunk);
+  const int64_t out_base = (int64_t)bh * n_src + (int64_t)g * (chunk >> 1);
+  if (nB == 0) {  // a one-token tail chunk: nothing to match
+    if (tid == 0) { dst_local[out_base] = -1; score[out_base] = 0.f; }
+    return;
+  }
+  const __bf16* Kseq = K + kv.seq_base(bh) + (int64_t)g0 * kv.stride_s;
+
+  auto swz = [](int row, int piece) -> int {
+    return row * ROWB + (((piece ^ (row >> KEYSHIFT)) & (OCT - 1)) << 4);
+  };
+
+  // ---- stage the A block (even offsets) and its inverse norms --------------------------------
+  {
+    constexpr int ROWS_PER_PASS = kThreads / OCT;
+    const int piece = tid % OCT, r0 = tid / OCT;
+#pragma unroll 4
+    for (int row = r0; row < kABlock; row += ROWS_PER_PASS) {
+      Piece x;
+      x.u = make_uint4(0, 0, 0, 0);
+      const int a = a0 + row;
+      if (a < nA) x.u = *reinterpret_cast<const uint4*>(Kseq + (int64_t)(2 * a) * kv.stride_s + piece * 8);
+      float ss = sumsq8(x);
+#pragma unroll
+      for (int m = 1; m < OCT; m <<= 1) ss += __shfl_xor(ss, m);
+      *reinterpret_cast<uint4*>(panel0 + swz(row, piece)) = x.u;
+      if (piece == 0) inva[row] = inv_norm(ss);
+    }
+  }
+  __syncthreads();
+  bf16x8 afrag[2][KSTEPS];
+  const int half = lane >> 5, col = lane & 31;
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    const int row = wave * kRowsPerWave + rt * 32 + col;
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s)
+      afrag[rt][s] = *reinterpret_cast<const bf16x8*>(panel0 + swz(row, 2 * s + half));
+  }
+  const float my_inva0 = inva[wave * kRowsPerWave + col];
+  const float my_inva1 = inva[wave * kRowsPerWave + 32 + col];
+  __syncthreads();
+
+  // ---- stream B panels -----------------------------------------------------------------------
+  constexpr int PIECES = kPanel * OCT / kThreads;   // 16-byte pieces per thread per panel
+  Piece stage[PIECES];
+  auto load_panel = [&](int pbase) {
+#pragma unroll
+    for (int it = 0; it < PIECES; ++it) {
+      const int q = tid + it * kThreads, row = q / OCT, piece = q % OCT, j = pbase + row;
+      stage[it].u = make_uint4(0, 0, 0, 0);
+      if (j < nB)
+        stage[it].u = *reinterpret_cast<const uint4*>(Kseq + (int64_t)(2 * j + 1) * kv.stride_s + piece * 8);
+    }
+  };
+  auto store_panel = [&](int buf) {
+    unsigned char* pb = panel0 + buf * kPanel * ROWB;
+#pragma unroll
+    for (int it = 0; it < PIECES; ++it) {
+      const int q = tid + it * kThreads, row = q / OCT, piece = q % OCT;
+      float ss = sumsq8(stage[it]);
+#pragma unroll
+      for (int m = 1; m < OCT; m <<= 1) ss += __shfl_xor(ss, m);
+      *reinterpret_cast<uint4*>(pb + swz(row, piece)) = stage[it].u;
+      if (piece == 0) invb[buf * kPanel + row] = inv_norm(ss);
+    }
+  };
+
+  float best[2] = {-INFINITY, -INFINITY};
+  int bestj[2] = {0, 0};
+  const bool wave_active = (a0 + wave * kRowsPerWave) < nA;
+  const int n_panels = div_up(nB, kPanel);
+  load_panel(0);
+  store_panel(0);
+  for (int p = 0; p < n_panels; ++p) {
+    const int buf = p & 1, pbase = p * kPanel;
+    if (p + 1 < n_panels) load_panel(pbase + kPanel);
+    __syncthreads();
+    if (wave_active) {
+      const unsigned char* pb = panel0 + buf * kPanel * ROWB;
+      const int rows_here = min(kPanel, nB - pbase);
+      const int n_ct = div_up(rows_here, 32);
+      for (int ct = 0; ct < n_ct; ++ct) {
+        f32x16 acc0 = {0}, acc1 = {0};
+        const int brow = ct * 32 + col;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+          const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(pb + swz(brow, 2 * s + half));
+          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, afrag[0][s], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, afrag[1][s], acc1, 0, 0, 0);
+        }
+        // accumulator r of this lane: B row 8*(r/4) + 4*half + r%4 of the tile, A row = col
+        f32x4 ib[4];
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd)
+          ib[qd] = *reinterpret_cast<const f32x4*>(&invb[buf * kPanel + ct * 32 + 8 * qd + 4 * half]);
+        const bool ragged = (ct * 32 + 32) > rows_here;
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+          const f32x16& acc = rt ? acc1 : acc0;
+          float sc[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sc[r] = acc[r] * ib[r >> 2][r & 3];
+          if (ragged) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if (ct * 32 + 8 * (r >> 2) + 4 * half + (r & 3) >= rows_here) sc[r] = -INFINITY;
+          }
+          float mt = fmaxf(sc[0], sc[1]);
+#pragma unroll
+          for (int r = 2; r < 16; r += 2) mt = fmaxf(mt, fmaxf(sc[r], sc[r + 1]));
+          const bool upd = mt > best[rt];
+          if (__any(upd)) {
+            int idx = 0;
+#pragma unroll
+            for (int r = 15; r >= 0; --r) idx = (sc[r] == mt) ? r : idx;
+            const int j = pbase + ct * 32 + ((idx >> 2) << 3) + (half << 2) + (idx & 3);
+            best[rt] = upd ? mt : best[rt];
+            bestj[rt] = upd ? j : bestj[rt];
+          }
+        }
+      }
+    }
+    if (p + 1 < n_panels) store_panel(buf ^ 1);
+  }
+
+  // ---- merge the two lane halves of every A row and write ------------------------------------
+  if (wave_active) {
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      const float ob = __shfl_xor(best[rt], 32);
+      const int oj = __shfl_xor(bestj[rt], 32);
+      float b = best[rt];
+      int j = bestj[rt];
+      if (ob > b || (ob == b && oj < j)) { b = ob; j = oj; }
+      const int a = a0 + wave * kRowsPerWave + rt * 32 + col;
+      if (half == 0 && a < nA) {
+        dst_local[out_base + a] = j;
+        score[out_base + a] = b * (rt ? my_inva1 : my_inva0);
+      }
+    }
+  }
+}
+
+// ---- fp32 keys: plain FMA, LDS tiles; a correctness path, not a roofline one -------------------
+constexpr int kF32ARows = 64, kF32BRows = 32, kF32MaxD = 128;
+
+__global__ __launch_bounds__(kThreads) void match_f32_kernel(
+    const float* __restrict__ K, TensorView kv, int dim, int seq, int chunk, int n_chunks,
+    int a_blocks, int32_t* __restrict__ dst_local, float* __restrict__ score) {
+  __shared__ float As[kF32ARows][kF32MaxD + 1];
+  __shared__ float Bs[kF32BRows][kF32MaxD + 1];
+  __shared__ float inva[kF32ARows], invb[kF32BRows];
+  const int w = blockIdx.x;
+  const int ab = w % a_blocks, g = (w / a_blocks) % n_chunks, bh = w / (a_blocks * n_chunks);
+  const int g0 = g * chunk, L = min(chunk, seq - g0);
+  const int nA = (L + 1) >> 1, nB = L >> 1, a0 = ab * kF32ARows;
+  if (a0 >= nA) return;
+  const int tid = threadIdx.x;
+  const int n_src = n_sources(seq, chunk);
+  const int64_t out_base = (int64_t)bh * n_src + (int64_t)g * (chunk >> 1);
+  if (nB == 0) {
+    if (tid == 0) { dst_local[out_base] = -1; score[out_base] = 0.f; }
+    return;
+  }
+  const float* Kseq = K + kv.seq_base(bh) + (int64_t)g0 * kv.stride_s;
+  for (int e = tid; e < kF32ARows * dim; e += kThreads) {
+    const int row = e / dim, k = e % dim, a = a0 + row;
+    As[row][k] = (a < nA) ? Kseq[(int64_t)(2 * a) * kv.stride_s + k] : 0.f;
+  }
+  __syncthreads();
+  if (tid < kF32ARows) {
+    float ss = 0.f;
+    for (int k = 0; k < dim; ++k) ss = fmaf(As[tid][k], As[tid][k], ss);
+    inva[tid] = inv_norm(ss);
+  }
+  const int r = tid >> 2, q = tid & 3;
+  float best = -INFINITY;
+  int bestj = 0;
+  for (int pbase = 0; pbase < nB; pbase += kF32BRows) {
+    __syncthreads();
+    for (int e = tid; e < kF32BRows * dim; e += kThreads) {
+      const int row = e / dim, k = e % dim, j = pbase + row;
+      Bs[row][k] = (j < nB) ? Kseq[(int64_t)(2 * j + 1) * kv.stride_s + k] : 0.f;
+    }
+    __syncthreads();
+    if (tid < kF32BRows) {
+      float ss = 0.f;
+      for (int k = 0; k < dim; ++k) ss = fmaf(Bs[tid][k], Bs[tid][k], ss);
+      invb[tid] = inv_norm(ss);
+    }
+    __syncthreads();
+    float acc[kF32BRows / 4];
+#pragma unroll
+    for (int m = 0; m < kF32BRows / 4; ++m) acc[m] = 0.f;
+    for (int k = 0; k < dim; ++k) {
+      const float a = As[r][k];
+#pragma unroll
+      for (int m = 0; m < kF32BRows / 4; ++m) acc[m] = fmaf(a, Bs[q + 4 * m][k], acc[m]);
+    }
+#pragma unroll
+    for (int m = 0; m < kF32BRows / 4; ++m) {
+      const int jl = q + 4 * m, j = pbase + jl;
+      const float s = acc[m] * invb[jl];
+      if (j < nB && s > best) { best = s; bestj = j; }
+    }
+  }
+#pragma unroll
+  for (int m = 1; m < 4; m <<= 1) {
+    const float ob = __shfl_xor(best, m);
+    const int oj = __shfl_xor(bestj, m);
+    if (ob > best || (ob == best && oj < bestj)) { best = ob; bestj = oj; }
+  }
+  const int a = a0 + r;
+  if (q == 0 && a < nA) {
+    dst_local[out_base + a] = bestj;
+    score[out_base + a] = best * inva[r];
+  }
+}
+
+__global__ void dst_positions_kernel(const int32_t* __restrict__ dst_local, int32_t* __restrict__ dst_pos,
+                                     int n_src, int chunk, int64_t total) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= total) return;
+  const int i = (int)(e % n_src);
+  const int g = i / (chunk >> 1);
+  const int j = dst_local[e];
+  dst_pos[e] = (j < 0) ? -1 : g * chunk + 2 * j + 1;
+}
+
+template <int D>
+hipError_t launch_match_bf16(const void* K, TensorView kv, int n_bh, int seq, int chunk,
+                             int32_t* dst_local, float* score, hipStream_t st) {
+  constexpr size_t lds = 2 * kPanel * D * 2 + (2 * kPanel + kABlock) * sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&match_bf16_kernel<D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int n_chunks = div_up(seq, chunk);
+  const int a_blocks = div_up(chunk / 2, kABlock);
+  const int64_t total = (int64_t)n_bh * n_chunks * a_blocks;
+  if (total > (1 << 30)) return hipErrorInvalidValue;
+  const int per_xcd = div_up((int)total, 8);
+  ScopedTimer t("match_bf16", st);
+  hipLaunchKernelGGL(match_bf16_kernel<D>, dim3(per_xcd * 8), dim3(kThreads), lds, st,
+                     static_cast<const __bf16*>(K), kv, seq, chunk, n_chunks, a_blocks, (int)total,
+                     per_xcd, dst_local, score);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_match(const void* K, int dtype, int dim, TensorView kv, int n_bh, int seq,
+                        int chunk, int32_t* dst_local, float* score, hipStream_t st) {
+  if (dtype == CKV_BF16) {
+    if (dim == 128) return launch_match_bf16<128>(K, kv, n_bh, seq, chunk, dst_local, score, st);
+    if (dim == 64) return launch_match_bf16<64>(K, kv, n_bh, seq, chunk, dst_local, score, st);
+    return hipErrorInvalidValue;
+  }
+  if (dim > kF32MaxD) return hipErrorInvalidValue;
+  const int n_chunks = div_up(seq, chunk);
+  const int a_blocks = div_up(chunk / 2, kF32ARows);
+  const int64_t total = (int64_t)n_bh * n_chunks * a_blocks;
+  if (total > (1 << 30)) return hipErrorInvalidValue;
+  ScopedTimer t("match_f32", st);
+  hipLaunchKernelGGL(match_f32_kernel, dim3((int)total), dim3(kThreads), 0, st,
+                     static_cast<const float*>(K), kv, dim, seq, chunk, n_chunks, a_blocks, dst_local,
+                     score);
+  return hipGetLastError();
+}
+
+hipError_t launch_dst_positions(const int32_t* dst_local, int32_t* dst_pos, int n_bh, int seq,
+                                int chunk, hipStream_t st) {
+  const int n_src = n_sources(seq, chunk);
+  const int64_t total = (int64_t)n_bh * n_src;
+  ScopedTimer t("dst_positions", st);
+  hipLaunchKernelGGL(dst_positions_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     dst_local, dst_pos, n_src, chunk, total);
+  return hipGetLastError();
+}
+
+}  // namespace ckv

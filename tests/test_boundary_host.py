@@ -1,0 +1,109 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/ckv.h declares, and its
+host-side logic (schedule, lengths, argument validation) agrees with the oracle's integer math.
+No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2506_11418_amd as ckv
+from oracle import direct_schedule, round_lengths
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _lay(batch=1, heads=2, seq=4096, dim=128, dtype=ckv.BF16):
+    return ckv.Layout(batch, heads, seq, dim, heads * seq * dim, seq * dim, dim, dtype)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ckv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(ckv_[a-z_]+)\s*\(", header))
+    assert {"ckv_plan", "ckv_match", "ckv_compress", "ckv_decode_attn", "ckv_decode_attn_workspace",
+            "ckv_version", "ckv_strerror"} <= names
+    L = ckv.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert "gfx950" in ckv.version()
+    assert L.ckv_strerror(-4).decode() == "workspace too small"
+
+
+@pytest.mark.parametrize("rho", [1.0, 0.75, 0.5, 0.375, 0.3, 0.25, 0.125, 0.1])
+@pytest.mark.parametrize("seq,chunk", [(32768, 1024), (4096, 256), (1000, 64), (77, 16), (1, 2), (2049, 2048)])
+def test_plan_matches_oracle_schedule_and_lengths(rho, seq, chunk):
+    pl = ckv.plan(_lay(seq=seq), ckv.make_params(chunk, rho))
+    sched = direct_schedule(rho)
+    assert len(pl.round_r) == len(sched)
+    for a, b in zip(pl.round_r, sched):
+        assert abs(a - b) < 1e-6
+    assert pl.round_len == round_lengths(seq, chunk, pl.round_r)
+    assert pl.out_seq == pl.round_len[-1]
+
+
+@pytest.mark.parametrize("rounds", [[1.0], [0.5], [0.8, 0.6, 0.4], [1.0, 1.0, 0.3], [0.0]])
+def test_plan_explicit_rounds(rounds):
+    for seq, chunk in [(5000, 256), (333, 32), (8192, 2048)]:
+        pl = ckv.plan(_lay(seq=seq), ckv.make_params(chunk, rounds=rounds))
+        assert pl.round_len == round_lengths(seq, chunk, rounds)
+
+
+def test_plan_workspace_grows_with_rounds():
+    one = ckv.plan(_lay(), ckv.make_params(1024, 0.5)).workspace_bytes
+    two = ckv.plan(_lay(), ckv.make_params(1024, 0.25)).workspace_bytes
+    assert 0 < one < two
+    # two rounds keep one intermediate cache: K, V (bf16) and degrees for 2 heads x 2048 tokens
+    assert two - one >= 2 * 2048 * (2 * 128 * 2 + 4)
+
+
+def test_plan_rejects_bad_arguments():
+    L = ckv.lib()
+    pt = ckv.PlanT()
+
+    def st(lay, p):
+        return L.ckv_plan(C.byref(lay), C.byref(p), C.byref(pt))
+
+    ok = ckv.make_params(256, 0.5)
+    assert st(_lay(), ok) == 0
+    assert st(_lay(), ckv.make_params(255, 0.5)) == -1          # odd chunk
+    assert st(_lay(), ckv.make_params(0, 0.5)) == -1
+    assert st(_lay(), ckv.make_params(4096, 0.5)) == -1         # chunk > 2048
+    assert st(_lay(), ckv.make_params(256, 0.0)) == -1          # ratio outside (0,1]
+    assert st(_lay(), ckv.make_params(256, 1.5)) == -1
+    assert st(_lay(), ckv.make_params(256, rounds=[1.2])) == -1
+    assert st(_lay(seq=0), ok) == -2
+    assert st(_lay(dtype=7), ok) == -1
+    bad = _lay()
+    bad.stride_s = 100                                          # smaller than dim
+    assert st(bad, ok) == -2
+    odd = _lay()
+    odd.stride_s = 132                                          # 264 bytes: not a multiple of 16
+    assert st(odd, ok) == -3
+    sink = ckv.make_params(256, 0.5)
+    sink.n_sink = 16
+    assert st(_lay(), sink) == -5
+    assert L.ckv_plan(None, C.byref(ok), C.byref(pt)) == -1
+
+
+def test_entry_points_reject_null_and_misaligned_pointers_before_any_launch():
+    L = ckv.lib()
+    lay, p = _lay(), ckv.make_params(256, 0.5)
+    z = C.c_void_p(0)
+    assert L.ckv_compress(z, z, z, C.byref(lay), C.byref(p), z, z, z, C.byref(lay), z, z, 0, z) == -1
+    short = _lay(seq=100)                                       # output shorter than the plan's length
+    a = C.c_void_p(4096)
+    assert L.ckv_compress(a, a, z, C.byref(lay), C.byref(p), a, a, a, C.byref(short), z, a, 1 << 30, z) == -2
+    assert L.ckv_compress(a, a, z, C.byref(lay), C.byref(p), a, a, a, C.byref(lay), z, a, 1 << 30, z) == -1  # overlap
+    big = C.c_void_p(1 << 40)
+    far = C.c_void_p(1 << 41)
+    ws = C.c_void_p(1 << 42)
+    assert L.ckv_compress(a, big, z, C.byref(lay), C.byref(p), far, C.c_void_p((1 << 41) + (1 << 30)), ws,
+                          C.byref(lay), z, C.c_void_p(1 << 43), 16, z) == -4             # workspace too small
+    n = C.c_size_t(0)
+    assert L.ckv_decode_attn_workspace(C.byref(lay), 8, C.byref(n)) == 0 and n.value > 0
+    assert L.ckv_decode_attn_workspace(C.byref(lay), 3, C.byref(n)) == -2        # 3 % 2 heads
+    assert L.ckv_decode_attn(z, 8, z, z, C.byref(lay), z, z, 0.0, z, 1, z, 0, z) == -1
+    assert L.ckv_match(z, C.byref(lay), 256, z, z, z) == -1
+    assert L.ckv_match(C.c_void_p(8), C.byref(lay), 256, C.c_void_p(16), C.c_void_p(16), z) == -3
+    assert L.ckv_match(C.c_void_p(16), C.byref(lay), 251, C.c_void_p(16), C.c_void_p(16), z) == -1   # odd chunk

@@ -1,0 +1,215 @@
+"""GPU parity: ckv_match / ckv_compress (HIP, through the C ABI) vs the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_11418_amd as ckv
+from parity_util import DT, check_match, check_round, f64, i64
+from synth import kv_host
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _run_rounds_teacher_forced(K, V, chunk, rounds, what, deg=None):
+    """Each round: GPU consumes the GPU's previous output; the oracle is fed the same input."""
+    dtype = DT[K.dtype]
+    curK, curV, curdeg = K, V, deg
+    alt = 0
+    for j, r in enumerate(rounds):
+        gK, gV, gdeg, gas = ckv.compress(curK, curV, chunk, rounds=[r], deg=curdeg)
+        torch.cuda.synchronize()
+        B, H = curK.shape[:2]
+        for b in range(B):
+            for h in range(H):
+                d_in = np.ones(curK.shape[2], dtype=np.int64) if curdeg is None else i64(curdeg[b, h])
+                alt += check_round(f64(curK[b, h]), f64(curV[b, h]), d_in, chunk, r, dtype,
+                                   f64(gK[b, h]), f64(gV[b, h]), i64(gdeg[b, h]), i64(gas[b, h]),
+                                   what=f"{what} round {j} (b{b},h{h})")
+        curK, curV, curdeg = gK, gV, gdeg
+    return curK, curV, curdeg, alt
+
+
+# ---- config 1: 1 x 1 x 1024 x 64 fp32, chunk 64 ---------------------------------------------
+def _config1():
+    K, V, rng = kv_host(0, 1, 1024, 64, "f32", alpha=0.9, single_stream=True)
+    return K.to(DEV), V.to(DEV), rng
+
+
+def test_match_config1_fp32():
+    _say("match config1")
+    K, V, _ = _config1()
+    dst, score = ckv.match(K, 64)
+    torch.cuda.synchronize()
+    n = check_match(f64(K[0, 0]), 64, i64(dst[0, 0]), f64(score[0, 0]), "config1")
+    assert n == 0
+
+
+@pytest.mark.parametrize("rho,chunk", [(0.5, 64), (0.75, 64), (0.25, 64), (0.5, 8), (0.375, 16), (1.0, 64)])
+def test_compress_config1_fp32(rho, chunk):
+    _say(f"compress config1 rho={rho} chunk={chunk}")
+    K, V, _ = _config1()
+    pl = ckv.plan(ckv.layout_of(K), ckv.make_params(chunk, rho))
+    fK, fV, fdeg, alt = _run_rounds_teacher_forced(K, V, chunk, pl.round_r, f"config1 rho={rho}")
+    assert alt == 0
+    # the one-call multi-round path gives the same bits as the chained single rounds
+    gK, gV, gdeg, gas = ckv.compress(K, V, chunk, retain_ratio=rho)
+    torch.cuda.synchronize()
+    assert gK.shape[2] == pl.out_seq == int(round(rho * 1024))
+    if pl.round_r:
+        assert torch.equal(gK, fK) and torch.equal(gV, fV) and torch.equal(gdeg, fdeg)
+    # and matches the oracle end to end (no near-ties on this input)
+    ref = oracle.compress(f64(K[0, 0]), f64(V[0, 0]), chunk, pl.round_r, "f32")
+    assert np.array_equal(i64(gas[0, 0]), ref["assign"])
+    assert np.array_equal(i64(gdeg[0, 0]), ref["deg"])
+    assert np.allclose(f64(gK[0, 0]), ref["K"], rtol=1e-5, atol=1e-6)
+    assert np.array_equal(np.bincount(i64(gas[0, 0]), minlength=pl.out_seq), i64(gdeg[0, 0]))
+
+
+# ---- bf16, several tiles, ragged tails ------------------------------------------------------
+@pytest.mark.parametrize("heads,seq,dim,chunk", [
+    (2, 4096, 128, 1024),      # two A blocks per chunk
+    (2, 3000, 128, 1024),      # tail chunk of 952 tokens
+    (1, 2047, 128, 256),       # odd tail
+    (1, 5000, 128, 2048),      # largest chunk, ragged
+    (2, 1536, 64, 512),        # head_dim 64
+    (3, 700, 128, 64),         # small chunks
+    (1, 130, 128, 2),          # smallest chunk
+    (1, 1, 128, 16),           # single token
+])
+def test_match_bf16_shapes(heads, seq, dim, chunk):
+    _say(f"match bf16 H={heads} S={seq} D={dim} c={chunk}")
+    K, _, _ = kv_host(11, heads, seq, dim, "bf16", alpha=0.9, n_outlier=4 if dim == 128 else 0)
+    K = K.to(DEV)
+    dst, score = ckv.match(K, chunk)
+    torch.cuda.synchronize()
+    for h in range(heads):
+        check_match(f64(K[0, h]), chunk, i64(dst[0, h]), f64(score[0, h]), f"h{h}")
+
+
+@pytest.mark.parametrize("heads,seq,dim,chunk,rounds", [
+    (2, 4096, 128, 1024, [1.0, 1.0]),
+    (2, 3000, 128, 1024, [1.0, 0.5]),
+    (1, 2047, 128, 256, [0.8, 0.6]),
+    (1, 5000, 128, 2048, [0.3]),
+    (2, 1536, 64, 512, [1.0]),
+    (3, 700, 128, 64, [0.75, 0.75, 0.75]),
+    (1, 130, 128, 2, [1.0]),
+    (1, 1, 128, 16, [1.0]),
+    (1, 9, 128, 8, [1.0]),
+])
+def test_compress_bf16_shapes(heads, seq, dim, chunk, rounds):
+    _say(f"compress bf16 H={heads} S={seq} D={dim} c={chunk} rounds={rounds}")
+    K, V, _ = kv_host(12, heads, seq, dim, "bf16", alpha=0.9, n_outlier=4 if dim == 128 else 0)
+    K, V = K.to(DEV), V.to(DEV)
+    fK, fV, fdeg, _ = _run_rounds_teacher_forced(K, V, chunk, rounds, "bf16 shapes")
+    gK, gV, gdeg, gas = ckv.compress(K, V, chunk, rounds=rounds)
+    torch.cuda.synchronize()
+    assert torch.equal(gK, fK) and torch.equal(gV, fV) and torch.equal(gdeg, fdeg)
+    for h in range(heads):
+        a = i64(gas[0, h])
+        assert np.array_equal(np.bincount(a, minlength=gK.shape[2]), i64(gdeg[0, h]))
+
+
+def test_compress_config2_llama_layer_bf16():
+    """8 KV heads x 32768 x 128 bf16, chunk 1024, retain 25% (rounds [1, 1])."""
+    _say("compress config2")
+    K, V, _ = kv_host(2, 8, 32768, 128, "bf16", alpha=0.9, n_outlier=4)
+    K, V = K.to(DEV), V.to(DEV)
+    pl = ckv.plan(ckv.layout_of(K), ckv.make_params(1024, 0.25))
+    assert pl.round_r == [1.0, 1.0] and pl.out_seq == 8192
+    fK, fV, fdeg, alt = _run_rounds_teacher_forced(K, V, 1024, pl.round_r, "config2")
+    _say(f"config2: {alt} near-tie rows resolved differently")
+    gK, gV, gdeg, gas = ckv.compress(K, V, 1024, retain_ratio=0.25)
+    torch.cuda.synchronize()
+    assert torch.equal(gK, fK) and torch.equal(gV, fV) and torch.equal(gdeg, fdeg)
+    assert int(gdeg.sum()) == 8 * 32768
+
+
+# ---- layouts, degrees, degenerate inputs ------------------------------------------------------
+def test_bshd_layout_and_padded_output():
+    _say("compress strided layout")
+    K, V, _ = kv_host(13, 2, 1024, 128, "bf16", n_outlier=4)
+    # store as [B, S, H, D] and view as [B, H, S, D]
+    Kb = K.permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+    Vb = V.permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+    ref = ckv.compress(K.to(DEV), V.to(DEV), 256, rounds=[0.5])
+    K_out = torch.zeros((1, 800, 2, 128), dtype=torch.bfloat16, device=DEV).permute(0, 2, 1, 3)   # room to spare
+    V_out = torch.zeros_like(K_out)
+    deg_out = torch.zeros((1, 2, 800), dtype=torch.int32, device=DEV)
+    got = ckv.compress(Kb, Vb, 256, rounds=[0.5], out=(K_out, V_out, deg_out, None))
+    torch.cuda.synchronize()
+    n = ref[0].shape[2]
+    assert n == 768
+    assert torch.equal(got[0][:, :, :n], ref[0]) and torch.equal(got[1][:, :, :n], ref[1])
+    assert torch.equal(deg_out[:, :, :n], ref[2])
+    assert float(K_out[:, :, n:].abs().sum()) == 0.0            # rows beyond out_seq untouched
+
+
+def test_incoming_degrees_weight_the_merge():
+    _say("compress with deg_in")
+    K, V, _ = kv_host(14, 1, 512, 128, "bf16", n_outlier=4)
+    K, V = K.to(DEV), V.to(DEV)
+    deg = torch.from_numpy(np.random.default_rng(0).integers(1, 9, (1, 1, 512)).astype(np.int32)).to(DEV)
+    _run_rounds_teacher_forced(K, V, 128, [0.75, 0.5], "deg_in", deg=deg)
+
+
+def test_duplicate_keys_merge_losslessly_on_gpu():
+    _say("compress duplicate keys")
+    k = torch.randn(128, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16)
+    K = k.repeat(1, 1, 512, 1).contiguous().to(DEV)
+    V = torch.randn((1, 1, 512, 128), generator=torch.Generator().manual_seed(4)).to(torch.bfloat16).to(DEV)
+    gK, gV, gdeg, gas = ckv.compress(K, V, 256, rounds=[1.0])
+    torch.cuda.synchronize()
+    assert torch.equal(gK, k.to(DEV).expand_as(gK))             # every centroid key == the key
+    # exact ties: all 128 sources of a chunk join the chunk's first B token
+    assert i64(gdeg[0, 0]).tolist() == ([129] + [1] * 127) * 2
+    ref = oracle.csm_round(f64(K[0, 0]), f64(V[0, 0]), np.ones(512, dtype=np.int64), 256, 1.0, "bf16")
+    assert np.array_equal(i64(gas[0, 0]), ref["assign"])
+    assert np.array_equal(f64(gV[0, 0]), ref["V"])
+
+
+def test_zero_rounds_and_r_zero_are_identity():
+    _say("compress identity")
+    K, V, _ = kv_host(15, 2, 300, 64, "bf16")
+    K, V = K.to(DEV), V.to(DEV)
+    for kw in (dict(retain_ratio=1.0), dict(rounds=[0.0])):
+        gK, gV, gdeg, gas = ckv.compress(K, V, 64, **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(gK, K) and torch.equal(gV, V)
+        assert bool((gdeg == 1).all())
+        assert torch.equal(gas, torch.arange(300, dtype=torch.int32, device=DEV).expand(1, 2, 300))
+
+
+def test_zero_keys_and_run_to_run_determinism():
+    _say("compress zero keys / determinism")
+    K, V, _ = kv_host(16, 2, 2048, 128, "bf16", n_outlier=4)
+    K[0, 0, 100:140] = 0                                        # zero-norm keys: similarity 0
+    K, V = K.to(DEV), V.to(DEV)
+    _run_rounds_teacher_forced(K, V, 512, [0.6], "zero keys")
+    a = ckv.compress(K, V, 512, retain_ratio=0.25)
+    b = ckv.compress(K, V, 512, retain_ratio=0.25)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_runtime_argument_errors():
+    _say("compress argument errors")
+    K, V, _ = kv_host(17, 1, 256, 128, "bf16")
+    K, V = K.to(DEV), V.to(DEV)
+    with pytest.raises(ckv.CkvError) as e:
+        ckv.compress(K, V, 64, rounds=[1.0], workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert e.value.status == -4
+    with pytest.raises(ckv.CkvError) as e:
+        ckv.compress(K, K, 64, rounds=[1.0], out=(K, V, torch.empty((1, 1, 256), dtype=torch.int32, device=DEV), None))
+    assert e.value.status == -1                                  # output overlaps input
+    K96 = torch.zeros((1, 1, 64, 96), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(ckv.CkvError) as e:
+        ckv.compress(K96, K96.clone(), 16, rounds=[1.0])
+    assert e.value.status == -5                                  # head_dim without a kernel
