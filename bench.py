@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config3", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage", default="all", choices=["all", "match", "compress", "decode"],
+                    help="time only one stage of the path (kernel tuning / profiling); the JSON line is "
+                         "the full contract only for 'all'")
     ap.add_argument("--seed", type=int, default=2024)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -113,12 +116,17 @@ def main():
         K, V = sets[i % n_sets]
         if timed:
             ev[3 * i].record()
-        ckv.compress(K, V, cfg["chunk"], retain_ratio=cfg["retain"], out=(K_out, V_out, deg_out, assign),
-                     workspace=ws)
+        if args.stage == "match":
+            ckv.match(K, cfg["chunk"])
+        elif args.stage != "decode" or i == 0:
+            ckv.compress(K, V, cfg["chunk"], retain_ratio=cfg["retain"], out=(K_out, V_out, deg_out, assign),
+                         workspace=ws)
         if timed:
             ev[3 * i + 1].record()
-        for l in range(Ly):
-            ckv.decode_attn(q[l], K_out[l:l + 1], V_out[l:l + 1], deg=deg_out[l:l + 1], out=o[l], workspace=attn_ws)
+        if args.stage in ("all", "decode"):
+            for l in range(Ly):
+                ckv.decode_attn(q[l], K_out[l:l + 1], V_out[l:l + 1], deg=deg_out[l:l + 1], out=o[l],
+                                workspace=attn_ws)
         if timed:
             ev[3 * i + 2].record()
 
@@ -155,6 +163,10 @@ def main():
             ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                        frac=round(ach / PEAK_HBM_GBS, 4))
         kernels[name] = ent
+    if args.stage == "match":      # ckv_match runs the first round only
+        one = algorithmic_work(cfg, type(plan)(plan.round_len[1], plan.round_len[:2], plan.round_r[:1], 0))
+        ach = one["match_bf16"] / (kernels["match_bf16"]["ms_per_step"] * 1e-3) / 1e12
+        kernels["match_bf16"].update(achieved=round(ach, 1), frac=round(ach / PEAK_BF16_TFLOPS, 4))
     hot = [k for k in kernels if k in work]
     dom = max(hot, key=lambda k: kernels[k]["ms_per_step"])
     roofline = {"kernel": dom, **{k: kernels[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")},
@@ -202,6 +214,8 @@ def main():
         "decode_attn_GBps_wall": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
     }
+    if args.stage != "all":
+        out["stage"] = args.stage
     print(json.dumps(out))
 
 

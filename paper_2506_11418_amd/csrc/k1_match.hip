@@ -11,6 +11,8 @@
 // S^T (B index on the M side) so that a lane's 16 accumulators of a 32x32 tile all belong to ONE
 // A row: the running maximum costs one multiply (by 1/|k_j|) and half a max3 per element, and the
 // exact index is only resolved for tiles that raise some lane's maximum.
+#include <type_traits>
+
 #include "ckv_internal.h"
 
 namespace ckv {
@@ -40,12 +42,53 @@ __device__ inline float sumsq8(const Piece& x) {
   return s;
 }
 
-__device__ inline float inv_norm(float ss) { return ss > 0.f ? 1.0f / sqrtf(ss) : 0.f; }
+// 1/sqrt(ss) by the hardware reciprocal square root (1 ulp), 0 for a zero key.
+__device__ inline float inv_norm(float ss) { return ss > 0.f ? __builtin_amdgcn_rsqf(ss) : 0.f; }
+
+// Sum over the LANES lanes (8 or 16, aligned) that hold one key row, with DPP adds: xor 1 and
+// xor 2 inside each quad, then the mirrored half-row and row (after the quad steps all lanes of
+// a quad agree, so a mirror brings in exactly the other quad's / other half's sum).
+template <int LANES>
+__device__ __forceinline__ float row_sum(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));
+  if (LANES == 16)
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));
+  return x;
+}
 
 // Map dispatch order to logical work so that the 8 XCDs (which receive consecutive workgroup ids
 // round-robin) each walk a contiguous range: neighbours in the range (the A blocks of one chunk,
 // adjacent chunks) then share an L2.
 __device__ inline int xcd_remap(int id, int per_xcd) { return (id & 7) * per_xcd + (id >> 3); }
+
+// Fold one 32x32 tile of S^T into the running (max, argmax) of this lane's A row.  sc = acc/|k_j|
+// (the row's own 1/|k_i| > 0 cannot change the argmax and is applied at the end).  Tiles arrive in
+// rotated order, so an equal maximum from a tile of LOWER B indices also replaces the incumbent:
+// the result is the lowest index among all maxima, whatever the visiting order.
+template <bool RAGGED>
+__device__ __forceinline__ void tile_argmax(const f32x16& acc, const f32x4 (&ib)[4], int jbase, int half,
+                                            int valid, float& best, int& bestj) {
+  float sc[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    sc[r] = acc[r] * ib[r >> 2][r & 3];
+    if (RAGGED && (8 * (r >> 2) + 4 * half + (r & 3)) >= valid) sc[r] = -INFINITY;
+  }
+  float mt = __builtin_fmaxf(sc[0], sc[1]);
+#pragma unroll
+  for (int r = 2; r < 16; r += 2) mt = __builtin_fmaxf(__builtin_fmaxf(mt, sc[r]), sc[r + 1]);
+  const bool upd = (mt > best) | ((mt == best) & (jbase < bestj));
+  if (__any(upd)) {
+    int idx = 0;
+#pragma unroll
+    for (int r = 15; r >= 0; --r) idx = (sc[r] == mt) ? r : idx;
+    const int j = jbase + ((idx >> 2) << 3) + (half << 2) + (idx & 3);
+    best = upd ? mt : best;
+    bestj = upd ? j : bestj;
+  }
+}
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
@@ -84,20 +127,70 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
   };
 
   // ---- stage the A block (even offsets) and its inverse norms --------------------------------
-  {
-    constexpr int ROWS_PER_PASS = kThreads / OCT;
-    const int piece = tid % OCT, r0 = tid / OCT;
-#pragma unroll 4
-    for (int row = r0; row < kABlock; row += ROWS_PER_PASS) {
-      Piece x;
-      x.u = make_uint4(0, 0, 0, 0);
-      const int a = a0 + row;
-      if (a < nA) x.u = *reinterpret_cast<const uint4*>(Kseq + (int64_t)(2 * a) * kv.stride_s + piece * 8);
-      float ss = sumsq8(x);
+  // All global loads are issued before the first use (rows past the end re-read the last valid
+  // row and are zeroed), together with the first B panel, so one memory latency covers both.
+  constexpr int PIECES = kPanel * OCT / kThreads;   // 16-byte pieces per thread per panel
+  Piece stage[PIECES];
+  const int piece = tid % OCT, r0 = tid / OCT;
+  constexpr int ROWS_PER_PASS = kThreads / OCT;
+  // every thread walks its own column of 16-byte pieces: row r0 + it*ROWS_PER_PASS of a panel
+  const __bf16* Bcol = Kseq + kv.stride_s + piece * 8;          // B row j lives at token 2j+1
+  const int64_t row_pitch = 2 * kv.stride_s;
+  auto load_panel = [&](int pbase) {
+    if (pbase + kPanel > nB) {   // ragged last panel (uniform branch): clamp to the last row
 #pragma unroll
-      for (int m = 1; m < OCT; m <<= 1) ss += __shfl_xor(ss, m);
-      *reinterpret_cast<uint4*>(panel0 + swz(row, piece)) = x.u;
-      if (piece == 0) inva[row] = inv_norm(ss);
+      for (int it = 0; it < PIECES; ++it) {
+        const int j = min(pbase + r0 + it * ROWS_PER_PASS, nB - 1);
+        stage[it].u = *reinterpret_cast<const uint4*>(Bcol + j * row_pitch);
+      }
+    } else {
+      const __bf16* src = Bcol + (int64_t)(pbase + r0) * row_pitch;
+#pragma unroll
+      for (int it = 0; it < PIECES; ++it)
+        stage[it].u = *reinterpret_cast<const uint4*>(src + it * ROWS_PER_PASS * row_pitch);
+    }
+  };
+  // ROWS_PER_PASS is a multiple of the swizzle period, so a thread's pieces sit at a fixed
+  // offset plus a multiple of ROWS_PER_PASS rows
+  static_assert(ROWS_PER_PASS % (OCT << KEYSHIFT) == 0, "swizzle period");
+  const int lds_piece0 = swz(r0, piece);
+  auto store_panel = [&](int buf, int pbase) {
+    unsigned char* pb = panel0 + buf * kPanel * ROWB + lds_piece0;
+    if (pbase + kPanel > nB) {   // ragged last panel (uniform branch): rows past the end are zero
+#pragma unroll
+      for (int it = 0; it < PIECES; ++it)
+        if (pbase + r0 + it * ROWS_PER_PASS >= nB) stage[it].u = make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int it = 0; it < PIECES; ++it) {
+      const float ss = row_sum<OCT>(sumsq8(stage[it]));
+      *reinterpret_cast<uint4*>(pb + it * ROWS_PER_PASS * ROWB) = stage[it].u;
+      if (piece == 0) invb[buf * kPanel + r0 + it * ROWS_PER_PASS] = inv_norm(ss);
+    }
+  };
+  // panels are visited starting at the one that holds this block's own neighbourhood (keys are
+  // most similar to their neighbours, so the running maxima settle in the first panel)
+  const int n_panels = div_up(nB, kPanel);
+  const int p_first = min(a0 / kPanel, n_panels - 1);
+  {
+    constexpr int APIECES = kABlock * OCT / kThreads;
+    Piece xa[APIECES];
+#pragma unroll
+    for (int it = 0; it < APIECES; ++it) {
+      const int a = min(a0 + r0 + it * ROWS_PER_PASS, nA - 1);
+      xa[it].u = *reinterpret_cast<const uint4*>(Kseq + (int64_t)(2 * a) * kv.stride_s + piece * 8);
+    }
+    load_panel(p_first * kPanel);
+    if (a0 + kABlock > nA) {
+#pragma unroll
+      for (int it = 0; it < APIECES; ++it)
+        if (a0 + r0 + it * ROWS_PER_PASS >= nA) xa[it].u = make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int it = 0; it < APIECES; ++it) {
+      const float ss = row_sum<OCT>(sumsq8(xa[it]));
+      *reinterpret_cast<uint4*>(panel0 + lds_piece0 + it * ROWS_PER_PASS * ROWB) = xa[it].u;
+      if (piece == 0) inva[r0 + it * ROWS_PER_PASS] = inv_norm(ss);
     }
   }
   __syncthreads();
@@ -115,86 +208,66 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
   __syncthreads();
 
   // ---- stream B panels -----------------------------------------------------------------------
-  constexpr int PIECES = kPanel * OCT / kThreads;   // 16-byte pieces per thread per panel
-  Piece stage[PIECES];
-  auto load_panel = [&](int pbase) {
-#pragma unroll
-    for (int it = 0; it < PIECES; ++it) {
-      const int q = tid + it * kThreads, row = q / OCT, piece = q % OCT, j = pbase + row;
-      stage[it].u = make_uint4(0, 0, 0, 0);
-      if (j < nB)
-        stage[it].u = *reinterpret_cast<const uint4*>(Kseq + (int64_t)(2 * j + 1) * kv.stride_s + piece * 8);
-    }
-  };
-  auto store_panel = [&](int buf) {
-    unsigned char* pb = panel0 + buf * kPanel * ROWB;
-#pragma unroll
-    for (int it = 0; it < PIECES; ++it) {
-      const int q = tid + it * kThreads, row = q / OCT, piece = q % OCT;
-      float ss = sumsq8(stage[it]);
-#pragma unroll
-      for (int m = 1; m < OCT; m <<= 1) ss += __shfl_xor(ss, m);
-      *reinterpret_cast<uint4*>(pb + swz(row, piece)) = stage[it].u;
-      if (piece == 0) invb[buf * kPanel + row] = inv_norm(ss);
-    }
-  };
-
   float best[2] = {-INFINITY, -INFINITY};
   int bestj[2] = {0, 0};
   const bool wave_active = (a0 + wave * kRowsPerWave) < nA;
-  const int n_panels = div_up(nB, kPanel);
-  load_panel(0);
-  store_panel(0);
-  for (int p = 0; p < n_panels; ++p) {
-    const int buf = p & 1, pbase = p * kPanel;
-    if (p + 1 < n_panels) load_panel(pbase + kPanel);
-    __syncthreads();
-    if (wave_active) {
-      const unsigned char* pb = panel0 + buf * kPanel * ROWB;
-      const int rows_here = min(kPanel, nB - pbase);
-      const int n_ct = div_up(rows_here, 32);
-      for (int ct = 0; ct < n_ct; ++ct) {
-        f32x16 acc0 = {0}, acc1 = {0};
-        const int brow = ct * 32 + col;
+  // LDS byte offsets of this lane's B fragments inside a 32-row tile: the swizzle key of row
+  // ct*32 + col only depends on col, so tile and buffer offsets are compile-time immediates
+  int boff[KSTEPS];
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-          const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(pb + swz(brow, 2 * s + half));
-          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, afrag[0][s], acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, afrag[1][s], acc1, 0, 0, 0);
-        }
-        // accumulator r of this lane: B row 8*(r/4) + 4*half + r%4 of the tile, A row = col
-        f32x4 ib[4];
+  for (int s = 0; s < KSTEPS; ++s) boff[s] = swz(col, 2 * s + half);
+  const float* ib_lane = invb + 4 * half;
+  auto compute_tiles = [&](auto buf_c, auto full_c, int pbase, int rows_here) {
+    constexpr int BUF = decltype(buf_c)::value;
+    constexpr bool FULL = decltype(full_c)::value;
+    const unsigned char* pb = panel0 + BUF * kPanel * ROWB;
+    const int n_ct = FULL ? kPanel / 32 : div_up(rows_here, 32);
 #pragma unroll
-        for (int qd = 0; qd < 4; ++qd)
-          ib[qd] = *reinterpret_cast<const f32x4*>(&invb[buf * kPanel + ct * 32 + 8 * qd + 4 * half]);
-        const bool ragged = (ct * 32 + 32) > rows_here;
+    for (int ct = 0; ct < kPanel / 32; ++ct) {
+      if (!FULL && ct >= n_ct) break;
+      f32x16 acc0 = {0}, acc1 = {0};
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt) {
-          const f32x16& acc = rt ? acc1 : acc0;
-          float sc[16];
+      for (int s = 0; s < KSTEPS; ++s) {
+        const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(pb + ct * 32 * ROWB + boff[s]);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, afrag[0][s], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, afrag[1][s], acc1, 0, 0, 0);
+      }
+      // accumulator r of this lane: B row 8*(r/4) + 4*half + r%4 of the tile, A row = col
+      f32x4 ib[4];
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sc[r] = acc[r] * ib[r >> 2][r & 3];
-          if (ragged) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              if (ct * 32 + 8 * (r >> 2) + 4 * half + (r & 3) >= rows_here) sc[r] = -INFINITY;
-          }
-          float mt = fmaxf(sc[0], sc[1]);
-#pragma unroll
-          for (int r = 2; r < 16; r += 2) mt = fmaxf(mt, fmaxf(sc[r], sc[r + 1]));
-          const bool upd = mt > best[rt];
-          if (__any(upd)) {
-            int idx = 0;
-#pragma unroll
-            for (int r = 15; r >= 0; --r) idx = (sc[r] == mt) ? r : idx;
-            const int j = pbase + ct * 32 + ((idx >> 2) << 3) + (half << 2) + (idx & 3);
-            best[rt] = upd ? mt : best[rt];
-            bestj[rt] = upd ? j : bestj[rt];
-          }
-        }
+      for (int qd = 0; qd < 4; ++qd)
+        ib[qd] = *reinterpret_cast<const f32x4*>(ib_lane + BUF * kPanel + ct * 32 + 8 * qd);
+      const int jbase = pbase + ct * 32;
+      const int valid = rows_here - ct * 32;      // rows of this tile that exist (>= 32: all)
+      if (FULL || valid >= 32) {
+        tile_argmax<false>(acc0, ib, jbase, half, valid, best[0], bestj[0]);
+        tile_argmax<false>(acc1, ib, jbase, half, valid, best[1], bestj[1]);
+      } else {
+        tile_argmax<true>(acc0, ib, jbase, half, valid, best[0], bestj[0]);
+        tile_argmax<true>(acc1, ib, jbase, half, valid, best[1], bestj[1]);
       }
     }
-    if (p + 1 < n_panels) store_panel(buf ^ 1);
+  };
+  store_panel(0, p_first * kPanel);
+  for (int it_p = 0; it_p < n_panels; ++it_p) {
+    int p = p_first + it_p;
+    if (p >= n_panels) p -= n_panels;
+    int p_next = p + 1;
+    if (p_next >= n_panels) p_next = 0;
+    const int buf = it_p & 1, pbase = p * kPanel;
+    if (it_p + 1 < n_panels) load_panel(p_next * kPanel);
+    __syncthreads();
+    if (wave_active) {
+      const int rows_here = min(kPanel, nB - pbase);
+      if (rows_here == kPanel) {
+        if (buf == 0) compute_tiles(std::integral_constant<int, 0>{}, std::true_type{}, pbase, kPanel);
+        else compute_tiles(std::integral_constant<int, 1>{}, std::true_type{}, pbase, kPanel);
+      } else {
+        if (buf == 0) compute_tiles(std::integral_constant<int, 0>{}, std::false_type{}, pbase, rows_here);
+        else compute_tiles(std::integral_constant<int, 1>{}, std::false_type{}, pbase, rows_here);
+      }
+    }
+    if (it_p + 1 < n_panels) store_panel(buf ^ 1, p_next * kPanel);
   }
 
   // ---- merge the two lane halves of every A row and write ------------------------------------

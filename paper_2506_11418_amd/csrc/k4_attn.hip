@@ -4,6 +4,10 @@
 // 16-byte loads (one row per group of row_bytes/16 lanes), serves all G query heads of its KV head
 // from registers, keeps an online softmax in the exp2 domain, and writes (max, sum, o) partials;
 // a second small kernel merges the partials with the usual log-sum-exp rescaling.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "ckv_internal.h"
 
 namespace ckv {
@@ -17,6 +21,29 @@ struct Elems;
 template <>
 struct Elems<__bf16> {
   static constexpr int E = 8;
+  typedef uint4 Raw;
+  __device__ static Raw load_raw(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
+  __device__ static void unpack(const Raw& u, float* x) {
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(w[i] << 16);
+      x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  // q.k over this lane's 8 elements: packed bf16 pairs straight into v_dot2 (products exact,
+  // fp32 accumulation), no unpacking of the key
+  typedef uint4 Q;
+  __device__ static Q load_q(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
+  __device__ static float dot(const Q& qv, const Raw& kv) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    const uint32_t a[4] = {qv.x, qv.y, qv.z, qv.w}, b[4] = {kv.x, kv.y, kv.z, kv.w};
+    float d = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a[i]), __builtin_bit_cast(bf16x2, b[i]), d, false);
+    return d;
+  }
   __device__ static void load(const __bf16* p, float* x) {
     const uint4 u = *reinterpret_cast<const uint4*>(p);
     const uint32_t w[4] = {u.x, u.y, u.z, u.w};
@@ -30,11 +57,35 @@ struct Elems<__bf16> {
 template <>
 struct Elems<float> {
   static constexpr int E = 4;
+  typedef float4 Raw;
+  __device__ static Raw load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static void unpack(const Raw& u, float* x) { x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w; }
+  typedef float4 Q;
+  __device__ static Q load_q(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static float dot(const Q& a, const Raw& b) {
+    return fmaf(a.w, b.w, fmaf(a.z, b.z, fmaf(a.y, b.y, a.x * b.x)));
+  }
   __device__ static void load(const float* p, float* x) {
     const float4 u = *reinterpret_cast<const float4*>(p);
     x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w;
   }
 };
+
+// Sum over the LANES consecutive lanes (aligned) that share a cache row; every lane gets the sum.
+// Quad steps and the mirrored half-row / row are DPP adds; 32 lanes add one cross-row exchange.
+template <int LANES>
+__device__ __forceinline__ float row_sum(float x) {
+  auto dpp = [](float v, auto ctrl) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value,
+                                                                 0xF, 0xF, true));
+  };
+  x += dpp(x, std::integral_constant<int, 0xB1>{});                    // lane ^ 1
+  x += dpp(x, std::integral_constant<int, 0x4E>{});                    // lane ^ 2
+  if (LANES >= 8) x += dpp(x, std::integral_constant<int, 0x141>{});   // mirrored within 8
+  if (LANES >= 16) x += dpp(x, std::integral_constant<int, 0x140>{});  // mirrored within 16
+  if (LANES >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
 
 __device__ inline uint16_t f32_to_bf16_rne(float f) {
   const uint32_t u = __float_as_uint(f);
@@ -43,6 +94,14 @@ __device__ inline uint16_t f32_to_bf16_rne(float f) {
 }
 
 // partial layout: o_part[((b*Hkv + kvh)*S + split)*G + g][D], ml_part[...][2] = (max, sum)
+//
+// Thread mapping: LPR = row_bytes/16 lanes share one cache row ("row group"); a wave holds 64/LPR
+// row groups, so one wave-wide 16-byte load covers 64/LPR consecutive rows = 1 KiB contiguous.
+// Every row group takes kUnroll tokens per iteration: their K and V loads are all issued before
+// the first use (bytes in flight hide HBM latency), the logits of the kUnroll tokens share one
+// running-max update, so the accumulators are rescaled once per kUnroll tokens.
+constexpr int kUnroll = 4;
+
 template <typename T, int D, int G>
 __global__ __launch_bounds__(kThreads) void attn_partial_kernel(
     const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V, TensorView kv, int kv_heads,
@@ -51,6 +110,7 @@ __global__ __launch_bounds__(kThreads) void attn_partial_kernel(
   constexpr int E = Elems<T>::E;
   constexpr int LPR = D / E;
   constexpr int NRG = kThreads / LPR;
+  constexpr int U = kUnroll;
   __shared__ float s_m[NRG][G];
   __shared__ float s_l[NRG][G];
   __shared__ float s_o[NRG][D];
@@ -60,16 +120,14 @@ __global__ __launch_bounds__(kThreads) void attn_partial_kernel(
   const int len = lens ? min(lens[b], seq) : seq;
   const int t0 = split * span, t1 = min(t0 + span, len);
   const int64_t base = (int64_t)b * kv.stride_b + (int64_t)kvh * kv.stride_h + piece * E;
+  const T* Kp = K + base;
+  const T* Vp = V + base;
   const int32_t* dseq = deg ? deg + ((int64_t)b * kv_heads + kvh) * seq : nullptr;
 
-  float qf[G][E];
+  typename Elems<T>::Q qv[G];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float x[E];
-    Elems<T>::load(q + ((int64_t)b * kv_heads * G + kvh * G + g) * D + piece * E, x);
-#pragma unroll
-    for (int e = 0; e < E; ++e) qf[g][e] = x[e] * scale_log2e;
-  }
+  for (int g = 0; g < G; ++g)
+    qv[g] = Elems<T>::load_q(q + ((int64_t)b * kv_heads * G + kvh * G + g) * D + piece * E);
   float m[G], l[G], acc[G][E];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
@@ -79,34 +137,71 @@ __global__ __launch_bounds__(kThreads) void attn_partial_kernel(
     for (int e = 0; e < E; ++e) acc[g][e] = 0.f;
   }
 
-  for (int t = t0 + rg; t < t1; t += NRG) {
-    float kx[E], vx[E];
-    Elems<T>::load(K + base + (int64_t)t * kv.stride_s, kx);
-    Elems<T>::load(V + base + (int64_t)t * kv.stride_s, vx);
-    const float bias = dseq ? __log2f((float)dseq[t]) : 0.f;
-    float z[G];
+  // token of (iteration, slot u) for this row group: tb + u*NRG + rg.  The loads of iteration
+  // i+1 are issued before iteration i is consumed (two register sets, software pipeline).
+  struct Stage {
+    typename Elems<T>::Raw kr[U], vr[U];
+    int dg[U];
+  };
+  auto issue = [&](Stage& st, int tb) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float d = 0.f;
+    for (int u = 0; u < U; ++u) {
+      const int tc = min(tb + u * NRG + rg, t1 - 1);   // clamp: always a valid row, masked at use
+      st.kr[u] = Elems<T>::load_raw(Kp + (int64_t)tc * kv.stride_s);
+      st.vr[u] = Elems<T>::load_raw(Vp + (int64_t)tc * kv.stride_s);
+      st.dg[u] = dseq ? dseq[tc] : 1;
+    }
+  };
+  auto consume = [&](const Stage& st, int tb) {
+    float z[U][G];
 #pragma unroll
-      for (int e = 0; e < E; ++e) d = fmaf(qf[g][e], kx[e], d);
-      z[g] = d;
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) z[u][g] = row_sum<LPR>(Elems<T>::dot(qv[g], st.kr[u]));
+      const float lb = dseq ? __log2f((float)st.dg[u]) : 0.f;
+      const bool ok = (tb + u * NRG + rg) < t1;
+#pragma unroll
+      for (int g = 0; g < G; ++g) z[u][g] = ok ? fmaf(z[u][g], scale_log2e, lb) : -INFINITY;
     }
 #pragma unroll
-    for (int s = 1; s < LPR; s <<= 1) {
-#pragma unroll
-      for (int g = 0; g < G; ++g) z[g] += __shfl_xor(z[g], s);
-    }
-#pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float zg = z[g] + bias;
-      const float mn = fmaxf(m[g], zg);
-      const float alpha = exp2f(m[g] - mn);
-      const float p = exp2f(zg - mn);
-      l[g] = l[g] * alpha + p;
+      float mn = m[g];
 #pragma unroll
-      for (int e = 0; e < E; ++e) acc[g][e] = fmaf(acc[g][e], alpha, p * vx[e]);
+      for (int u = 0; u < U; ++u) mn = fmaxf(mn, z[u][g]);
+      // a row group that has seen no valid token yet keeps mn = -inf: subtract 0 instead, so that
+      // exp2(-inf) = 0 comes out rather than NaN
+      const float ref = (mn == -INFINITY) ? 0.f : mn;
+      const float alpha = exp2f(m[g] - ref);
       m[g] = mn;
+      l[g] *= alpha;
+#pragma unroll
+      for (int e = 0; e < E; ++e) acc[g][e] *= alpha;
+#pragma unroll
+      for (int u = 0; u < U; ++u) z[u][g] = exp2f(z[u][g] - ref);   // now the weight p
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float vx[E];
+      Elems<T>::unpack(st.vr[u], vx);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        l[g] += z[u][g];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[g][e] = fmaf(z[u][g], vx[e], acc[g][e]);
+      }
+    }
+  };
+  constexpr int STEP = NRG * U;
+  if (t0 < t1) {
+    Stage sa, sb;
+    issue(sa, t0);
+    for (int tb = t0; tb < t1; tb += 2 * STEP) {
+      if (tb + STEP < t1) issue(sb, tb + STEP);
+      consume(sa, tb);
+      if (tb + STEP < t1) {
+        if (tb + 2 * STEP < t1) issue(sa, tb + 2 * STEP);
+        consume(sb, tb + STEP);
+      }
     }
   }
 
@@ -143,24 +238,50 @@ __global__ __launch_bounds__(kThreads) void attn_partial_kernel(
   }
 }
 
+// Merge the split partials of one (batch, query head): weights exp2(m_s - M) are computed once
+// into LDS by the first n_splits threads, then every thread owns one output channel and sums
+// over splits with independent (unrolled) loads.
+constexpr int kMaxSplits = 1024;
 template <int G>
 __global__ void attn_combine_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
                                     int kv_heads, int n_splits, int dim, void* __restrict__ o, int o_dtype) {
+  __shared__ float s_w[kMaxSplits];
+  __shared__ float s_red[2][4];
   const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
   const int kvh = hq / G, g = hq % G;
   const int64_t pbase = ((int64_t)b * kv_heads + kvh) * n_splits;
-  float M = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml_part[((pbase + s) * G + g) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const int64_t idx = (pbase + s) * G + g;
-    const float ms = ml_part[idx * 2];
-    if (ms == -INFINITY) continue;
-    const float f = exp2f(ms - M);
-    den += ml_part[idx * 2 + 1] * f;
-    if (d < dim) num += o_part[idx * dim + d] * f;
+  const int lane = d & 63, wave = d >> 6, n_waves = blockDim.x >> 6;
+  float mloc = -INFINITY;
+  for (int s = d; s < n_splits; s += blockDim.x) {
+    const float ms = ml_part[((pbase + s) * G + g) * 2];
+    s_w[s] = ms;
+    mloc = fmaxf(mloc, ms);
   }
+#pragma unroll
+  for (int sh = 32; sh > 0; sh >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, sh));
+  if (lane == 0) s_red[0][wave] = mloc;
+  __syncthreads();
+  float M = -INFINITY;
+  for (int w2 = 0; w2 < n_waves; ++w2) M = fmaxf(M, s_red[0][w2]);
+  float dloc = 0.f;
+  for (int s = d; s < n_splits; s += blockDim.x) {
+    const float ms = s_w[s];
+    const float f = (ms == -INFINITY) ? 0.f : exp2f(ms - M);
+    s_w[s] = f;
+    dloc += f * ml_part[((pbase + s) * G + g) * 2 + 1];
+  }
+#pragma unroll
+  for (int sh = 32; sh > 0; sh >>= 1) dloc += __shfl_xor(dloc, sh);
+  if (lane == 0) s_red[1][wave] = dloc;
+  __syncthreads();
+  float den = 0.f;
+  for (int w2 = 0; w2 < n_waves; ++w2) den += s_red[1][w2];
   if (d >= dim) return;
+  float num = 0.f;
+  const float* op = o_part + (pbase * G + g) * dim + d;
+  const int64_t pitch = (int64_t)G * dim;
+#pragma unroll 8
+  for (int s = 0; s < n_splits; ++s) num = fmaf(op[s * pitch], s_w[s], num);
   const float res = den > 0.f ? num / den : 0.f;
   const int64_t oi = ((int64_t)b * kv_heads * G + hq) * dim + d;
   if (o_dtype == CKV_BF16) reinterpret_cast<uint16_t*>(o)[oi] = f32_to_bf16_rne(res);
@@ -205,12 +326,14 @@ hipError_t launch_attn_g(int G, const void* q, const void* K, const void* V, Ten
 }  // namespace
 
 int attn_splits(int n_b, int kv_heads, int seq) {
-  // enough workgroups to fill 256 CUs several times over, but at least 256 tokens per slice
+  // about two workgroups per CU (each has a fixed merge/write cost), at least 256 tokens per slice
   const int64_t bh = (int64_t)n_b * kv_heads;
-  int want = (int)((2048 + bh - 1) / bh);
-  const int cap = (seq + 255) / 256;
+  int want = (int)((512 + bh - 1) / bh);
+  int cap = (seq + 255) / 256;
+  if (cap > 1024) cap = 1024;   // the combine kernel keeps one weight per split in LDS
   if (want > cap) want = cap;
   if (want < 1) want = 1;
+  if (const char* e = getenv("CKV_TUNE_ATTN_SPLITS")) { int v = atoi(e); if (v >= 1 && v <= 1024) want = v; }
   return want;
 }
 
