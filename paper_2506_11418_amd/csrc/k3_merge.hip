@@ -17,10 +17,13 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kMaxHalf = 1024;  // max |A| = |B| (chunk <= 2048)
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
 // Quotient S/n rounded to bf16 with a single nearest-even rounding: the fp32 quotient is
 // correctly rounded, so a second rounding can only go wrong when it sits exactly on a bf16
 // midpoint; the sign of the exact residual S - q*n then says on which side the true value lies.
-__device__ inline uint16_t div_round_bf16(float S, float n) {
+__device__ inline uint32_t div_round_bf16(float S, float n) {
   const float q = S / n;
   const uint32_t u = __float_as_uint(q);
   const uint32_t low = u & 0xffffu;
@@ -31,7 +34,7 @@ __device__ inline uint16_t div_round_bf16(float S, float n) {
   } else {
     up = low > 0x8000u;
   }
-  return (uint16_t)((u >> 16) + up);
+  return ((u >> 16) + up) & 0xffffu;
 }
 
 __device__ inline int block_exclusive_scan(int v, int* s_wave_tot, int* total) {
@@ -64,21 +67,45 @@ template <>
 struct Row<__bf16> {
   static constexpr int E = 8;
   typedef float Acc;
-  __device__ static void load(const __bf16* p, float* x) {
-    const uint4 u = *reinterpret_cast<const uint4*>(p);
-    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+  typedef uint4 Raw;
+  __device__ static Raw load_raw(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
+  __device__ static void store_raw(__bf16* p, const Raw& r) { *reinterpret_cast<uint4*>(p) = r; }
+  __device__ static void fma_into(Acc* acc, const Raw& u, Acc w) {
+    const uint32_t x[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      x[2 * i] = __uint_as_float(w[i] << 16);
-      x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      acc[2 * i] = fmaf(w, __uint_as_float(x[i] << 16), acc[2 * i]);
+      acc[2 * i + 1] = fmaf(w, __uint_as_float(x[i] & 0xffff0000u), acc[2 * i + 1]);
     }
   }
-  __device__ static void store_div(__bf16* p, const float* acc, int n) {
-    uint32_t w[4];
+  // acc/n, one rounding to bf16.  Fast path: multiply by the fp32 reciprocal and let the packed
+  // converter round (nearest-even).  For n a power of two the product is exact, midpoints
+  // included.  Otherwise it is within 3 ulp(fp32) of the true quotient, so whenever its low 16
+  // bits are farther than that from a bf16 midpoint the result is the correctly rounded quotient;
+  // the few elements inside the window take the exact path.
+  __device__ static void store_div(__bf16* p, const Acc* acc, int n) {
     const float fn = (float)n;
+    const float rcp = __builtin_amdgcn_rcpf(fn);   // exact for powers of two, 1 ulp otherwise
+    const bool pow2 = (n & (n - 1)) == 0;          // then acc*rcp IS the quotient: no second rounding
+    float qv[8];
+    bool risky = false;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      w[i] = (uint32_t)div_round_bf16(acc[2 * i], fn) | ((uint32_t)div_round_bf16(acc[2 * i + 1], fn) << 16);
+    for (int i = 0; i < 8; ++i) {
+      qv[i] = acc[i] * rcp;
+      risky |= ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
+    }
+    risky &= !pow2;
+    uint32_t w[4];
+    if (__any(risky)) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w[i] = div_round_bf16(acc[2 * i], fn) | (div_round_bf16(acc[2 * i + 1], fn) << 16);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const f32x2 v = {qv[2 * i], qv[2 * i + 1]};
+        w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+      }
+    }
     *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 };
@@ -87,16 +114,20 @@ template <>
 struct Row<float> {
   static constexpr int E = 4;
   typedef double Acc;
-  __device__ static void load(const float* p, float* x) {
-    const float4 u = *reinterpret_cast<const float4*>(p);
-    x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w;
+  typedef float4 Raw;
+  __device__ static Raw load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static void store_raw(float* p, const Raw& r) { *reinterpret_cast<float4*>(p) = r; }
+  __device__ static void fma_into(Acc* acc, const Raw& u, Acc w) {
+    acc[0] += w * (double)u.x; acc[1] += w * (double)u.y; acc[2] += w * (double)u.z; acc[3] += w * (double)u.w;
   }
-  __device__ static void store_div(float* p, const double* acc, int n) {
+  __device__ static void store_div(float* p, const Acc* acc, int n) {
     const double dn = (double)n;
     *reinterpret_cast<float4*>(p) = make_float4((float)(acc[0] / dn), (float)(acc[1] / dn),
                                                 (float)(acc[2] / dn), (float)(acc[3] / dn));
   }
 };
+
+constexpr int kRowsInFlight = 2;   // output rows a row group works on at once
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void merge_kernel(
@@ -106,14 +137,17 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     int32_t* __restrict__ deg_out, TensorView out, int64_t deg_out_stride, int32_t* __restrict__ map_out) {
   constexpr int E = Row<T>::E;
   constexpr int LPR = D / E;                 // lanes per row
-  constexpr int NRG = kThreads / LPR;        // rows in flight per workgroup
+  constexpr int NRG = kThreads / LPR;        // row groups per workgroup
+  constexpr int U = kRowsInFlight;
   typedef typename Row<T>::Acc Acc;
+  typedef typename Row<T>::Raw Raw;
 
-  __shared__ int32_t s_dst[kMaxHalf];
-  __shared__ float s_score[kMaxHalf];
-  __shared__ unsigned char s_keep[kMaxHalf];
+  // s_dstk[i]: destination (B index) of source i if its edge is kept, -1 otherwise
+  __shared__ __attribute__((aligned(16))) int16_t s_dstk[kMaxHalf];
+  __shared__ __attribute__((aligned(16))) float s_score[kMaxHalf];
   __shared__ int32_t s_cnt[kMaxHalf];
-  __shared__ int32_t s_start[kMaxHalf];
+  __shared__ int32_t s_fill[kMaxHalf];
+  __shared__ int16_t s_start[kMaxHalf];
   __shared__ int16_t s_members[kMaxHalf];
   __shared__ int16_t s_local_out[2 * kMaxHalf];
   __shared__ int16_t s_src_of_out[2 * kMaxHalf];
@@ -128,45 +162,56 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   const int out_base = g * chunk_out(chunk, r);
   const int n_src = n_sources(seq, chunk);
   const int64_t src_base = (int64_t)bh * n_src + (int64_t)g * (chunk >> 1);
+  const int nA_pad = (nA + 7) & ~7;
 
-  for (int i = tid; i < nA; i += kThreads) {
-    s_dst[i] = dst_local[src_base + i];
-    s_score[i] = score[src_base + i];
+  for (int i = tid; i < nA_pad; i += kThreads) {
+    s_dstk[i] = (i < nA && m > 0) ? (int16_t)dst_local[src_base + i] : (int16_t)-1;
+    if (m > 0 && m < nA) s_score[i] = (i < nA) ? score[src_base + i] : -INFINITY;
   }
   for (int j = tid; j < nB; j += kThreads) s_cnt[j] = 0;
   __syncthreads();
 
-  // ---- top-r: rank by counting ---------------------------------------------------------------
-  if (m == nA || m == 0) {
-    for (int i = tid; i < nA; i += kThreads) s_keep[i] = (m != 0);
-  } else {
-    for (int i = tid; i < nA; i += kThreads) {
-      const float si = s_score[i];
-      int rank = 0;
-      for (int o = 0; o < nA; ++o) {
-        const float so = s_score[o];
-        rank += (so > si) || (so == si && o < i);
+  // ---- top-r: rank by counting (score descending, index ascending) ----------------------------
+  if (m > 0 && m < nA) {
+    bool drop[kMaxHalf / kThreads];
+#pragma unroll
+    for (int it = 0; it < kMaxHalf / kThreads; ++it) {
+      const int i = tid + it * kThreads;
+      drop[it] = false;
+      if (i < nA) {
+        const float si = s_score[i];
+        int rank = 0;
+        for (int o4 = 0; o4 < nA_pad; o4 += 4) {
+          const float4 so = *reinterpret_cast<const float4*>(&s_score[o4]);
+          rank += (so.x > si) || (so.x == si && o4 < i);
+          rank += (so.y > si) || (so.y == si && o4 + 1 < i);
+          rank += (so.z > si) || (so.z == si && o4 + 2 < i);
+          rank += (so.w > si) || (so.w == si && o4 + 3 < i);
+        }
+        drop[it] = rank >= m;
       }
-      s_keep[i] = rank < m;
     }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kMaxHalf / kThreads; ++it)
+      if (drop[it]) s_dstk[tid + it * kThreads] = -1;
+    __syncthreads();
   }
-  __syncthreads();
 
   // ---- kept sources grouped by destination, ascending within a group --------------------------
-  int my_pos[kMaxHalf / kThreads];
+  // counts by integer atomics (order-free), then slots handed out by atomics in arbitrary order
+  // and every destination's short list sorted: the final order is unique, so results stay
+  // run-to-run identical.  Lists longer than kSortMax (degenerate inputs: many identical keys)
+  // are placed by rank counting instead.
+  constexpr int kSortMax = 8;
 #pragma unroll
   for (int it = 0; it < kMaxHalf / kThreads; ++it) {
     const int i = tid + it * kThreads;
-    my_pos[it] = 0;
-    if (i < nA && s_keep[i]) {
-      const int d = s_dst[i];
-      int pos = 0;
-      for (int o = 0; o < i; ++o) pos += (s_keep[o] && s_dst[o] == d);
-      my_pos[it] = pos;
-      atomicAdd(&s_cnt[d], 1);   // integer count: the total does not depend on the order
-    }
+    const int d = (i < nA) ? (int)s_dstk[i] : -1;
+    if (d >= 0) atomicAdd(&s_cnt[d], 1);
   }
   __syncthreads();
+  int longest = 0;
   {
     int c[4], sum = 0;
 #pragma unroll
@@ -174,21 +219,47 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       const int j = tid * 4 + e;
       c[e] = (j < nB) ? s_cnt[j] : 0;
       sum += c[e];
+      longest = max(longest, c[e]);
     }
     int tot;
     int base = block_exclusive_scan(sum, s_wave_tot, &tot);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int j = tid * 4 + e;
-      if (j < nB) s_start[j] = base;
+      if (j < nB) { s_start[j] = (int16_t)base; s_fill[j] = 0; }
       base += c[e];
+    }
+  }
+  const bool any_long = __syncthreads_or(longest > kSortMax);
+#pragma unroll
+  for (int it = 0; it < kMaxHalf / kThreads; ++it) {
+    const int i = tid + it * kThreads;
+    const int d = (i < nA) ? (int)s_dstk[i] : -1;
+    if (d >= 0) {
+      int pos;
+      if (any_long && s_cnt[d] > kSortMax) {        // rank among earlier sources of the same list
+        pos = 0;
+        for (int o = 0; o < i; ++o) pos += ((int)s_dstk[o] == d);
+      } else {
+        pos = atomicAdd(&s_fill[d], 1);
+      }
+      s_members[s_start[d] + pos] = (int16_t)i;
     }
   }
   __syncthreads();
 #pragma unroll
-  for (int it = 0; it < kMaxHalf / kThreads; ++it) {
-    const int i = tid + it * kThreads;
-    if (i < nA && s_keep[i]) s_members[s_start[s_dst[i]] + my_pos[it]] = (int16_t)i;
+  for (int e = 0; e < 4; ++e) {                     // insertion sort of the short lists
+    const int j = tid * 4 + e;
+    const int n = (j < nB) ? s_cnt[j] : 0;
+    if (n > 1 && n <= kSortMax) {
+      int16_t* lst = &s_members[s_start[j]];
+      for (int a = 1; a < n; ++a) {
+        const int16_t v = lst[a];
+        int b2 = a - 1;
+        while (b2 >= 0 && lst[b2] > v) { lst[b2 + 1] = lst[b2]; --b2; }
+        lst[b2 + 1] = v;
+      }
+    }
   }
 
   // ---- retained tokens: prefix sum over the chunk --------------------------------------------
@@ -197,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int u = tid * 8 + e;
-      const bool ret = (u < L) && ((u & 1) || !s_keep[u >> 1]);
+      const bool ret = (u < L) && ((u & 1) || s_dstk[u >> 1] < 0);
       flags |= (int)ret << e;
       cnt += ret;
     }
@@ -219,55 +290,75 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   if (map_out != nullptr) {
     int32_t* mp = map_out + (int64_t)bh * seq + g0;
     for (int u = tid; u < L; u += kThreads) {
-      const bool ret = (u & 1) || !s_keep[u >> 1];
-      const int slot = ret ? s_local_out[u] : s_local_out[2 * s_dst[u >> 1] + 1];
+      const int d = (u & 1) ? -1 : (int)s_dstk[u >> 1];
+      const int slot = (d < 0) ? s_local_out[u] : s_local_out[2 * d + 1];
       mp[u] = out_base + slot;
     }
   }
 
-  // ---- emit rows -----------------------------------------------------------------------------
+  // ---- emit rows: every row group works on U output rows at once; the loads of their own rows
+  // and of their first merged source are all in flight before anything is consumed ---------------
   const int rg = tid / LPR, piece = tid % LPR;
-  const int64_t in_seq = in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E;
-  const int64_t out_seq = out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
+  const T* Kin = K + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E;
+  const T* Vin = V + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E;
+  T* Ko = K_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
+  T* Vo = V_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
   const int32_t* dseq = deg_in ? deg_in + (int64_t)bh * seq + g0 : nullptr;
   int32_t* dout = deg_out + (int64_t)bh * deg_out_stride + out_base;
-  for (int o = rg; o < n_out; o += NRG) {
-    const int u = s_src_of_out[o];
-    const int64_t src_off = in_seq + (int64_t)u * in.stride_s;
-    const int64_t dst_off = out_seq + (int64_t)o * out.stride_s;
-    const int nmem = (u & 1) ? s_cnt[u >> 1] : 0;
-    const int du = dseq ? dseq[u] : 1;
-    if (nmem == 0) {  // untouched token: bit copy
-      *reinterpret_cast<uint4*>(K_out + dst_off) = *reinterpret_cast<const uint4*>(K + src_off);
-      *reinterpret_cast<uint4*>(V_out + dst_off) = *reinterpret_cast<const uint4*>(V + src_off);
-      if (piece == 0) dout[o] = du;
-      continue;
-    }
-    float x[E], y[E];
-    Acc ak[E], av[E];
-    Row<T>::load(K + src_off, x);
-    Row<T>::load(V + src_off, y);
-    {
-      const Acc w = (Acc)du;
+  for (int ob = 0; ob < n_out; ob += NRG * U) {
+    int tok[U], nmem[U], first[U], mem0[U], du[U], dm[U];
+    bool valid[U];
 #pragma unroll
-      for (int e = 0; e < E; ++e) { ak[e] = w * (Acc)x[e]; av[e] = w * (Acc)y[e]; }
+    for (int u = 0; u < U; ++u) {
+      const int o = ob + u * NRG + rg;
+      valid[u] = o < n_out;
+      tok[u] = s_src_of_out[valid[u] ? o : n_out - 1];
+      const bool isB = tok[u] & 1;
+      nmem[u] = isB ? s_cnt[tok[u] >> 1] : 0;
+      first[u] = isB ? (int)s_start[tok[u] >> 1] : 0;
+      mem0[u] = (nmem[u] > 0) ? 2 * (int)s_members[first[u]] : tok[u];   // no source: re-read own row
     }
-    int ndeg = du;
-    const int first = s_start[u >> 1];
-    for (int q = 0; q < nmem; ++q) {
-      const int ua = 2 * (int)s_members[first + q];
-      const int da = dseq ? dseq[ua] : 1;
-      const int64_t a_off = in_seq + (int64_t)ua * in.stride_s;
-      Row<T>::load(K + a_off, x);
-      Row<T>::load(V + a_off, y);
-      const Acc w = (Acc)da;
+    Raw kb[U], vb[U], km[U], vm[U];
 #pragma unroll
-      for (int e = 0; e < E; ++e) { ak[e] += w * (Acc)x[e]; av[e] += w * (Acc)y[e]; }
-      ndeg += da;
+    for (int u = 0; u < U; ++u) {
+      kb[u] = Row<T>::load_raw(Kin + (int64_t)tok[u] * in.stride_s);
+      vb[u] = Row<T>::load_raw(Vin + (int64_t)tok[u] * in.stride_s);
+      km[u] = Row<T>::load_raw(Kin + (int64_t)mem0[u] * in.stride_s);
+      vm[u] = Row<T>::load_raw(Vin + (int64_t)mem0[u] * in.stride_s);
+      du[u] = dseq ? dseq[tok[u]] : 1;
+      dm[u] = dseq ? dseq[mem0[u]] : 1;
     }
-    Row<T>::store_div(K_out + dst_off, ak, ndeg);
-    Row<T>::store_div(V_out + dst_off, av, ndeg);
-    if (piece == 0) dout[o] = ndeg;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!valid[u]) continue;
+      const int o = ob + u * NRG + rg;
+      if (nmem[u] == 0) {  // untouched token: bit copy
+        Row<T>::store_raw(Ko + (int64_t)o * out.stride_s, kb[u]);
+        Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, vb[u]);
+        if (piece == 0) dout[o] = du[u];
+        continue;
+      }
+      Acc ak[E], av[E];
+#pragma unroll
+      for (int e = 0; e < E; ++e) { ak[e] = 0; av[e] = 0; }
+      Row<T>::fma_into(ak, kb[u], (Acc)du[u]);
+      Row<T>::fma_into(av, vb[u], (Acc)du[u]);
+      Row<T>::fma_into(ak, km[u], (Acc)dm[u]);
+      Row<T>::fma_into(av, vm[u], (Acc)dm[u]);
+      int ndeg = du[u] + dm[u];
+      for (int q = 1; q < nmem[u]; ++q) {
+        const int ua = 2 * (int)s_members[first[u] + q];
+        const int da = dseq ? dseq[ua] : 1;
+        const Raw kx = Row<T>::load_raw(Kin + (int64_t)ua * in.stride_s);
+        const Raw vx = Row<T>::load_raw(Vin + (int64_t)ua * in.stride_s);
+        Row<T>::fma_into(ak, kx, (Acc)da);
+        Row<T>::fma_into(av, vx, (Acc)da);
+        ndeg += da;
+      }
+      Row<T>::store_div(Ko + (int64_t)o * out.stride_s, ak, ndeg);
+      Row<T>::store_div(Vo + (int64_t)o * out.stride_s, av, ndeg);
+      if (piece == 0) dout[o] = ndeg;
+    }
   }
 }
 
