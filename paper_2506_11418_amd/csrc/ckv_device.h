@@ -1,0 +1,166 @@
+// Device helpers shared by the kernel translation units of libckv (bf16 pieces, LDS swizzle,
+// lane-group sums, the fused tile argmax, and the single-rounding bf16 quotient).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ckv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+union Piece {   // 16 bytes = 8 bf16
+  uint4 u;
+  bf16x8 v;
+  bf16x2 p[4];
+};
+
+__device__ inline float sumsq8(const Piece& x) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_fdot2_f32_bf16(x.p[i], x.p[i], s, false);
+  return s;
+}
+
+// 1/sqrt(ss) by the hardware reciprocal square root (1 ulp), 0 for a zero key.
+__device__ inline float inv_norm(float ss) { return ss > 0.f ? __builtin_amdgcn_rsqf(ss) : 0.f; }
+
+// Sum over the LANES lanes (8 or 16, aligned) that hold one key row, with DPP adds: xor 1 and
+// xor 2 inside each quad, then the mirrored half-row and row (after the quad steps all lanes of
+// a quad agree, so a mirror brings in exactly the other quad's / other half's sum).
+template <int LANES>
+__device__ __forceinline__ float row_sum(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));
+  if (LANES == 16)
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));
+  return x;
+}
+
+// Map dispatch order to logical work so that the 8 XCDs (which receive consecutive workgroup ids
+// round-robin) each walk a contiguous range: neighbours in the range (the A blocks of one chunk,
+// adjacent chunks) then share an L2.
+__device__ inline int xcd_remap(int id, int per_xcd) { return (id & 7) * per_xcd + (id >> 3); }
+
+// Fold one 32x32 tile of S^T into the running (max, argmax) of this lane's A row.  sc = acc/|k_j|
+// (the row's own 1/|k_i| > 0 cannot change the argmax and is applied at the end).  Tiles arrive in
+// rotated order, so an equal maximum from a tile of LOWER B indices also replaces the incumbent:
+// the result is the lowest index among all maxima, whatever the visiting order.
+template <bool RAGGED>
+__device__ __forceinline__ void tile_argmax(const f32x16& acc, const f32x4 (&ib)[4], int jbase, int half,
+                                            int valid, float& best, int& bestj) {
+  float sc[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    sc[r] = acc[r] * ib[r >> 2][r & 3];
+    if (RAGGED && (8 * (r >> 2) + 4 * half + (r & 3)) >= valid) sc[r] = -INFINITY;
+  }
+  float mt = __builtin_fmaxf(sc[0], sc[1]);
+#pragma unroll
+  for (int r = 2; r < 16; r += 2) mt = __builtin_fmaxf(__builtin_fmaxf(mt, sc[r]), sc[r + 1]);
+  const bool upd = (mt > best) | ((mt == best) & (jbase < bestj));
+  if (__any(upd)) {
+    int idx = 0;
+#pragma unroll
+    for (int r = 15; r >= 0; --r) idx = (sc[r] == mt) ? r : idx;
+    const int j = jbase + ((idx >> 2) << 3) + (half << 2) + (idx & 3);
+    best = upd ? mt : best;
+    bestj = upd ? j : bestj;
+  }
+}
+
+
+// Quotient S/n rounded to bf16 with a single nearest-even rounding: the fp32 quotient is
+// correctly rounded, so a second rounding can only go wrong when it sits exactly on a bf16
+// midpoint; the sign of the exact residual S - q*n then says on which side the true value lies.
+__device__ inline uint32_t div_round_bf16(float S, float n) {
+  const float q = S / n;
+  const uint32_t u = __float_as_uint(q);
+  const uint32_t low = u & 0xffffu;
+  uint32_t up;
+  if (low == 0x8000u) {
+    const float res = fmaf(-q, n, S);
+    up = (res == 0.f) ? ((u >> 16) & 1u) : (((res > 0.f) == (q > 0.f)) ? 1u : 0u);
+  } else {
+    up = low > 0x8000u;
+  }
+  return ((u >> 16) + up) & 0xffffu;
+}
+
+
+// acc[0..8)/n as 8 packed bf16, ONE nearest-even rounding.  Fast path: multiply by the fp32
+// reciprocal and let the packed converter round.  For n a power of two the product is exact,
+// midpoints included.  Otherwise the product q is within 3 ulp(fp32) of the true quotient: if its
+// low 16 bits are farther than that from a bf16 midpoint, or if q*n == acc exactly (sums of bf16
+// values divide evenly quite often, and exact midpoints are then rounded correctly by the
+// converter), the result is the correctly rounded quotient; the few remaining elements take the
+// exact path.
+__device__ __forceinline__ uint4 round_div_pack_bf16(const float* acc, int n) {
+  const float fn = (float)n;
+  const float rcp = __builtin_amdgcn_rcpf(fn);   // exact for powers of two, 1 ulp otherwise
+  const bool pow2 = (n & (n - 1)) == 0;          // then acc*rcp IS the quotient: no second rounding
+  float qv[8];
+  bool risky = false;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    qv[i] = acc[i] * rcp;
+    const bool window = ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
+    risky |= window & (fmaf(-qv[i], fn, acc[i]) != 0.f);
+  }
+  risky &= !pow2;
+  uint32_t w[4];
+  if (__any(risky)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = div_round_bf16(acc[2 * i], fn) | (div_round_bf16(acc[2 * i + 1], fn) << 16);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f32x2 v = {qv[2 * i], qv[2 * i + 1]};
+      w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    }
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// 16-byte load at a 32-bit byte offset from a workgroup-uniform base (the compiler then uses the
+// scalar-base + vector-offset addressing form: no 64-bit address arithmetic per lane).
+__device__ __forceinline__ uint4 ldg16(const void* base, uint32_t byte_off) {
+  return *reinterpret_cast<const uint4*>(static_cast<const char*>(base) + byte_off);
+}
+__device__ __forceinline__ void stg16(void* base, uint32_t byte_off, const uint4& v) {
+  *reinterpret_cast<uint4*>(static_cast<char*>(base) + byte_off) = v;
+}
+
+// acc += w * (8 bf16 of u), element order = memory order.  Integer weights up to 256 are exact in
+// bf16, so each element is ONE v_dot2 of the packed pair with (w, 0) or (0, w): the product is
+// exact, the other lane of the pair contributes an exact zero, and the single fp32 rounding is
+// that of fmaf (for finite data; a non-finite element also poisons its pair partner).  Larger
+// weights take the unpack + fma route.
+__device__ __forceinline__ void fma_bf16x8(float* acc, const uint4& u, int w) {
+  const uint32_t x[4] = {u.x, u.y, u.z, u.w};
+  if (__any(w > 256)) {
+    const float fw = (float)w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc[2 * i] = fmaf(fw, __uint_as_float(x[i] << 16), acc[2 * i]);
+      acc[2 * i + 1] = fmaf(fw, __uint_as_float(x[i] & 0xffff0000u), acc[2 * i + 1]);
+    }
+  } else {
+    const uint32_t wb = __float_as_uint((float)w);
+    const bf16x2 w_lo = __builtin_bit_cast(bf16x2, wb >> 16), w_hi = __builtin_bit_cast(bf16x2, wb & 0xffff0000u);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bf16x2 xi = __builtin_bit_cast(bf16x2, x[i]);
+      acc[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(xi, w_lo, acc[2 * i], false);
+      acc[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(xi, w_hi, acc[2 * i + 1], false);
+    }
+  }
+}
+
+}  // namespace ckv

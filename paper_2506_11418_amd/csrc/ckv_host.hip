@@ -1,6 +1,7 @@
 // Host driver of libckv: argument validation, the rounds schedule (Algorithm 1's loop after
 // prefill), workspace carving, kernel sequencing and optional per-kernel timing.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <string>
@@ -248,26 +249,43 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
   const void* curV = V;
   const int32_t* curDeg = deg_in;
   TensorView curView = view_of(in);
+  // The single-pass two-round kernel is bit-identical to the round-by-round path but, at one
+  // workgroup per CU, currently slower on MI355X; it runs only when CKV_ENABLE_FUSED=1.
+  const char* fuse_env = getenv("CKV_ENABLE_FUSED");
+  const bool allow_fused = fuse_env && fuse_env[0] == '1';
   for (int j = 0; j < plan.n_rounds; ++j) {
-    const int len = plan.round_len[j], next = plan.round_len[j + 1];
-    const bool last = (j == plan.n_rounds - 1);
-    hipError_t err = launch_match(curK, in->dtype, in->dim, curView, n_bh, len, p->chunk, dst, score, s);
-    if (err != hipSuccess) return hip_status(err);
-    void* oK = last ? K_out : ws + w.K[j & 1];
-    void* oV = last ? V_out : ws + w.V[j & 1];
-    int32_t* oDeg = last ? deg_out : reinterpret_cast<int32_t*>(ws + w.deg[j & 1]);
+    const int len = plan.round_len[j];
+    // rounds j and j+1 in one pass when the first merges every edge and the shape has a kernel
+    const bool fuse = allow_fused && j + 1 < plan.n_rounds &&
+                      fused2_supported(in->dtype, in->dim, p->chunk, len, plan.round_r[j]) &&
+                      curView.stride_s <= (1 << 18) && out->stride_s <= (1 << 18);
+    const int jo = fuse ? j + 1 : j;                 // index of the round whose output is produced
+    const int next = plan.round_len[jo + 1];
+    const bool last = (jo == plan.n_rounds - 1);
+    void* oK = last ? K_out : ws + w.K[jo & 1];
+    void* oV = last ? V_out : ws + w.V[jo & 1];
+    int32_t* oDeg = last ? deg_out : reinterpret_cast<int32_t*>(ws + w.deg[jo & 1]);
     const TensorView oView = last ? view_of(out) : compact_view(in->heads, next, in->dim);
     const int64_t oDegStride = last ? out->seq : next;
     int32_t* map = nullptr;
     if (assign) map = (j == 0) ? assign : reinterpret_cast<int32_t*>(ws + w.map);
-    err = launch_merge(curK, curV, curDeg, in->dtype, in->dim, curView, n_bh, len, p->chunk, plan.round_r[j],
-                       dst, score, oK, oV, oDeg, oView, oDegStride, next, map, s);
+    hipError_t err;
+    if (fuse) {
+      err = launch_fused2(curK, curV, curDeg, curView, n_bh, len, plan.round_r[j + 1], oK, oV, oDeg, oView,
+                          oDegStride, map, s);
+    } else {
+      err = launch_match(curK, in->dtype, in->dim, curView, n_bh, len, p->chunk, dst, score, s);
+      if (err != hipSuccess) return hip_status(err);
+      err = launch_merge(curK, curV, curDeg, in->dtype, in->dim, curView, n_bh, len, p->chunk, plan.round_r[j],
+                         dst, score, oK, oV, oDeg, oView, oDegStride, next, map, s);
+    }
     if (err != hipSuccess) return hip_status(err);
     if (assign && j > 0) {
       err = launch_compose(assign, map, n_bh, in->seq, len, s);
       if (err != hipSuccess) return hip_status(err);
     }
     curK = oK; curV = oV; curDeg = oDeg; curView = oView;
+    j = jo;
   }
   return CKV_OK;
 }

@@ -51,6 +51,13 @@ hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int
                         int32_t* deg_out, TensorView out, int64_t deg_out_stride, int out_seq,
                         int32_t* map_out, hipStream_t st);
 
+// Two rounds in one pass (first round r = 1, bf16, dim 128, chunk 1024, seq a multiple of 2048):
+// same outputs as launch_match + launch_merge twice; map_out gets the composition of both rounds.
+bool fused2_supported(int dtype, int dim, int chunk, int seq, float r0);
+hipError_t launch_fused2(const void* K, const void* V, const int32_t* deg_in, TensorView in, int n_bh, int seq,
+                         float r1, void* K_out, void* V_out, int32_t* deg_out, TensorView out,
+                         int64_t deg_out_stride, int32_t* map_out, hipStream_t st);
+
 // assign[bh, t] = map[bh, assign[bh, t]] for t < seq0.
 hipError_t launch_compose(int32_t* assign, const int32_t* map, int n_bh, int seq0, int map_len,
                           hipStream_t st);

@@ -14,81 +14,16 @@
 #include <type_traits>
 
 #include "ckv_internal.h"
+#include "ckv_device.h"
 
 namespace ckv {
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kRowsPerWave = 64;                 // two 32-row MFMA tiles
 constexpr int kABlock = kWaves * kRowsPerWave;   // A rows per workgroup
 constexpr int kPanel = 128;                      // B rows per LDS panel
-
-union Piece {   // 16 bytes = 8 bf16
-  uint4 u;
-  bf16x8 v;
-  bf16x2 p[4];
-};
-
-__device__ inline float sumsq8(const Piece& x) {
-  float s = 0.f;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_fdot2_f32_bf16(x.p[i], x.p[i], s, false);
-  return s;
-}
-
-// 1/sqrt(ss) by the hardware reciprocal square root (1 ulp), 0 for a zero key.
-__device__ inline float inv_norm(float ss) { return ss > 0.f ? __builtin_amdgcn_rsqf(ss) : 0.f; }
-
-// Sum over the LANES lanes (8 or 16, aligned) that hold one key row, with DPP adds: xor 1 and
-// xor 2 inside each quad, then the mirrored half-row and row (after the quad steps all lanes of
-// a quad agree, so a mirror brings in exactly the other quad's / other half's sum).
-template <int LANES>
-__device__ __forceinline__ float row_sum(float x) {
-  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
-  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
-  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));
-  if (LANES == 16)
-    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));
-  return x;
-}
-
-// Map dispatch order to logical work so that the 8 XCDs (which receive consecutive workgroup ids
-// round-robin) each walk a contiguous range: neighbours in the range (the A blocks of one chunk,
-// adjacent chunks) then share an L2.
-__device__ inline int xcd_remap(int id, int per_xcd) { return (id & 7) * per_xcd + (id >> 3); }
-
-// Fold one 32x32 tile of S^T into the running (max, argmax) of this lane's A row.  sc = acc/|k_j|
-// (the row's own 1/|k_i| > 0 cannot change the argmax and is applied at the end).  Tiles arrive in
-// rotated order, so an equal maximum from a tile of LOWER B indices also replaces the incumbent:
-// the result is the lowest index among all maxima, whatever the visiting order.
-template <bool RAGGED>
-__device__ __forceinline__ void tile_argmax(const f32x16& acc, const f32x4 (&ib)[4], int jbase, int half,
-                                            int valid, float& best, int& bestj) {
-  float sc[16];
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    sc[r] = acc[r] * ib[r >> 2][r & 3];
-    if (RAGGED && (8 * (r >> 2) + 4 * half + (r & 3)) >= valid) sc[r] = -INFINITY;
-  }
-  float mt = __builtin_fmaxf(sc[0], sc[1]);
-#pragma unroll
-  for (int r = 2; r < 16; r += 2) mt = __builtin_fmaxf(__builtin_fmaxf(mt, sc[r]), sc[r + 1]);
-  const bool upd = (mt > best) | ((mt == best) & (jbase < bestj));
-  if (__any(upd)) {
-    int idx = 0;
-#pragma unroll
-    for (int r = 15; r >= 0; --r) idx = (sc[r] == mt) ? r : idx;
-    const int j = jbase + ((idx >> 2) << 3) + (half << 2) + (idx & 3);
-    best = upd ? mt : best;
-    bestj = upd ? j : bestj;
-  }
-}
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(

@@ -10,32 +10,13 @@
 // Rows are then produced gather-style: 16-byte pieces, one row per group of row_bytes/16 lanes,
 // fp32 accumulation for bf16 (fp64 for fp32 storage), one rounding to the storage type.
 #include "ckv_internal.h"
+#include "ckv_device.h"
 
 namespace ckv {
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxHalf = 1024;  // max |A| = |B| (chunk <= 2048)
-
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-
-// Quotient S/n rounded to bf16 with a single nearest-even rounding: the fp32 quotient is
-// correctly rounded, so a second rounding can only go wrong when it sits exactly on a bf16
-// midpoint; the sign of the exact residual S - q*n then says on which side the true value lies.
-__device__ inline uint32_t div_round_bf16(float S, float n) {
-  const float q = S / n;
-  const uint32_t u = __float_as_uint(q);
-  const uint32_t low = u & 0xffffu;
-  uint32_t up;
-  if (low == 0x8000u) {
-    const float res = fmaf(-q, n, S);
-    up = (res == 0.f) ? ((u >> 16) & 1u) : (((res > 0.f) == (q > 0.f)) ? 1u : 0u);
-  } else {
-    up = low > 0x8000u;
-  }
-  return ((u >> 16) + up) & 0xffffu;
-}
 
 __device__ inline int block_exclusive_scan(int v, int* s_wave_tot, int* total) {
   // 256 threads = 4 waves
@@ -70,43 +51,9 @@ struct Row<__bf16> {
   typedef uint4 Raw;
   __device__ static Raw load_raw(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
   __device__ static void store_raw(__bf16* p, const Raw& r) { *reinterpret_cast<uint4*>(p) = r; }
-  __device__ static void fma_into(Acc* acc, const Raw& u, Acc w) {
-    const uint32_t x[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc[2 * i] = fmaf(w, __uint_as_float(x[i] << 16), acc[2 * i]);
-      acc[2 * i + 1] = fmaf(w, __uint_as_float(x[i] & 0xffff0000u), acc[2 * i + 1]);
-    }
-  }
-  // acc/n, one rounding to bf16.  Fast path: multiply by the fp32 reciprocal and let the packed
-  // converter round (nearest-even).  For n a power of two the product is exact, midpoints
-  // included.  Otherwise it is within 3 ulp(fp32) of the true quotient, so whenever its low 16
-  // bits are farther than that from a bf16 midpoint the result is the correctly rounded quotient;
-  // the few elements inside the window take the exact path.
+  __device__ static void fma_into(Acc* acc, const Raw& u, int w) { fma_bf16x8(acc, u, w); }
   __device__ static void store_div(__bf16* p, const Acc* acc, int n) {
-    const float fn = (float)n;
-    const float rcp = __builtin_amdgcn_rcpf(fn);   // exact for powers of two, 1 ulp otherwise
-    const bool pow2 = (n & (n - 1)) == 0;          // then acc*rcp IS the quotient: no second rounding
-    float qv[8];
-    bool risky = false;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      qv[i] = acc[i] * rcp;
-      risky |= ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
-    }
-    risky &= !pow2;
-    uint32_t w[4];
-    if (__any(risky)) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) w[i] = div_round_bf16(acc[2 * i], fn) | (div_round_bf16(acc[2 * i + 1], fn) << 16);
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const f32x2 v = {qv[2 * i], qv[2 * i + 1]};
-        w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-      }
-    }
-    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    *reinterpret_cast<uint4*>(p) = round_div_pack_bf16(acc, n);
   }
 };
 
@@ -117,7 +64,8 @@ struct Row<float> {
   typedef float4 Raw;
   __device__ static Raw load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
   __device__ static void store_raw(float* p, const Raw& r) { *reinterpret_cast<float4*>(p) = r; }
-  __device__ static void fma_into(Acc* acc, const Raw& u, Acc w) {
+  __device__ static void fma_into(Acc* acc, const Raw& u, int wi) {
+    const double w = (double)wi;
     acc[0] += w * (double)u.x; acc[1] += w * (double)u.y; acc[2] += w * (double)u.z; acc[3] += w * (double)u.w;
   }
   __device__ static void store_div(float* p, const Acc* acc, int n) {
@@ -341,18 +289,18 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       Acc ak[E], av[E];
 #pragma unroll
       for (int e = 0; e < E; ++e) { ak[e] = 0; av[e] = 0; }
-      Row<T>::fma_into(ak, kb[u], (Acc)du[u]);
-      Row<T>::fma_into(av, vb[u], (Acc)du[u]);
-      Row<T>::fma_into(ak, km[u], (Acc)dm[u]);
-      Row<T>::fma_into(av, vm[u], (Acc)dm[u]);
+      Row<T>::fma_into(ak, kb[u], du[u]);
+      Row<T>::fma_into(av, vb[u], du[u]);
+      Row<T>::fma_into(ak, km[u], dm[u]);
+      Row<T>::fma_into(av, vm[u], dm[u]);
       int ndeg = du[u] + dm[u];
       for (int q = 1; q < nmem[u]; ++q) {
         const int ua = 2 * (int)s_members[first[u] + q];
         const int da = dseq ? dseq[ua] : 1;
         const Raw kx = Row<T>::load_raw(Kin + (int64_t)ua * in.stride_s);
         const Raw vx = Row<T>::load_raw(Vin + (int64_t)ua * in.stride_s);
-        Row<T>::fma_into(ak, kx, (Acc)da);
-        Row<T>::fma_into(av, vx, (Acc)da);
+        Row<T>::fma_into(ak, kx, da);
+        Row<T>::fma_into(av, vx, da);
         ndeg += da;
       }
       Row<T>::store_div(Ko + (int64_t)o * out.stride_s, ak, ndeg);

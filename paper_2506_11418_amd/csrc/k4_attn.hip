@@ -4,8 +4,6 @@
 // 16-byte loads (one row per group of row_bytes/16 lanes), serves all G query heads of its KV head
 // from registers, keeps an online softmax in the exp2 domain, and writes (max, sum, o) partials;
 // a second small kernel merges the partials with the usual log-sum-exp rescaling.
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "ckv_internal.h"
@@ -333,7 +331,6 @@ int attn_splits(int n_b, int kv_heads, int seq) {
   if (cap > 1024) cap = 1024;   // the combine kernel keeps one weight per split in LDS
   if (want > cap) want = cap;
   if (want < 1) want = 1;
-  if (const char* e = getenv("CKV_TUNE_ATTN_SPLITS")) { int v = atoi(e); if (v >= 1 && v <= 1024) want = v; }
   return want;
 }
 

@@ -213,3 +213,63 @@ def test_runtime_argument_errors():
     with pytest.raises(ckv.CkvError) as e:
         ckv.compress(K96, K96.clone(), 16, rounds=[1.0])
     assert e.value.status == -5                                  # head_dim without a kernel
+
+
+# ---- the two-rounds-in-one-pass kernel ----------------------------------------------------------
+@pytest.mark.parametrize("rounds,use_deg", [
+    ([1.0, 1.0], False),
+    ([1.0, 0.5], False),
+    ([1.0, 0.0], False),
+    ([1.0, 1.0, 1.0], False),          # fused pair + a third separate round
+    ([0.5, 1.0, 1.0], False),          # fused pair fed by a separate round (incoming degrees > 1)
+    ([1.0, 0.7], True),
+])
+def test_fused_two_round_kernel_is_bit_identical_to_separate_rounds(rounds, use_deg):
+    """With CKV_ENABLE_FUSED=1, chunk 1024 / bf16 / dim 128 / length a multiple of 2048 and a first
+    round with r = 1 take the single-pass kernel; it must reproduce the round-by-round path bit
+    for bit (and that path is checked against the oracle above)."""
+    import os
+    _say(f"fused2 rounds={rounds} deg={use_deg}")
+    seq = 8192 if rounds[0] != 1.0 else 4096
+    K, V, _ = kv_host(21, 3, seq, 128, "bf16", alpha=0.9, n_outlier=4)
+    K, V = K.to(DEV), V.to(DEV)
+    deg = None
+    if use_deg:
+        deg = torch.from_numpy(np.random.default_rng(1).integers(1, 6, (1, 3, seq)).astype(np.int32)).to(DEV)
+    ref = ckv.compress(K, V, 1024, rounds=rounds, deg=deg)
+    os.environ["CKV_ENABLE_FUSED"] = "1"
+    try:
+        got = ckv.compress(K, V, 1024, rounds=rounds, deg=deg)
+        # the fused kernel really ran: its name shows up in the library's kernel timing
+        ckv.timing_reset()
+        ckv.timing_enable(True)
+        ckv.compress(K, V, 1024, rounds=rounds, deg=deg)
+        torch.cuda.synchronize()
+        ckv.timing_enable(False)
+        assert "fused2_bf16" in ckv.timing_read()
+    finally:
+        del os.environ["CKV_ENABLE_FUSED"]
+    torch.cuda.synchronize()
+    names = ["K'", "V'", "deg'", "assign"]
+    for n, a, b in zip(names, got, ref):
+        assert a.shape == b.shape, n
+        assert torch.equal(a, b), f"{n} differs between the fused and the round-by-round path"
+
+
+def test_fused_kernel_on_duplicate_keys():
+    _say("fused2 duplicate keys")
+    k = torch.randn(128, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
+    K = k.repeat(1, 1, 4096, 1).contiguous().to(DEV)
+    V = torch.randn((1, 1, 4096, 128), generator=torch.Generator().manual_seed(6)).to(torch.bfloat16).to(DEV)
+    import os
+    os.environ["CKV_ENABLE_FUSED"] = "1"
+    try:
+        gK, gV, gdeg, gas = ckv.compress(K, V, 1024, retain_ratio=0.25)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["CKV_ENABLE_FUSED"]
+    assert torch.equal(gK, k.to(DEV).expand_as(gK))
+    ref = oracle.compress(f64(K[0, 0]), f64(V[0, 0]), 1024, [1.0, 1.0], "bf16")
+    assert np.array_equal(i64(gas[0, 0]), ref["assign"])
+    assert np.array_equal(i64(gdeg[0, 0]), ref["deg"])
+    assert np.array_equal(f64(gV[0, 0]), ref["V"])
