@@ -103,7 +103,7 @@ __device__ inline uint32_t div_round_bf16(float S, float n) {
 // exact path.
 __device__ __forceinline__ uint4 round_div_pack_bf16(const float* acc, int n) {
   const float fn = (float)n;
-  const float rcp = __builtin_amdgcn_rcpf(fn);   // exact for powers of two, 1 ulp otherwise
+  const float rcp = 1.0f / fn;   // correctly rounded: quotients that divide evenly then come out exact
   const bool pow2 = (n & (n - 1)) == 0;          // then acc*rcp IS the quotient: no second rounding
   float qv[8];
   bool risky = false;
