@@ -26,6 +26,16 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 
+# HBM bytes per launch of a kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (one counter per
+# run), each scaled by what the same counter reads for the library's plain row-copy kernel of known
+# size; see profiles/bench_config3_hbm_traffic.txt for the runs and the factors.  Filled in by hand
+# from those runs: {(workload, kernel): bytes per launch averaged over the launches of one step}.
+MEASURED_TRAFFIC = {
+    ("config3", "merge_bf16"): int((6349556.6 * 2.0 + 6475060.0) * 1024),
+    ("config3", "match_bf16"): int((4310969.1 * 2.0 + 98304.0) * 1024),
+    ("config3", "attn_partial_bf16"): int((66219.4 * 2.0 + 1040.4) * 1024),
+}
+
 WORKLOADS = {
     # benchmark configs[2]: full-model prefill compression, Llama-3-8B KV shape, 128k tokens
     "config3": dict(layers=32, kv_heads=8, q_heads=32, dim=128, seq=131072, chunk=1024, retain=0.25,
@@ -81,7 +91,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config3", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--stage", default="all", choices=["all", "match", "compress", "decode"],
+    ap.add_argument("--stage", default="all", choices=["all", "match", "compress", "decode", "copy"],
                     help="time only one stage of the path (kernel tuning / profiling); the JSON line is "
                          "the full contract only for 'all'")
     ap.add_argument("--seed", type=int, default=2024)
@@ -127,6 +137,9 @@ def main():
     attn_lay = ckv.layout_of(K_out[0:1])
     attn_ws = torch.empty(ckv.decode_attn_workspace(attn_lay, Hq), dtype=torch.uint8, device=dev)
     o = torch.empty((Ly, 1, Hq, D), dtype=torch.bfloat16, device=dev)
+    if args.stage == "copy":
+        K_copy, V_copy = torch.empty_like(sets[0][0]), torch.empty_like(sets[0][1])
+        deg_copy = torch.empty((Ly, H, S), dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * args.steps)]
@@ -137,6 +150,8 @@ def main():
             ev[3 * i].record()
         if args.stage == "match":
             ckv.match(K, cfg["chunk"])
+        elif args.stage == "copy":      # zero rounds: a plain row copy of known size (counter calibration)
+            ckv.compress(K, V, cfg["chunk"], retain_ratio=1.0, out=(K_copy, V_copy, deg_copy, assign), workspace=ws)
         elif args.stage != "decode" or i == 0:
             ckv.compress(K, V, cfg["chunk"], retain_ratio=cfg["retain"], out=(K_out, V_out, deg_out, assign),
                          workspace=ws)
@@ -167,7 +182,7 @@ def main():
     dec_ms = float(np.mean([ev[3 * i + 1].elapsed_time(ev[3 * i + 2]) for i in range(args.steps)]))
 
     # ---- per-kernel roofline figures ------------------------------------------------------------
-    work = algorithmic_work(cfg, plan)
+    work = algorithmic_work(cfg, plan, fused="fused2_bf16" in ktimes)
     kernels = {}
     for name, (tot_ms, launches) in ktimes.items():
         per_step_ms = tot_ms / args.steps
@@ -190,9 +205,11 @@ def main():
         ach = one["match_bf16"] / (kernels["match_bf16"]["ms_per_step"] * 1e-3) / 1e12
         kernels["match_bf16"].update(achieved=round(ach, 1), frac=round(ach / PEAK_BF16_TFLOPS, 4))
     hot = [k for k in kernels if k in work and "bound" in kernels[k]]
-    dom = max(hot, key=lambda k: kernels[k]["ms_per_step"])
-    roofline = {"kernel": dom, **{k: kernels[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")},
-                "traffic": None}
+    roofline = None
+    if hot:
+        dom = max(hot, key=lambda k: kernels[k]["ms_per_step"])
+        roofline = {"kernel": dom, **{k: kernels[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")},
+                    "traffic": MEASURED_TRAFFIC.get((args.workload, dom))}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample ---------------------------
     cpu = None
@@ -203,10 +220,12 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = len(os.sched_getaffinity(0))
-        n_heads = 2
-        Kh = sets[0][0][0, :n_heads].to("cpu").to(torch.float64).numpy()
-        Vh = sets[0][1][0, :n_heads].to("cpu").to(torch.float64).numpy()
-        qh = q[0, 0, : n_heads * (Hq // H)].to("cpu").to(torch.float64).numpy()
+        n_heads = 16
+        n_heads = min(n_heads, Ly * H)
+        Kh = sets[0][0].reshape(Ly * H, S, D)[:n_heads].to("cpu").to(torch.float64).numpy()
+        Vh = sets[0][1].reshape(Ly * H, S, D)[:n_heads].to("cpu").to(torch.float64).numpy()
+        qh = torch.randn((n_heads * (Hq // H), D), generator=torch.Generator().manual_seed(args.seed)).to(
+            torch.bfloat16).to(torch.float64).numpy()
         c0 = time.perf_counter()
         outs = [oracle.compress(Kh[h], Vh[h], cfg["chunk"], plan.round_r, "bf16") for h in range(n_heads)]
         oracle.app_attn(qh, np.stack([x["K"] for x in outs]), np.stack([x["V"] for x in outs]),
