@@ -237,6 +237,35 @@ def main():
                "sample": f"{n_heads} of {Ly * H} (layer, KV head) sequences of {S} tokens: oracle.compress "
                          f"(rounds {plan.round_r}) + oracle.app_attn, {c1 - c0:.1f} s; scaled to whole-model tokens"}
 
+    # ---- context figure: one layer of the batch-16 serving shape (BASELINE configs[3]) ------------
+    # 16 sequences x 8 KV heads x 8192 centroids (32768 tokens at 25%), 32 query heads; kernel time
+    # from the library's events.  Not part of `value`.
+    serving = None
+    if args.stage == "all":
+        Bs, Ls = 16, 8192
+        gK = torch.randn((Bs, H, Ls, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        gV = torch.randn((Bs, H, Ls, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        gq = torch.randn((Bs, Hq, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        gdeg = torch.randint(1, 9, (Bs, H, Ls), generator=gen, device=dev, dtype=torch.int32)
+        go = torch.empty_like(gq)
+        gws = torch.empty(ckv.decode_attn_workspace(ckv.layout_of(gK), Hq), dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            ckv.decode_attn(gq, gK, gV, deg=gdeg, out=go, workspace=gws)
+        torch.cuda.synchronize()
+        ckv.timing_reset()
+        ckv.timing_enable(True)
+        for _ in range(20):
+            ckv.decode_attn(gq, gK, gV, deg=gdeg, out=go, workspace=gws)
+        torch.cuda.synchronize()
+        ckv.timing_enable(False)
+        tt = ckv.timing_read()
+        us = tt["attn_partial_bf16"][0] / tt["attn_partial_bf16"][1] * 1e3
+        byts = Bs * H * Ls * (2 * D * 2 + 4)
+        serving = {"shape": f"batch {Bs} x {H} KV heads x {Ls} centroids x {D}, {Hq} q heads, bf16, one layer",
+                   "attn_partial_us": round(us, 2), "GBps": round(byts / us / 1e3, 1),
+                   "frac_of_hbm_peak": round(byts / us / 1e3 / PEAK_HBM_GBS, 4),
+                   "attn_combine_us": round(tt["attn_combine"][0] / tt["attn_combine"][1] * 1e3, 2)}
+
     dec_bytes = work["attn_partial_bf16"]
     out = {
         "metric": "KV tokens compressed/sec + decode-attn HBM GB/s (fraction of MI355X peak)",
@@ -253,7 +282,7 @@ def main():
         "compress_tokens_per_s": round(S / (comp_ms * 1e-3), 1),
         "compress_head_tokens_per_s": round(S * Ly * H / (comp_ms * 1e-3), 1),
         "decode_attn_GBps_wall": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
-        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "decode_serving_layer": serving, "cpu_baseline": cpu,
     }
     if args.stage != "all":
         out["stage"] = args.stage

@@ -88,3 +88,74 @@ def test_decode_attention_over_the_compressed_layer(full_cache, layer):
     torch.cuda.synchronize()
     ref = oracle.app_attn(f64(q[0]), f64(cK[layer]), f64(cV[layer]), i64(cdeg[layer]))
     assert_rows_close(f64(o[0]), ref, ATTN_TOL, f"layer {layer}")
+
+
+# ---- serving decode shape (batch 16, pre-compressed caches, appended tokens) --------------------
+def test_serving_decode_batch16_with_appended_tokens():
+    """16 sequences of 32768 tokens compressed to 25%, a few decoded tokens appended with degree 1
+    (capacity 8192 + 128), per-sequence lengths; compressed (with degrees) and uncompressed
+    (degrees = NULL) attention against the oracle on sampled sequences."""
+    _say("serving decode: batch 16")
+    B, H, S, CAP = 16, HEADS, 32768, 8192 + 128
+    K = torch.empty((B, H, S, DIM), dtype=torch.bfloat16, device=DEV)
+    V = torch.empty_like(K)
+    for b in range(B):
+        kv_device(4242, H, S, DIM, "bf16", 0.9, 4, layer=b, device=DEV, out_k=K[b], out_v=V[b])
+    cK = torch.zeros((B, H, CAP, DIM), dtype=torch.bfloat16, device=DEV)
+    cV = torch.zeros_like(cK)
+    cdeg = torch.ones((B, H, CAP), dtype=torch.int32, device=DEV)
+    ckv.compress(K, V, CHUNK, retain_ratio=RHO, out=(cK, cV, cdeg, None))       # rows [0, 8192) of the padded cache
+    gen = torch.Generator(device=DEV).manual_seed(9)
+    n_new = torch.randint(1, 129, (B,), generator=gen, device=DEV)
+    cK[:, :, 8192:] = torch.randn((B, H, 128, DIM), generator=gen, device=DEV).to(torch.bfloat16)
+    cV[:, :, 8192:] = torch.randn((B, H, 128, DIM), generator=gen, device=DEV).to(torch.bfloat16)
+    lens = (8192 + n_new).to(torch.int32)
+    q = torch.randn((B, QHEADS, DIM), generator=gen, device=DEV).to(torch.bfloat16)
+    o = ckv.decode_attn(q, cK, cV, lens=lens, deg=cdeg, out_dtype=torch.float32)
+    o_full = ckv.decode_attn(q, K, V, out_dtype=torch.float32)                  # uncompressed baseline
+    torch.cuda.synchronize()
+    assert int(cdeg[:, :, :8192].sum()) == B * H * S and bool((cdeg[:, :, 8192:] == 1).all())
+    for b in (0, 7, 15):
+        ref = oracle.app_attn(f64(q[b]), f64(cK[b]), f64(cV[b]), i64(cdeg[b]), int(lens[b]))
+        assert_rows_close(f64(o[b]), ref, ATTN_TOL, f"compressed b{b}")
+        ref_full = oracle.app_attn(f64(q[b]), f64(K[b]), f64(V[b]))
+        assert_rows_close(f64(o_full[b]), ref_full, ATTN_TOL, f"uncompressed b{b}")
+
+
+# ---- extreme context: 1M tokens, chunk 2048 ------------------------------------------------------
+def test_extreme_context_chunk2048():
+    """Two KV heads of a 1 048 576-token cache (alpha 0.95), chunk 2048, retain 25%.  Invariants on
+    everything; a 65536-token prefix (closed under both rounds: 16 round-1 chunks) is checked round
+    by round against the oracle and must equal the big call's prefix bit for bit; then one decode
+    step over the 262144 centroids."""
+    _say("extreme context: 1M tokens, chunk 2048")
+    H, S, C = 2, 1048576, 2048
+    K = torch.empty((1, H, S, DIM), dtype=torch.bfloat16, device=DEV)
+    V = torch.empty_like(K)
+    kv_device(555, H, S, DIM, "bf16", 0.95, 4, layer=0, device=DEV, out_k=K[0], out_v=V[0])
+    cK, cV, cdeg, assign = ckv.compress(K, V, C, retain_ratio=RHO)
+    torch.cuda.synchronize()
+    L2 = S // 4
+    assert cK.shape == (1, H, L2, DIM)
+    assert torch.equal(cdeg.sum(dim=-1), torch.full((1, H), S, dtype=torch.int64, device=DEV))
+    counts = torch.zeros((H, L2), dtype=torch.int32, device=DEV)
+    counts.scatter_add_(1, assign[0].to(torch.int64), torch.ones((H, S), dtype=torch.int32, device=DEV))
+    assert torch.equal(counts, cdeg[0])
+    P = 65536
+    h = 1
+    curK, curV, curdeg = K[:, h:h + 1, :P].contiguous(), V[:, h:h + 1, :P].contiguous(), None
+    for j, r in enumerate([1.0, 1.0]):
+        gK, gV, gdeg, gas = ckv.compress(curK, curV, C, rounds=[r], deg=curdeg)
+        torch.cuda.synchronize()
+        d_in = np.ones(curK.shape[2], dtype=np.int64) if curdeg is None else i64(curdeg[0, 0])
+        check_round(f64(curK[0, 0]), f64(curV[0, 0]), d_in, C, r, "bf16", f64(gK[0, 0]), f64(gV[0, 0]),
+                    i64(gdeg[0, 0]), i64(gas[0, 0]), what=f"1M prefix round {j}")
+        curK, curV, curdeg = gK, gV, gdeg
+    assert torch.equal(cK[0, h, :P // 4], curK[0, 0]) and torch.equal(cV[0, h, :P // 4], curV[0, 0])
+    assert torch.equal(cdeg[0, h, :P // 4], curdeg[0, 0])
+    gen = torch.Generator(device=DEV).manual_seed(11)
+    q = torch.randn((1, H * 4, DIM), generator=gen, device=DEV).to(torch.bfloat16)
+    o = ckv.decode_attn(q, cK, cV, deg=cdeg, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    ref = oracle.app_attn(f64(q[0]), f64(cK[0]), f64(cV[0]), i64(cdeg[0]))
+    assert_rows_close(f64(o[0]), ref, ATTN_TOL, "1M decode")
