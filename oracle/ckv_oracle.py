@@ -22,8 +22,9 @@ enumeration on chunks of <= 8 tokens (matching + selection); mass
 conservation, lossless merge of duplicated keys and scatter-mean from the
 assignment map (merge); textbook softmax attention at degree 1, the q = 0 mean
 and exactness on duplicate-key clusters (attention); the paper's KV-cache size
-column (budget arithmetic).  Parity unpinned: nothing in this file; the
-annealed-schedule stopping rule, global top-r and sink/recent handling are not
+column (budget arithmetic); sink / recent tokens bit-identical, the middle equal
+to a round on the slice alone (sinks and recents).  Parity unpinned: nothing in
+this file; the annealed-schedule stopping rule and global top-r are not
 implemented here.
 """
 from __future__ import annotations
@@ -87,6 +88,9 @@ def match(K: np.ndarray, c: int, tau: float = TAU):
       near_tie[i]  True when best and second-best differ by less than tau.
     """
     src, dst, score, near = [], [], [], []
+    if K.shape[0] == 0:
+        e = np.zeros(0, dtype=np.int64)
+        return e, e.copy(), np.zeros(0), np.zeros(0, dtype=bool)
     for g0, g1 in chunk_bounds(K.shape[0], c):
         a_off, b_off = alternating_partition(g1 - g0)
         if len(b_off) == 0:
@@ -174,12 +178,25 @@ def merge(K, V, deg, src, dst, keep, dtype: str):
             new_deg[retained].astype(np.int64), assign.astype(np.int64), Kc, Vc)
 
 
-def csm_round(K, V, deg, c: int, r: float, dtype: str, tau: float = TAU):
-    """One clustering round on one (layer, KV head) sequence: chunk, alternating
-    partition, cosine similarity, per-A argmax edge, per-chunk top-r, merge
-    (Sec. 5.2 + 5.3).  K, V: [s, d] fp64 holding storage-type values."""
-    src, dst, score, near = match(K, c, tau)
-    keep, cut_ties = select(src, dst, score, K.shape[0], c, r, tau)
+def clusterable_range(s: int, n_sink: int, n_recent: int):
+    """The first n_sink and the last n_recent tokens are kept out of the clustering (Sec. 5.2:
+    sinks and recent tokens are set aside before partitioning); chunks start right after the
+    sinks.  A cache no longer than n_sink + n_recent has nothing to cluster."""
+    if s <= n_sink + n_recent:
+        return 0, 0
+    return n_sink, s - n_recent
+
+
+def csm_round(K, V, deg, c: int, r: float, dtype: str, tau: float = TAU, n_sink: int = 0, n_recent: int = 0):
+    """One clustering round on one (layer, KV head) sequence: set sinks / recents aside, chunk
+    the rest, alternating partition, cosine similarity, per-A argmax edge, per-chunk top-r,
+    merge, and put the result back between the untouched sinks and recents (Sec. 5.2 + 5.3).
+    K, V: [s, d] fp64 holding storage-type values."""
+    lo, hi = clusterable_range(K.shape[0], n_sink, n_recent)
+    src, dst, score, near = match(K[lo:hi], c, tau)
+    keep, cut_ties = select(src, dst, score, hi - lo, c, r, tau)
+    src = src + lo
+    dst = np.where(dst >= 0, dst + lo, dst)
     Ko, Vo, dego, assign, Kx, Vx = merge(K, V, deg, src, dst, keep, dtype)
     return dict(K=Ko, V=Vo, deg=dego, assign=assign, src=src, dst=dst, score=score,
                 keep=keep, near_tie=near, cut_ties=cut_ties, K_exact=Kx, V_exact=Vx)
@@ -203,12 +220,13 @@ def direct_schedule(retain_ratio: float):
     return [1.0] * (J - 1) + [2.0 * (1.0 - rho * 2.0 ** (J - 1))]
 
 
-def round_lengths(s: int, c: int, rounds):
+def round_lengths(s: int, c: int, rounds, n_sink: int = 0, n_recent: int = 0):
     """Sequence length after each round (pure integer arithmetic)."""
     out = [s]
     for r in rounds:
-        n = 0
-        for g0, g1 in chunk_bounds(out[-1], c):
+        lo, hi = clusterable_range(out[-1], n_sink, n_recent)
+        n = out[-1] - (hi - lo)
+        for g0, g1 in chunk_bounds(hi - lo, c):
             L = g1 - g0
             n_a, n_b = (L + 1) // 2, L // 2
             n += L - (merge_count(r, n_a) if n_b > 0 else 0)
@@ -216,7 +234,7 @@ def round_lengths(s: int, c: int, rounds):
     return out
 
 
-def compress(K, V, c: int, rounds, dtype: str, deg=None, tau: float = TAU):
+def compress(K, V, c: int, rounds, dtype: str, deg=None, tau: float = TAU, n_sink: int = 0, n_recent: int = 0):
     """Repeat csm_round on the CURRENT cache with the same chunk size
     (Algorithm 1, the while-loop after prefill).  Degrees start at 1 and
     accumulate; the assignment maps compose.  Each round's rounded output is
@@ -226,7 +244,7 @@ def compress(K, V, c: int, rounds, dtype: str, deg=None, tau: float = TAU):
     assign = np.arange(s, dtype=np.int64)
     per_round = []
     for r in rounds:
-        res = csm_round(K, V, deg, c, r, dtype, tau)
+        res = csm_round(K, V, deg, c, r, dtype, tau, n_sink, n_recent)
         K, V, deg = res["K"], res["V"], res["deg"]
         assign = res["assign"][assign]
         per_round.append(res)

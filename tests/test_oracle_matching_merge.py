@@ -234,3 +234,43 @@ def test_budget_reproduces_the_papers_kv_cache_column(golden_dir):
         assert out == n // 4
         assert abs((n + 1024) * per_token / 2 ** 30 - float(full)) < 0.01           # printed to two decimals
         assert abs((out + 1024) * per_token / 2 ** 30 - float(comp)) < 0.01           # printed to two decimals
+
+
+# ---- attention sinks and recent tokens (Sec. 5.2 / 5.3) --------------------------------------
+def test_sinks_and_recents_bypass_the_clustering():
+    s, c, n1, n2 = 200, 32, 5, 11
+    K, V = _kv(41, s, 16)
+    K = K.astype(np.float32).astype(np.float64)
+    V = V.astype(np.float32).astype(np.float64)
+    deg = np.random.default_rng(2).integers(1, 4, s)
+    res = csm_round(K, V, deg, c, 0.75, "f32", n_sink=n1, n_recent=n2)
+    n_out = len(res["K"])
+    # sinks first, recents last, bit for bit, degrees untouched
+    assert np.array_equal(res["K"][:n1], K[:n1]) and np.array_equal(res["V"][:n1], V[:n1])
+    assert np.array_equal(res["K"][n_out - n2:], K[s - n2:]) and np.array_equal(res["V"][n_out - n2:], V[s - n2:])
+    assert np.array_equal(res["deg"][:n1], deg[:n1]) and np.array_equal(res["deg"][n_out - n2:], deg[s - n2:])
+    assert list(res["assign"][:n1]) == list(range(n1))
+    assert list(res["assign"][s - n2:]) == list(range(n_out - n2, n_out))
+    # no edge touches a sink or a recent token; chunks start right after the sinks
+    assert res["src"].min() >= n1 and res["src"].max() < s - n2
+    assert res["dst"].min() >= n1 and res["dst"].max() < s - n2
+    assert np.all((res["src"] - n1) // c == (res["dst"] - n1) // c)
+    assert res["src"][0] == n1 and (res["src"][0] - n1) % 2 == 0
+    # the middle is exactly a plain round on the slice alone
+    mid = csm_round(K[n1:s - n2], V[n1:s - n2], deg[n1:s - n2], c, 0.75, "f32")
+    assert np.array_equal(res["K"][n1:n_out - n2], mid["K"]) and np.array_equal(res["deg"][n1:n_out - n2], mid["deg"])
+    assert n_out == n1 + n2 + len(mid["K"]) == round_lengths(s, c, [0.75], n1, n2)[1]
+
+
+def test_sinks_and_recents_over_rounds_and_short_caches():
+    s, c, n1, n2 = 300, 64, 16, 64
+    K, V = _kv(42, s, 8)
+    out = compress(K, V, c, [1.0, 1.0], "f32", n_sink=n1, n_recent=n2)
+    lens = round_lengths(s, c, [1.0, 1.0], n1, n2)
+    assert len(out["K"]) == lens[-1] == n1 + n2 + (s - n1 - n2) // 4
+    assert np.array_equal(np.bincount(out["assign"]), out["deg"])
+    assert np.all(out["deg"][:n1] == 1) and np.all(out["deg"][-n2:] == 1)
+    # a cache no longer than sinks + recents is returned unchanged
+    short = compress(K[:70], V[:70], c, [1.0], "f32", n_sink=n1, n_recent=n2)
+    assert np.array_equal(short["K"], K[:70].astype(np.float32).astype(np.float64))
+    assert list(short["assign"]) == list(range(70))
