@@ -58,7 +58,12 @@ typedef struct {
                            Sec. 5.1), r = 1 for the first J-1 and r = 2(1 - rho*2^(J-1)) last.  */
   int32_t n_rounds;     /* > 0: run exactly these rounds with merge fractions r[0..n_rounds)     */
   float r[CKV_MAX_ROUNDS]; /* r_j in [0,1]: fraction of a chunk's candidate edges merged (5.3)   */
-  int32_t n_sink, n_recent; /* n1, n2 of Algorithm 1: reserved, must be 0 (CKV_EUNSUPPORTED)     */
+  int32_t n_sink, n_recent; /* n1, n2 of Algorithm 1 (Sec. 5.2), >= 0: in every round the first n1
+                               and the last n2 tokens of the current cache are set aside before
+                               chunking and copied unchanged (degree kept) to the head / tail of
+                               the round's output (Sec. 5.3); chunks, merge fractions and
+                               retain_ratio's schedule apply to the tokens between them.  A cache
+                               of at most n1+n2 tokens passes through a round unchanged.          */
 } ckv_params;
 
 typedef struct {

@@ -86,9 +86,10 @@ def layout_of(t: torch.Tensor) -> Layout:
                   _DT[t.dtype])
 
 
-def make_params(chunk: int, retain_ratio: float = 1.0, rounds: Optional[Sequence[float]] = None) -> Params:
+def make_params(chunk: int, retain_ratio: float = 1.0, rounds: Optional[Sequence[float]] = None,
+                n_sink: int = 0, n_recent: int = 0) -> Params:
     p = Params()
-    p.chunk, p.retain_ratio, p.n_sink, p.n_recent = chunk, retain_ratio, 0, 0
+    p.chunk, p.retain_ratio, p.n_sink, p.n_recent = chunk, retain_ratio, n_sink, n_recent
     if rounds is not None:
         if not 0 < len(rounds) <= MAX_ROUNDS:
             raise ValueError("rounds must have 1..8 entries")
@@ -139,15 +140,16 @@ def match(K: torch.Tensor, chunk: int):
 def compress(K: torch.Tensor, V: torch.Tensor, chunk: int, retain_ratio: float = 1.0,
              rounds: Optional[Sequence[float]] = None, deg: Optional[torch.Tensor] = None,
              want_assign: bool = True, out: Optional[tuple] = None,
-             workspace: Optional[torch.Tensor] = None):
+             workspace: Optional[torch.Tensor] = None, n_sink: int = 0, n_recent: int = 0):
     """ckv_compress: returns (K', V', deg', assign or None).  K, V: [B,H,S,D] on the GPU.
+    The first n_sink and last n_recent tokens bypass the clustering in every round.
 
     `out` may pass preallocated (K_out, V_out, deg_out, assign) and `workspace` a uint8 tensor, so
     that a timed loop allocates nothing."""
     lay = layout_of(K)
     if layout_of(V).dtype != lay.dtype or V.shape != K.shape:
         raise ValueError("K and V must have the same shape and dtype")
-    params = make_params(chunk, retain_ratio, rounds)
+    params = make_params(chunk, retain_ratio, rounds, n_sink, n_recent)
     pl = plan(lay, params)
     B, H, S, D = K.shape
     if out is None:

@@ -49,9 +49,20 @@ TensorView compact_view(int heads, int len, int dim) {
   return TensorView{(int64_t)heads * len * dim, (int64_t)len * dim, (int64_t)dim, heads};
 }
 
-int seq_after_round(int len, int chunk, float r) {
-  const int full = len / chunk, tail = len % chunk;
-  return full * chunk_out(chunk, r) + chunk_out(tail, r);
+// [lo, hi): the tokens of a cache of `len` tokens that take part in the clustering; the first n_sink
+// and the last n_recent are set aside (Sec. 5.2).  Nothing is clustered when len <= n_sink+n_recent.
+void clusterable(int len, int n_sink, int n_recent, int* lo, int* hi) {
+  if (len <= n_sink + n_recent) { *lo = 0; *hi = 0; return; }
+  *lo = n_sink;
+  *hi = len - n_recent;
+}
+
+int seq_after_round(int len, int chunk, float r, int n_sink, int n_recent) {
+  int lo, hi;
+  clusterable(len, n_sink, n_recent, &lo, &hi);
+  const int mid = hi - lo;
+  const int full = mid / chunk, tail = mid % chunk;
+  return (len - mid) + full * chunk_out(chunk, r) + chunk_out(tail, r);
 }
 
 struct Workspace {
@@ -84,7 +95,7 @@ int make_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan) {
   if (st != CKV_OK) return st;
   if (!p || !plan) return CKV_EINVAL;
   if (p->chunk < 2 || p->chunk > 2048 || (p->chunk & 1)) return CKV_EINVAL;
-  if (p->n_sink != 0 || p->n_recent != 0) return CKV_EUNSUPPORTED;
+  if (p->n_sink < 0 || p->n_recent < 0) return CKV_EINVAL;
   if (p->n_rounds < 0 || p->n_rounds > CKV_MAX_ROUNDS) return CKV_EINVAL;
   memset(plan, 0, sizeof(*plan));
   if (p->n_rounds > 0) {
@@ -105,7 +116,7 @@ int make_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan) {
   }
   plan->round_len[0] = in->seq;
   for (int j = 0; j < plan->n_rounds; ++j)
-    plan->round_len[j + 1] = seq_after_round(plan->round_len[j], p->chunk, plan->round_r[j]);
+    plan->round_len[j + 1] = seq_after_round(plan->round_len[j], p->chunk, plan->round_r[j], p->n_sink, p->n_recent);
   plan->out_seq = plan->round_len[plan->n_rounds];
   plan->workspace_bytes = carve(in, plan, p->chunk).total;
   return CKV_OK;
@@ -257,6 +268,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     const int len = plan.round_len[j];
     // rounds j and j+1 in one pass when the first merges every edge and the shape has a kernel
     const bool fuse = allow_fused && j + 1 < plan.n_rounds &&
+                      p->n_sink == 0 && p->n_recent == 0 &&
                       fused2_supported(in->dtype, in->dim, p->chunk, len, plan.round_r[j]) &&
                       curView.stride_s <= (1 << 18) && out->stride_s <= (1 << 18);
     const int jo = fuse ? j + 1 : j;                 // index of the round whose output is produced
@@ -269,15 +281,28 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     const int64_t oDegStride = last ? out->seq : next;
     int32_t* map = nullptr;
     if (assign) map = (j == 0) ? assign : reinterpret_cast<int32_t*>(ws + w.map);
-    hipError_t err;
+    int lo, hi;
+    clusterable(len, p->n_sink, p->n_recent, &lo, &hi);
+    const int mid = hi - lo;
+    hipError_t err = hipSuccess;
     if (fuse) {
       err = launch_fused2(curK, curV, curDeg, curView, n_bh, len, plan.round_r[j + 1], oK, oV, oDeg, oView,
                           oDegStride, map, s);
     } else {
-      err = launch_match(curK, in->dtype, in->dim, curView, n_bh, len, p->chunk, dst, score, s);
-      if (err != hipSuccess) return hip_status(err);
-      err = launch_merge(curK, curV, curDeg, in->dtype, in->dim, curView, n_bh, len, p->chunk, plan.round_r[j],
-                         dst, score, oK, oV, oDeg, oView, oDegStride, next, map, s);
+      if (mid > 0) {   // cluster tokens [lo, hi): the same kernels on a view that starts at token lo
+        const unsigned char* mK = static_cast<const unsigned char*>(curK) + (size_t)lo * curView.stride_s * e;
+        const unsigned char* mV = static_cast<const unsigned char*>(curV) + (size_t)lo * curView.stride_s * e;
+        err = launch_match(mK, in->dtype, in->dim, curView, n_bh, mid, p->chunk, dst, score, s);
+        if (err != hipSuccess) return hip_status(err);
+        err = launch_merge(mK, mV, curDeg ? curDeg + lo : nullptr, in->dtype, in->dim, curView, n_bh, mid, p->chunk,
+                           plan.round_r[j], dst, score, static_cast<unsigned char*>(oK) + (size_t)lo * oView.stride_s * e,
+                           static_cast<unsigned char*>(oV) + (size_t)lo * oView.stride_s * e, oDeg + lo, oView,
+                           oDegStride, map ? map + lo : nullptr, len, len, lo, s);
+        if (err != hipSuccess) return hip_status(err);
+      }
+      if (mid < len)   // sinks and recents (or a cache too short to cluster): straight copy
+        err = launch_edges(curK, curV, curDeg, curView, len, oK, oV, oDeg, oView, oDegStride, next, map,
+                           mid > 0 ? lo : len, mid > 0 ? len - hi : 0, n_bh, in->dim * e, e, s);
     }
     if (err != hipSuccess) return hip_status(err);
     if (assign && j > 0) {

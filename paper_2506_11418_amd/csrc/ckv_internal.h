@@ -44,12 +44,20 @@ hipError_t launch_dst_positions(const int32_t* dst_local, int32_t* dst_pos, int 
                                 int chunk, hipStream_t st);
 
 // Per-chunk top-r selection + degree-weighted merge + order-preserving compaction.
-// map_out[bh, t] (t < seq) = output index of the centroid input token t joined; may be NULL.
+// map_out[bh*map_stride + t] (t < seq) = map_offset + output index of the centroid input token t
+// joined; may be NULL.  deg_in[bh*deg_in_stride + t].
 hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int dtype, int dim,
                         TensorView in, int n_bh, int seq, int chunk, float r,
                         const int32_t* dst_local, const float* score, void* K_out, void* V_out,
-                        int32_t* deg_out, TensorView out, int64_t deg_out_stride, int out_seq,
-                        int32_t* map_out, hipStream_t st);
+                        int32_t* deg_out, TensorView out, int64_t deg_out_stride, int32_t* map_out,
+                        int64_t deg_in_stride, int64_t map_stride, int map_offset, hipStream_t st);
+
+// Copy the first n_head and the last n_tail tokens of every sequence (sinks / recents) to the
+// head / tail of the output, with their degrees and their entries of the round's map.
+hipError_t launch_edges(const void* K, const void* V, const int32_t* deg_in, TensorView in, int in_len, void* K_out,
+                        void* V_out, int32_t* deg_out, TensorView out, int64_t deg_out_stride, int out_len,
+                        int32_t* map_out, int n_head, int n_tail, int n_bh, int row_bytes, int elem_bytes,
+                        hipStream_t st);
 
 // Two rounds in one pass (first round r = 1, bf16, dim 128, chunk 1024, seq a multiple of 2048):
 // same outputs as launch_match + launch_merge twice; map_out gets the composition of both rounds.

@@ -82,7 +82,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     const T* __restrict__ K, const T* __restrict__ V, const int32_t* __restrict__ deg_in, TensorView in,
     int seq, int chunk, int n_chunks, float r, const int32_t* __restrict__ dst_local,
     const float* __restrict__ score, T* __restrict__ K_out, T* __restrict__ V_out,
-    int32_t* __restrict__ deg_out, TensorView out, int64_t deg_out_stride, int32_t* __restrict__ map_out) {
+    int32_t* __restrict__ deg_out, TensorView out, int64_t deg_out_stride, int32_t* __restrict__ map_out,
+    int64_t deg_in_stride, int64_t map_stride, int map_offset) {
   constexpr int E = Row<T>::E;
   constexpr int LPR = D / E;                 // lanes per row
   constexpr int NRG = kThreads / LPR;        // row groups per workgroup
@@ -236,11 +237,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
   // ---- assignment map of this round ----------------------------------------------------------
   if (map_out != nullptr) {
-    int32_t* mp = map_out + (int64_t)bh * seq + g0;
+    int32_t* mp = map_out + (int64_t)bh * map_stride + g0;
     for (int u = tid; u < L; u += kThreads) {
       const int d = (u & 1) ? -1 : (int)s_dstk[u >> 1];
       const int slot = (d < 0) ? s_local_out[u] : s_local_out[2 * d + 1];
-      mp[u] = out_base + slot;
+      mp[u] = map_offset + out_base + slot;
     }
   }
 
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   const T* Vin = V + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E;
   T* Ko = K_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
   T* Vo = V_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
-  const int32_t* dseq = deg_in ? deg_in + (int64_t)bh * seq + g0 : nullptr;
+  const int32_t* dseq = deg_in ? deg_in + (int64_t)bh * deg_in_stride + g0 : nullptr;
   int32_t* dout = deg_out + (int64_t)bh * deg_out_stride + out_base;
   for (int ob = 0; ob < n_out; ob += NRG * U) {
     int tok[U], nmem[U], first[U], mem0[U], du[U], dm[U];
@@ -331,6 +332,34 @@ __global__ void copy_rows_kernel(const unsigned char* __restrict__ src, TensorVi
   *reinterpret_cast<uint4*>(dst + dof) = *reinterpret_cast<const uint4*>(src + so);
 }
 
+// Tokens that bypass the clustering (Sec. 5.2: attention sinks and recent tokens are set aside
+// before partitioning; Sec. 5.3: they are concatenated back): the first n_head and the last n_tail
+// tokens of every sequence are copied to the head / tail of the output (keys, values, degree), and
+// their entries of the round's assignment map are written.
+__global__ void edges_kernel(const unsigned char* __restrict__ K, const unsigned char* __restrict__ V,
+                             const int32_t* __restrict__ deg_in, TensorView in, int in_len,
+                             unsigned char* __restrict__ K_out, unsigned char* __restrict__ V_out,
+                             int32_t* __restrict__ deg_out, TensorView out, int64_t deg_out_stride, int out_len,
+                             int32_t* __restrict__ map_out, int n_head, int n_tail, int pieces_per_row,
+                             int elem_bytes, int64_t total) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= total) return;
+  const int piece = (int)(e % pieces_per_row);
+  const int64_t row = e / pieces_per_row;
+  const int n_edge = n_head + n_tail;
+  const int k = (int)(row % n_edge), bh = (int)(row / n_edge);
+  const int t_in = k < n_head ? k : in_len - n_tail + (k - n_head);
+  const int t_out = k < n_head ? k : out_len - n_tail + (k - n_head);
+  const int64_t so = (in.seq_base(bh) + (int64_t)t_in * in.stride_s) * elem_bytes + piece * 16;
+  const int64_t dof = (out.seq_base(bh) + (int64_t)t_out * out.stride_s) * elem_bytes + piece * 16;
+  *reinterpret_cast<uint4*>(K_out + dof) = *reinterpret_cast<const uint4*>(K + so);
+  *reinterpret_cast<uint4*>(V_out + dof) = *reinterpret_cast<const uint4*>(V + so);
+  if (piece == 0) {
+    deg_out[(int64_t)bh * deg_out_stride + t_out] = deg_in ? deg_in[(int64_t)bh * in_len + t_in] : 1;
+    if (map_out) map_out[(int64_t)bh * in_len + t_in] = t_out;
+  }
+}
+
 __global__ void fill_deg_kernel(const int32_t* __restrict__ deg_in, int32_t* __restrict__ deg_out,
                                 int64_t out_stride, int32_t* __restrict__ assign, int seq, int64_t total) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -345,7 +374,8 @@ template <typename T, int D>
 hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, TensorView in, int n_bh,
                           int seq, int chunk, float r, const int32_t* dst_local, const float* score,
                           void* K_out, void* V_out, int32_t* deg_out, TensorView out,
-                          int64_t deg_out_stride, int32_t* map_out, hipStream_t st) {
+                          int64_t deg_out_stride, int32_t* map_out, int64_t deg_in_stride, int64_t map_stride,
+                          int map_offset, hipStream_t st) {
   const int n_chunks = div_up(seq, chunk);
   const int64_t total = (int64_t)n_bh * n_chunks;
   if (total > (1 << 30)) return hipErrorInvalidValue;
@@ -353,7 +383,7 @@ hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, T
   hipLaunchKernelGGL((merge_kernel<T, D>), dim3((int)total), dim3(kThreads), 0, st,
                      static_cast<const T*>(K), static_cast<const T*>(V), deg_in, in, seq, chunk, n_chunks,
                      r, dst_local, score, static_cast<T*>(K_out), static_cast<T*>(V_out), deg_out, out,
-                     deg_out_stride, map_out);
+                     deg_out_stride, map_out, deg_in_stride, map_stride, map_offset);
   return hipGetLastError();
 }
 
@@ -362,12 +392,11 @@ hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, T
 hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int dtype, int dim,
                         TensorView in, int n_bh, int seq, int chunk, float r,
                         const int32_t* dst_local, const float* score, void* K_out, void* V_out,
-                        int32_t* deg_out, TensorView out, int64_t deg_out_stride, int out_seq,
-                        int32_t* map_out, hipStream_t st) {
-  (void)out_seq;
+                        int32_t* deg_out, TensorView out, int64_t deg_out_stride, int32_t* map_out,
+                        int64_t deg_in_stride, int64_t map_stride, int map_offset, hipStream_t st) {
 #define CKV_MERGE(T, DD)                                                                             \
   return launch_merge_t<T, DD>(K, V, deg_in, in, n_bh, seq, chunk, r, dst_local, score, K_out, V_out, \
-                               deg_out, out, deg_out_stride, map_out, st)
+                               deg_out, out, deg_out_stride, map_out, deg_in_stride, map_stride, map_offset, st)
   if (dtype == CKV_BF16) {
     if (dim == 128) CKV_MERGE(__bf16, 128);
     if (dim == 64) CKV_MERGE(__bf16, 64);
@@ -398,6 +427,21 @@ hipError_t launch_copy_rows(const void* src, TensorView in, void* dst, TensorVie
   hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                      static_cast<const unsigned char*>(src), in, static_cast<unsigned char*>(dst), out, seq,
                      ppr, elem_bytes, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_edges(const void* K, const void* V, const int32_t* deg_in, TensorView in, int in_len, void* K_out,
+                        void* V_out, int32_t* deg_out, TensorView out, int64_t deg_out_stride, int out_len,
+                        int32_t* map_out, int n_head, int n_tail, int n_bh, int row_bytes, int elem_bytes,
+                        hipStream_t st) {
+  const int ppr = row_bytes / 16;
+  const int64_t total = (int64_t)n_bh * (n_head + n_tail) * ppr;
+  if (total == 0) return hipSuccess;
+  ScopedTimer t("edges_copy", st);
+  hipLaunchKernelGGL(edges_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const unsigned char*>(K), static_cast<const unsigned char*>(V), deg_in, in, in_len,
+                     static_cast<unsigned char*>(K_out), static_cast<unsigned char*>(V_out), deg_out, out,
+                     deg_out_stride, out_len, map_out, n_head, n_tail, ppr, elem_bytes, total);
   return hipGetLastError();
 }
 

@@ -86,6 +86,36 @@ def check_round(K, V, deg, c, r, dtype, gK, gV, gdeg, gassign, what=""):
     return n_alt
 
 
+def check_round_with_edges(K, V, deg, c, r, dtype, n_sink, n_recent, gK, gV, gdeg, gassign, what=""):
+    """One round with attention sinks / recent tokens set aside: the edge tokens must come out bit
+    for bit (keys, values, degree, map entry) where the oracle puts them, and the tokens between
+    them are held to check_round's bar.  When the matching agrees with the oracle's, the whole
+    output is also compared with the oracle's round in one piece."""
+    s = K.shape[0]
+    full = oracle.csm_round(K, V, deg, c, r, dtype, n_sink=n_sink, n_recent=n_recent)
+    out_len = full["K"].shape[0]
+    assert gK.shape == full["K"].shape, f"{what}: output length {gK.shape} vs {full['K'].shape}"
+    lo, hi = oracle.clusterable_range(s, n_sink, n_recent)
+    n_tail = s - hi
+    head_in, tail_in = np.arange(0, lo), np.arange(hi, s)
+    head_out, tail_out = np.arange(0, lo), np.arange(out_len - n_tail, out_len)
+    for ins, outs, name in ((head_in, head_out, "sinks"), (tail_in, tail_out, "recents")):
+        assert np.array_equal(gK[outs], K[ins]) and np.array_equal(gV[outs], V[ins]), f"{what}: {name} changed"
+        assert np.array_equal(gdeg[outs], deg[ins]), f"{what}: {name} degree changed"
+        assert np.array_equal(gassign[ins], outs), f"{what}: {name} map entries"
+        assert np.array_equal(full["assign"][ins], outs)
+    n_alt = 0
+    if hi > lo:
+        mid_out = slice(lo, out_len - n_tail)
+        n_alt = check_round(K[lo:hi], V[lo:hi], deg[lo:hi], c, r, dtype, gK[mid_out], gV[mid_out], gdeg[mid_out],
+                            gassign[lo:hi] - lo, what=what + " (middle)")
+    if np.array_equal(gassign, full["assign"]):
+        assert np.array_equal(gdeg, full["deg"])
+        assert_rows_close(gK, full["K"], TOL[dtype], f"{what} K' (whole)")
+        assert_rows_close(gV, full["V"], TOL[dtype], f"{what} V' (whole)")
+    return n_alt
+
+
 def check_match(K, c, gdst, gscore, what=""):
     """ckv_match output of one sequence vs the oracle: partners bit-exact off near-ties."""
     src, dst, score, near = oracle.match(K, c)

@@ -49,6 +49,13 @@ def test_plan_explicit_rounds(rounds):
         assert pl.round_len == round_lengths(seq, chunk, rounds)
 
 
+@pytest.mark.parametrize("n_sink,n_recent", [(4, 0), (0, 64), (16, 64), (100, 300)])
+def test_plan_with_sinks_and_recents(n_sink, n_recent):
+    for seq, chunk, rounds in [(5000, 256, [1.0, 0.5]), (333, 32, [0.7]), (300, 64, [1.0, 1.0, 1.0]), (50, 16, [1.0])]:
+        pl = ckv.plan(_lay(seq=seq), ckv.make_params(chunk, rounds=rounds, n_sink=n_sink, n_recent=n_recent))
+        assert pl.round_len == round_lengths(seq, chunk, rounds, n_sink, n_recent)
+
+
 def test_plan_workspace_grows_with_rounds():
     one = ckv.plan(_lay(), ckv.make_params(1024, 0.5)).workspace_bytes
     two = ckv.plan(_lay(), ckv.make_params(1024, 0.25)).workspace_bytes
@@ -80,9 +87,8 @@ def test_plan_rejects_bad_arguments():
     odd = _lay()
     odd.stride_s = 132                                          # 264 bytes: not a multiple of 16
     assert st(odd, ok) == -3
-    sink = ckv.make_params(256, 0.5)
-    sink.n_sink = 16
-    assert st(_lay(), sink) == -5
+    assert st(_lay(), ckv.make_params(256, 0.5, n_sink=-1)) == -1
+    assert st(_lay(), ckv.make_params(256, 0.5, n_recent=-4)) == -1
     assert L.ckv_plan(None, C.byref(ok), C.byref(pt)) == -1
 
 

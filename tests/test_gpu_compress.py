@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import paper_2506_11418_amd as ckv
-from parity_util import DT, check_match, check_round, f64, i64
+from parity_util import DT, TOL, assert_rows_close, check_match, check_round, check_round_with_edges, f64, i64
 from synth import kv_host
 
 pytestmark = pytest.mark.gpu
@@ -129,6 +129,75 @@ def test_compress_config2_llama_layer_bf16():
     torch.cuda.synchronize()
     assert torch.equal(gK, fK) and torch.equal(gV, fV) and torch.equal(gdeg, fdeg)
     assert int(gdeg.sum()) == 8 * 32768
+
+
+# ---- attention sinks and recent tokens (Sec. 5.2 / 5.3) ----------------------------------------
+@pytest.mark.parametrize("dtype,heads,seq,dim,chunk,rounds,n_sink,n_recent", [
+    ("bf16", 2, 4096 + 80, 128, 1024, [1.0, 1.0], 16, 64),
+    ("bf16", 2, 3001, 128, 256, [1.0, 0.6], 4, 0),
+    ("bf16", 1, 2500, 128, 512, [0.7], 0, 100),
+    ("bf16", 2, 700, 64, 64, [1.0, 1.0, 1.0], 3, 33),
+    ("f32", 1, 1024, 64, 64, [1.0, 0.5], 4, 32),
+    ("bf16", 1, 300, 128, 64, [1.0, 1.0, 1.0, 1.0], 100, 150),   # the middle dries up: 50 -> 25 -> 12 -> 6 -> 3
+    ("bf16", 2, 90, 128, 16, [1.0], 40, 50),                      # nothing between sinks and recents
+    ("bf16", 1, 50, 128, 16, [1.0], 40, 50),                      # shorter than n1 + n2
+])
+def test_compress_with_sinks_and_recents(dtype, heads, seq, dim, chunk, rounds, n_sink, n_recent):
+    _say(f"sinks/recents {dtype} H={heads} S={seq} D={dim} c={chunk} rounds={rounds} n1={n_sink} n2={n_recent}")
+    K, V, _ = kv_host(31, heads, seq, dim, dtype, alpha=0.9, n_outlier=4 if dim == 128 else 0)
+    K, V = K.to(DEV), V.to(DEV)
+    curK, curV, curdeg, maps = K, V, None, []
+    for j, r in enumerate(rounds):
+        gK, gV, gdeg, gas = ckv.compress(curK, curV, chunk, rounds=[r], deg=curdeg, n_sink=n_sink, n_recent=n_recent)
+        torch.cuda.synchronize()
+        for h in range(heads):
+            d_in = np.ones(curK.shape[2], dtype=np.int64) if curdeg is None else i64(curdeg[0, h])
+            check_round_with_edges(f64(curK[0, h]), f64(curV[0, h]), d_in, chunk, r, dtype, n_sink, n_recent,
+                                   f64(gK[0, h]), f64(gV[0, h]), i64(gdeg[0, h]), i64(gas[0, h]),
+                                   what=f"sinks/recents round {j} h{h}")
+        curK, curV, curdeg = gK, gV, gdeg
+        maps.append(gas.to(torch.int64))
+    gK, gV, gdeg, gas = ckv.compress(K, V, chunk, rounds=rounds, n_sink=n_sink, n_recent=n_recent)
+    torch.cuda.synchronize()
+    assert list(gK.shape) == [1, heads, oracle.round_lengths(seq, chunk, rounds, n_sink, n_recent)[-1], dim]
+    assert torch.equal(gK, curK) and torch.equal(gV, curV) and torch.equal(gdeg, curdeg)
+    comp = maps[0]
+    for m in maps[1:]:
+        comp = torch.gather(m, 2, comp)
+    assert torch.equal(gas.to(torch.int64), comp)
+    assert int(gdeg.sum()) == heads * seq
+
+
+def test_sinks_and_recents_with_strided_layout_and_retain_ratio():
+    """[B,S,H,D] input, padded output, incoming degrees, retain_ratio schedule with n1=16, n2=64:
+    the whole call against the oracle's compress (teacher-forcing is covered above)."""
+    _say("sinks/recents bshd")
+    B, H, S, D, c, n1, n2 = 2, 2, 2128, 128, 256, 16, 64
+    K0, V0, _ = kv_host(32, B * H, S, D, "bf16", alpha=0.9, n_outlier=4)
+    rng = np.random.default_rng(5)
+    Kb = K0.reshape(B, H, S, D).permute(0, 2, 1, 3).contiguous().to(DEV)      # [B,S,H,D] storage
+    Vb = V0.reshape(B, H, S, D).permute(0, 2, 1, 3).contiguous().to(DEV)
+    K, V = Kb.permute(0, 2, 1, 3), Vb.permute(0, 2, 1, 3)                     # [B,H,S,D] views
+    deg = torch.from_numpy(rng.integers(1, 4, size=(B, H, S)).astype(np.int32)).to(DEV)
+    out_len = oracle.round_lengths(S, c, oracle.direct_schedule(0.375), n1, n2)[-1]
+    pad = 40
+    oK = torch.zeros((B, H, out_len + pad, D), dtype=torch.bfloat16, device=DEV)
+    oV = torch.zeros_like(oK)
+    odeg = torch.zeros((B, H, out_len + pad), dtype=torch.int32, device=DEV)
+    oas = torch.empty((B, H, S), dtype=torch.int32, device=DEV)
+    ckv.compress(K, V, c, retain_ratio=0.375, deg=deg, out=(oK, oV, odeg, oas), n_sink=n1, n_recent=n2)
+    torch.cuda.synchronize()
+    assert not bool(oK[:, :, out_len:].any()) and not bool(odeg[:, :, out_len:].any())
+    for b in range(B):
+        for h in range(H):
+            ref = oracle.compress(f64(K[b, h]), f64(V[b, h]), c, oracle.direct_schedule(0.375), "bf16",
+                                  deg=i64(deg[b, h]), n_sink=n1, n_recent=n2)
+            if not np.array_equal(i64(oas[b, h]), ref["assign"]):
+                continue        # a near-tie somewhere; the per-round test above covers that case
+            assert np.array_equal(i64(odeg[b, h, :out_len]), ref["deg"])
+            assert_rows_close(f64(oK[b, h, :out_len]), ref["K"], TOL["bf16"], f"b{b}h{h} K'")
+            assert_rows_close(f64(oV[b, h, :out_len]), ref["V"], TOL["bf16"], f"b{b}h{h} V'")
+    assert int(odeg.sum()) == int(deg.sum())
 
 
 # ---- layouts, degrees, degenerate inputs ------------------------------------------------------
