@@ -23,8 +23,13 @@ conservation, lossless merge of duplicated keys and scatter-mean from the
 assignment map (merge); textbook softmax attention at degree 1, the q = 0 mean
 and exactness on duplicate-key clusters (attention); the paper's KV-cache size
 column (budget arithmetic); sink / recent tokens bit-identical, the middle equal
-to a round on the slice alone (sinks and recents).  Parity unpinned: nothing in
-this file; the annealed-schedule stopping rule and global top-r are not
+to a round on the slice alone (sinks and recents); the retained fractions
+0.6, 0.42, 0.336, 0.3024 of the annealed schedule at its defaults, and
+Algorithm 1's decode loop against plain attention over the whole uncompressed
+history on caches made of runs of identical tokens (online loop).  Parity
+unpinned: the POLICY that picks r for a decode-time clustering call and the
+floor that lets the annealed loop reach its budget are readings, not facts of
+the paper (the arithmetic for a given r is pinned); global top-r is not
 implemented here.
 """
 from __future__ import annotations
@@ -276,3 +281,60 @@ def app_attn(q, K, V, deg=None, length=None, scale=None):
         p = np.exp(z - z.max())
         o[h] = (p @ V[kv, :n]) / p.sum()
     return o
+
+
+# --------------------------------------------------------------------------
+# Eq. 4 and Algorithm 1: annealed schedule, budget loop, online decoding
+# --------------------------------------------------------------------------
+def annealed_ratio(j: int, r_init: float, delta_r: float, r_floor: float = 0.0) -> float:
+    """Merge fraction of clustering round j (Eq. 4): r_init - j*delta_r, never
+    below r_floor (the paper gives no floor; 0 reproduces the formula as
+    printed).  Returned as the float32 value the parameters carry."""
+    return float(np.float32(max(r_init - j * delta_r, r_floor)))
+
+
+def rounds_to_budget(s: int, c: int, budget: int, r_init: float, delta_r: float, r_floor: float = 0.0,
+                     n_sink: int = 0, n_recent: int = 0, max_rounds: int = 8):
+    """The loop after prefill of Algorithm 1 on lengths alone: cluster with
+    r_0, r_1, ... (Eq. 4) while the cache is longer than the budget.  Returns
+    the list of merge fractions used.  Raises when a round removes nothing
+    while s > budget (the schedule has run dry) or max_rounds is exceeded."""
+    rounds = []
+    while s > budget:
+        if len(rounds) == max_rounds:
+            raise ValueError("budget not reached within max_rounds")
+        r = annealed_ratio(len(rounds), r_init, delta_r, r_floor)
+        nxt = round_lengths(s, c, [r], n_sink, n_recent)[-1]
+        if nxt == s:
+            raise ValueError("the schedule stalls above the budget")
+        rounds.append(r)
+        s = nxt
+    return rounds
+
+
+def alg1_decode(K, V, deg, qs, ks, vs, c: int, budget: int, g: int, r_calls, dtype: str,
+                n_sink: int = 0, n_recent: int = 0, tau: float = TAU):
+    """Decoding part of Algorithm 1 for one layer.  K, V: [Hkv, s, d] and deg:
+    [Hkv, s], the cache after prefill (and its first clustering); step i
+    appends (ks[i], vs[i]) with degree 1 to every KV head, attends with
+    qs[i] over the whole cache (Eq. 3), then, if the cache has reached
+    budget + g tokens, runs ONE clustering round with the next merge
+    fraction of r_calls (a list, consumed in order; the last entry repeats).
+    Returns (outputs [steps, Hq, d], K, V, deg, steps at which a round ran)."""
+    K = [np.array(K[h], dtype=np.float64) for h in range(len(K))]
+    V = [np.array(V[h], dtype=np.float64) for h in range(len(V))]
+    deg = [np.array(deg[h], dtype=np.int64) for h in range(len(deg))]
+    outs, ran = [], []
+    for i in range(len(qs)):
+        for h in range(len(K)):
+            K[h] = np.concatenate([K[h], np.asarray(ks[i][h], dtype=np.float64)[None]], axis=0)
+            V[h] = np.concatenate([V[h], np.asarray(vs[i][h], dtype=np.float64)[None]], axis=0)
+            deg[h] = np.concatenate([deg[h], np.ones(1, dtype=np.int64)])
+        outs.append(app_attn(qs[i], np.stack(K), np.stack(V), np.stack(deg)))
+        if K[0].shape[0] >= budget + g:
+            r = r_calls[min(len(ran), len(r_calls) - 1)]
+            for h in range(len(K)):
+                res = csm_round(K[h], V[h], deg[h], c, r, dtype, tau, n_sink, n_recent)
+                K[h], V[h], deg[h] = res["K"], res["V"], res["deg"]
+            ran.append(i)
+    return np.stack(outs), np.stack(K), np.stack(V), np.stack(deg), ran
