@@ -46,6 +46,10 @@ typedef struct {
   int32_t batch, heads, seq, dim;
   int64_t stride_b, stride_h, stride_s; /* in elements */
   int32_t dtype;                        /* ckv_dtype */
+  int64_t deg_stride;                   /* elements between the rows of consecutive (batch, head)
+                                           sequences in the int32 degree array that goes with this
+                                           tensor; 0 = seq (a packed [batch, heads, seq] array).  A
+                                           cache with spare capacity sets it to the capacity.      */
 } ckv_layout;
 
 #define CKV_MAX_ROUNDS 8
@@ -97,12 +101,13 @@ int ckv_match(const void* K, const ckv_layout* in, int32_t chunk, int32_t* dst, 
               void* hip_stream);
 
 /* Compress a KV cache (Algorithm 1, the loop after prefill; Sec. 5.2-5.3).
- *   K, V     inputs, layout `in`;  deg_in [batch, heads, seq] int32 cluster degrees or NULL (= 1).
+ *   K, V     inputs, layout `in`;  deg_in [batch, heads, seq] int32 cluster degrees (row stride
+ *            in->deg_stride) or NULL (= 1).
  *   K_out, V_out  layout `out` (same batch/heads/dim/dtype; out->seq >= plan.out_seq); rows
  *            [0, plan.out_seq) of every (batch, head) are written: the retained tokens in their
  *            original order, each B token replaced by the degree-weighted mean of itself and the
  *            A tokens merged into it (keys and values alike), rounded to nearest-even.
- *   deg_out  [batch, heads, out->seq] int32 degrees of the output tokens.
+ *   deg_out  [batch, heads, out->seq] int32 degrees of the output tokens (row stride out->deg_stride).
  *   assign   [batch, heads, seq] int32 or NULL: output index of the centroid each INPUT token
  *            ended up in (composition over rounds).
  *   workspace  >= plan.workspace_bytes, 256-byte aligned.
@@ -112,6 +117,29 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
                  const ckv_layout* out, int32_t* assign, void* workspace, size_t workspace_bytes,
                  void* hip_stream);
 
+/* Host only.  The annealed schedule of merge fractions (Eq. 4) run as Algorithm 1's loop after
+ * prefill: starting from `seq` tokens, rounds j = 0, 1, ... with r_j = max(r_init - j*delta_r,
+ * r_floor) are added while the cache is longer than `budget` tokens (budget = R*n in Algorithm 1).
+ * Fills *out (chunk, n_sink, n_recent, n_rounds, r[]) for ckv_plan / ckv_compress; zero rounds
+ * (budget already met) gives the identity.  The paper states no floor: r_floor = 0 is Eq. 4 as
+ * printed, and then CKV_EUNSUPPORTED is returned when a round removes nothing while the cache is
+ * still above the budget, or when more than CKV_MAX_ROUNDS rounds would be needed. */
+int ckv_schedule_annealed(int32_t seq, int32_t chunk, int32_t n_sink, int32_t n_recent, int32_t budget,
+                          float r_init, float delta_r, float r_floor, ckv_params* out);
+
+/* Cache update of one decode step (Algorithm 1, decoding part: K = [K, k], V = [V, v], N = [N, 1]).
+ *   k_new, v_new [batch, heads, dim] contiguous, the cache's dtype, device.
+ *   K, V     the cache, layout `cache` with cache->seq = its CAPACITY in tokens; deg [batch, heads,
+ *            capacity] int32 (row stride cache->deg_stride) or NULL.
+ *   lens     device int32 [batch] or NULL.  With lens: the token of sequence b is written to row
+ *            lens[b] of every head, its degree set to 1, and lens[b] is incremented on the stream
+ *            afterwards; a sequence with lens[b] already at capacity is left untouched.  Without:
+ *            row `pos` of every sequence (CKV_ESHAPE when pos is outside [0, capacity)).
+ * To re-cluster (Algorithm 1: once the cache holds budget + g tokens), call ckv_compress with a
+ * layout whose seq is the current length, deg_in = deg, and one round. */
+int ckv_append(const void* k_new, const void* v_new, void* K, void* V, int32_t* deg, const ckv_layout* cache,
+               int32_t* lens, int32_t pos, void* hip_stream);
+
 /* Scratch bytes ckv_decode_attn needs for this cache shape and number of query heads. */
 int ckv_decode_attn_workspace(const ckv_layout* kv, int32_t q_heads, size_t* bytes);
 
@@ -120,7 +148,7 @@ int ckv_decode_attn_workspace(const ckv_layout* kv, int32_t q_heads, size_t* byt
  *   t < lens[b], kvh = h / (q_heads / kv->heads).
  *   q [batch, q_heads, dim] contiguous, same dtype as the cache; lens [batch] int32 (each
  *   <= kv->seq; 0 gives a zero output) or NULL (= kv->seq); deg [batch, heads, kv->seq] int32
- *   (>= 1) or NULL (= 1: plain attention, Eq. 1); scale <= 0 selects 1/sqrt(dim);
+ *   (>= 1; row stride kv->deg_stride) or NULL (= 1: plain attention, Eq. 1); scale <= 0 selects 1/sqrt(dim);
  *   o [batch, q_heads, dim] contiguous in o_dtype.  Arithmetic is fp32.
  * Supported: q_heads / kv->heads in {1,2,4,8}; bf16 dim 64/128; fp32 dim 32/64/128. */
 int ckv_decode_attn(const void* q, int32_t q_heads, const void* K, const void* V,

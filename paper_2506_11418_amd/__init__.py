@@ -29,7 +29,7 @@ class CkvError(RuntimeError):
 class Layout(C.Structure):
     _fields_ = [("batch", C.c_int32), ("heads", C.c_int32), ("seq", C.c_int32), ("dim", C.c_int32),
                 ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_s", C.c_int64),
-                ("dtype", C.c_int32)]
+                ("dtype", C.c_int32), ("deg_stride", C.c_int64)]
 
 
 class Params(C.Structure):
@@ -68,6 +68,9 @@ def lib() -> C.CDLL:
         L.ckv_decode_attn_workspace.argtypes = [C.POINTER(Layout), i32, C.POINTER(C.c_size_t)]
         L.ckv_decode_attn.argtypes = [vp, i32, vp, vp, C.POINTER(Layout), vp, vp, C.c_float, vp, i32,
                                       vp, C.c_size_t, vp]
+        L.ckv_schedule_annealed.argtypes = [i32, i32, i32, i32, i32, C.c_float, C.c_float, C.c_float,
+                                            C.POINTER(Params)]
+        L.ckv_append.argtypes = [vp, vp, vp, vp, vp, C.POINTER(Layout), vp, i32, vp]
         L.ckv_timing_enable.argtypes = [C.c_int]
         L.ckv_timing_read.argtypes = [C.POINTER(KernelTime), C.c_int]
         _lib = L
@@ -78,12 +81,22 @@ def version() -> str:
     return lib().ckv_version().decode()
 
 
-def layout_of(t: torch.Tensor) -> Layout:
-    """Layout of a [batch, heads, seq, dim] tensor (any strides, dim contiguous)."""
+def layout_of(t: torch.Tensor, deg: Optional[torch.Tensor] = None) -> Layout:
+    """Layout of a [batch, heads, seq, dim] tensor (any strides, dim contiguous) and of the int32
+    degree array [batch, heads, seq] that goes with it (rows evenly spaced, e.g. a slice of a
+    [batch, heads, capacity] buffer)."""
     if t.dim() != 4 or t.stride(3) != 1 or t.dtype not in _DT:
         raise ValueError("expected a [batch, heads, seq, dim] float32/bfloat16 tensor with contiguous dim")
+    deg_stride = 0
+    if deg is not None:
+        B, H, S = t.shape[:3]
+        if deg.dtype != torch.int32 or tuple(deg.shape) != (B, H, S) or (S > 1 and deg.stride(2) != 1):
+            raise ValueError("deg must be int32 [batch, heads, seq] with contiguous seq")
+        deg_stride = deg.stride(1) if H > 1 else (deg.stride(0) if B > 1 else S)
+        if B > 1 and H > 1 and deg.stride(0) != H * deg.stride(1):
+            raise ValueError("deg rows must be evenly spaced over (batch, head)")
     return Layout(t.shape[0], t.shape[1], t.shape[2], t.shape[3], t.stride(0), t.stride(1), t.stride(2),
-                  _DT[t.dtype])
+                  _DT[t.dtype], deg_stride)
 
 
 def make_params(chunk: int, retain_ratio: float = 1.0, rounds: Optional[Sequence[float]] = None,
@@ -146,7 +159,7 @@ def compress(K: torch.Tensor, V: torch.Tensor, chunk: int, retain_ratio: float =
 
     `out` may pass preallocated (K_out, V_out, deg_out, assign) and `workspace` a uint8 tensor, so
     that a timed loop allocates nothing."""
-    lay = layout_of(K)
+    lay = layout_of(K, deg)
     if layout_of(V).dtype != lay.dtype or V.shape != K.shape:
         raise ValueError("K and V must have the same shape and dtype")
     params = make_params(chunk, retain_ratio, rounds, n_sink, n_recent)
@@ -161,7 +174,7 @@ def compress(K: torch.Tensor, V: torch.Tensor, chunk: int, retain_ratio: float =
         K_out, V_out, deg_out, assign = out
     if workspace is None:
         workspace = torch.empty(max(pl.workspace_bytes, 256), dtype=torch.uint8, device=K.device)
-    olay = layout_of(K_out)
+    olay = layout_of(K_out, deg_out)
     st = lib().ckv_compress(_ptr(K), _ptr(V), _ptr(deg), C.byref(lay), C.byref(params), _ptr(K_out),
                             _ptr(V_out), _ptr(deg_out), C.byref(olay), _ptr(assign), _ptr(workspace),
                             workspace.numel(), _stream())
@@ -182,11 +195,9 @@ def decode_attn(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, lens: Optiona
                 deg: Optional[torch.Tensor] = None, scale: float = 0.0, out_dtype=None,
                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
     """ckv_decode_attn: q [B,Hq,D], K/V [B,Hkv,L,D], lens [B] int32, deg [B,Hkv,L] int32 -> o [B,Hq,D]."""
-    lay = layout_of(K)
+    lay = layout_of(K, deg)
     if not q.is_contiguous() or q.dim() != 3 or q.dtype != K.dtype:
         raise ValueError("q must be a contiguous [batch, q_heads, dim] tensor of the cache dtype")
-    if deg is not None and not deg.is_contiguous():
-        raise ValueError("deg must be contiguous [batch, heads, seq]")
     q_heads = q.shape[1]
     if out is None:
         out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
@@ -198,6 +209,35 @@ def decode_attn(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, lens: Optiona
     if st != 0:
         raise CkvError(st, "ckv_decode_attn")
     return out
+
+
+def schedule_annealed(seq: int, chunk: int, budget: int, r_init: float = 0.8, delta_r: float = 0.2,
+                      r_floor: float = 0.0, n_sink: int = 0, n_recent: int = 0) -> list:
+    """ckv_schedule_annealed: the merge fractions Algorithm 1's loop after prefill uses to bring
+    `seq` tokens within `budget` under the annealed schedule."""
+    p = Params()
+    st = lib().ckv_schedule_annealed(seq, chunk, n_sink, n_recent, budget, r_init, delta_r, r_floor, C.byref(p))
+    if st != 0:
+        raise CkvError(st, "ckv_schedule_annealed")
+    return list(p.r[: p.n_rounds])
+
+
+def append(k_new: torch.Tensor, v_new: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
+           deg: Optional[torch.Tensor], lens: Optional[torch.Tensor] = None, pos: int = -1) -> None:
+    """ckv_append: write one new token per (batch, head) into the cache buffers K, V
+    [batch, heads, capacity, dim] (deg [batch, heads, capacity] := 1 there) at row lens[b]
+    (device int32, incremented by the call) or at row `pos`."""
+    lay = layout_of(K, deg)
+    B, H, _, D = K.shape
+    for t in (k_new, v_new):
+        if tuple(t.shape) != (B, H, D) or not t.is_contiguous() or t.dtype != K.dtype:
+            raise ValueError("k_new, v_new must be contiguous [batch, heads, dim] tensors of the cache dtype")
+    if layout_of(V).stride_s != lay.stride_s or V.shape != K.shape or V.stride() != K.stride():
+        raise ValueError("K and V buffers must share shape and strides")
+    st = lib().ckv_append(_ptr(k_new), _ptr(v_new), _ptr(K), _ptr(V), _ptr(deg), C.byref(lay), _ptr(lens),
+                          pos, _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_append")
 
 
 def timing_enable(on: bool) -> None:

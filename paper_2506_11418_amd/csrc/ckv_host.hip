@@ -21,6 +21,7 @@ int check_layout(const ckv_layout* l) {
   if (l->batch <= 0 || l->heads <= 0 || l->seq <= 0 || l->dim <= 0) return CKV_ESHAPE;
   if (l->stride_s < l->dim || l->stride_h < l->dim || l->stride_b < l->dim) return CKV_ESHAPE;
   if ((int64_t)l->batch * l->heads > (1 << 24)) return CKV_ESHAPE;
+  if (l->deg_stride != 0 && l->deg_stride < l->seq) return CKV_ESHAPE;
   const int e = elem_bytes(l->dtype);
   if ((l->stride_s * e) % 16 || (l->stride_h * e) % 16 || (l->stride_b * e) % 16 || (l->dim * e) % 16)
     return CKV_EALIGN;
@@ -44,9 +45,12 @@ bool dims_supported(int dtype, int dim) {
   return dim == 16 || dim == 32 || dim == 64 || dim == 128;
 }
 
-TensorView view_of(const ckv_layout* l) { return TensorView{l->stride_b, l->stride_h, l->stride_s, l->heads}; }
+int64_t deg_stride_of(const ckv_layout* l) { return l->deg_stride ? l->deg_stride : l->seq; }
+TensorView view_of(const ckv_layout* l) {
+  return TensorView{l->stride_b, l->stride_h, l->stride_s, l->heads, deg_stride_of(l)};
+}
 TensorView compact_view(int heads, int len, int dim) {
-  return TensorView{(int64_t)heads * len * dim, (int64_t)len * dim, (int64_t)dim, heads};
+  return TensorView{(int64_t)heads * len * dim, (int64_t)len * dim, (int64_t)dim, heads, (int64_t)len};
 }
 
 // [lo, hi): the tokens of a cache of `len` tokens that take part in the clustering; the first n_sink
@@ -248,7 +252,8 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     hipError_t err = launch_copy_rows(K, view_of(in), K_out, view_of(out), n_bh, in->seq, in->dim * e, e, s);
     if (err == hipSuccess)
       err = launch_copy_rows(V, view_of(in), V_out, view_of(out), n_bh, in->seq, in->dim * e, e, s);
-    if (err == hipSuccess) err = launch_fill_deg(deg_in, deg_out, out->seq, assign, n_bh, in->seq, s);
+    if (err == hipSuccess)
+      err = launch_fill_deg(deg_in, deg_stride_of(in), deg_out, deg_stride_of(out), assign, n_bh, in->seq, s);
     return hip_status(err);
   }
 
@@ -268,7 +273,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     const int len = plan.round_len[j];
     // rounds j and j+1 in one pass when the first merges every edge and the shape has a kernel
     const bool fuse = allow_fused && j + 1 < plan.n_rounds &&
-                      p->n_sink == 0 && p->n_recent == 0 &&
+                      p->n_sink == 0 && p->n_recent == 0 && curView.deg_stride == len &&
                       fused2_supported(in->dtype, in->dim, p->chunk, len, plan.round_r[j]) &&
                       curView.stride_s <= (1 << 18) && out->stride_s <= (1 << 18);
     const int jo = fuse ? j + 1 : j;                 // index of the round whose output is produced
@@ -278,7 +283,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     void* oV = last ? V_out : ws + w.V[jo & 1];
     int32_t* oDeg = last ? deg_out : reinterpret_cast<int32_t*>(ws + w.deg[jo & 1]);
     const TensorView oView = last ? view_of(out) : compact_view(in->heads, next, in->dim);
-    const int64_t oDegStride = last ? out->seq : next;
+    const int64_t oDegStride = oView.deg_stride;
     int32_t* map = nullptr;
     if (assign) map = (j == 0) ? assign : reinterpret_cast<int32_t*>(ws + w.map);
     int lo, hi;
@@ -297,7 +302,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
         err = launch_merge(mK, mV, curDeg ? curDeg + lo : nullptr, in->dtype, in->dim, curView, n_bh, mid, p->chunk,
                            plan.round_r[j], dst, score, static_cast<unsigned char*>(oK) + (size_t)lo * oView.stride_s * e,
                            static_cast<unsigned char*>(oV) + (size_t)lo * oView.stride_s * e, oDeg + lo, oView,
-                           oDegStride, map ? map + lo : nullptr, len, len, lo, s);
+                           oDegStride, map ? map + lo : nullptr, curView.deg_stride, len, lo, s);
         if (err != hipSuccess) return hip_status(err);
       }
       if (mid < len)   // sinks and recents (or a cache too short to cluster): straight copy
@@ -313,6 +318,42 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     j = jo;
   }
   return CKV_OK;
+}
+
+int ckv_schedule_annealed(int32_t seq, int32_t chunk, int32_t n_sink, int32_t n_recent, int32_t budget,
+                          float r_init, float delta_r, float r_floor, ckv_params* out) {
+  if (!out || seq <= 0 || budget < 0 || n_sink < 0 || n_recent < 0) return CKV_EINVAL;
+  if (chunk < 2 || chunk > 2048 || (chunk & 1)) return CKV_EINVAL;
+  if (!(r_init >= 0.f && r_init <= 1.f) || !(delta_r >= 0.f) || !(r_floor >= 0.f && r_floor <= 1.f)) return CKV_EINVAL;
+  memset(out, 0, sizeof(*out));
+  out->chunk = chunk;
+  out->retain_ratio = 1.0f;
+  out->n_sink = n_sink;
+  out->n_recent = n_recent;
+  int len = seq, j = 0;
+  while (len > budget) {
+    if (j == CKV_MAX_ROUNDS) return CKV_EUNSUPPORTED;
+    const double want = (double)r_init - (double)j * (double)delta_r;
+    const float r = (float)(want > (double)r_floor ? want : (double)r_floor);
+    const int next = seq_after_round(len, chunk, r, n_sink, n_recent);
+    if (next == len) return CKV_EUNSUPPORTED;   // the schedule has run dry above the budget
+    out->r[j++] = r;
+    len = next;
+  }
+  out->n_rounds = j;
+  return CKV_OK;
+}
+
+int ckv_append(const void* k_new, const void* v_new, void* K, void* V, int32_t* deg, const ckv_layout* cache,
+               int32_t* lens, int32_t pos, void* hip_stream) {
+  int st = check_layout(cache);
+  if (st != CKV_OK) return st;
+  if (!k_new || !v_new || !K || !V) return CKV_EINVAL;
+  if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)K | (uintptr_t)V) % 16) return CKV_EALIGN;
+  if (!lens && (pos < 0 || pos >= cache->seq)) return CKV_ESHAPE;
+  const int e = elem_bytes(cache->dtype);
+  return hip_status(launch_append(k_new, v_new, K, V, deg, view_of(cache), cache->batch, cache->seq, lens, pos,
+                                  cache->dim * e, e, static_cast<hipStream_t>(hip_stream)));
 }
 
 int ckv_decode_attn_workspace(const ckv_layout* kv, int32_t q_heads, size_t* bytes) {

@@ -11,6 +11,7 @@ namespace ckv {
 struct TensorView {
   int64_t stride_b, stride_h, stride_s;
   int32_t heads;  // to split a flat (batch*heads) index
+  int64_t deg_stride;  // elements between the degree rows of consecutive (batch, head) sequences
   __host__ __device__ inline int64_t seq_base(int bh) const {
     return (int64_t)(bh / heads) * stride_b + (int64_t)(bh % heads) * stride_h;
   }
@@ -52,6 +53,12 @@ hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int
                         int32_t* deg_out, TensorView out, int64_t deg_out_stride, int32_t* map_out,
                         int64_t deg_in_stride, int64_t map_stride, int map_offset, hipStream_t st);
 
+// Decode-step cache update: row lens[b] (device, then incremented) or `pos` of every (batch, head)
+// := (k_new, v_new, degree 1).  k_new, v_new: [batch, heads, dim] contiguous.
+hipError_t launch_append(const void* k_new, const void* v_new, void* K, void* V, int32_t* deg, TensorView cache,
+                         int batch, int capacity, int32_t* lens, int pos, int row_bytes, int elem_bytes,
+                         hipStream_t st);
+
 // Copy the first n_head and the last n_tail tokens of every sequence (sinks / recents) to the
 // head / tail of the output, with their degrees and their entries of the round's map.
 hipError_t launch_edges(const void* K, const void* V, const int32_t* deg_in, TensorView in, int in_len, void* K_out,
@@ -73,7 +80,7 @@ hipError_t launch_compose(int32_t* assign, const int32_t* map, int n_bh, int seq
 // Plain strided copy of [n_bh, seq, dim] rows (used when the schedule has zero rounds).
 hipError_t launch_copy_rows(const void* src, TensorView in, void* dst, TensorView out, int n_bh,
                             int seq, int row_bytes, int elem_bytes, hipStream_t st);
-hipError_t launch_fill_deg(const int32_t* deg_in, int32_t* deg_out, int64_t out_stride, int32_t* assign,
+hipError_t launch_fill_deg(const int32_t* deg_in, int64_t in_stride, int32_t* deg_out, int64_t out_stride, int32_t* assign,
                            int n_bh, int seq, hipStream_t st);
 
 // Decode attention: split-K partials then combine.

@@ -355,18 +355,42 @@ __global__ void edges_kernel(const unsigned char* __restrict__ K, const unsigned
   *reinterpret_cast<uint4*>(K_out + dof) = *reinterpret_cast<const uint4*>(K + so);
   *reinterpret_cast<uint4*>(V_out + dof) = *reinterpret_cast<const uint4*>(V + so);
   if (piece == 0) {
-    deg_out[(int64_t)bh * deg_out_stride + t_out] = deg_in ? deg_in[(int64_t)bh * in_len + t_in] : 1;
+    deg_out[(int64_t)bh * deg_out_stride + t_out] = deg_in ? deg_in[(int64_t)bh * in.deg_stride + t_in] : 1;
     if (map_out) map_out[(int64_t)bh * in_len + t_in] = t_out;
   }
 }
 
-__global__ void fill_deg_kernel(const int32_t* __restrict__ deg_in, int32_t* __restrict__ deg_out,
+// Cache update of a decode step (Algorithm 1, decoding part): the new token of every (batch, head)
+// goes to row lens[b] (or `pos`) with degree 1.  A sequence already at capacity is left alone.
+__global__ void append_kernel(const unsigned char* __restrict__ k_new, const unsigned char* __restrict__ v_new,
+                              unsigned char* __restrict__ K, unsigned char* __restrict__ V,
+                              int32_t* __restrict__ deg, TensorView cache, int capacity,
+                              const int32_t* __restrict__ lens, int pos, int pieces_per_row, int elem_bytes,
+                              int total) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= total) return;
+  const int piece = e % pieces_per_row, bh = e / pieces_per_row;
+  const int t = lens ? lens[bh / cache.heads] : pos;
+  if (t < 0 || t >= capacity) return;
+  const int64_t so = ((int64_t)bh * pieces_per_row + piece) * 16;
+  const int64_t dof = (cache.seq_base(bh) + (int64_t)t * cache.stride_s) * elem_bytes + piece * 16;
+  *reinterpret_cast<uint4*>(K + dof) = *reinterpret_cast<const uint4*>(k_new + so);
+  *reinterpret_cast<uint4*>(V + dof) = *reinterpret_cast<const uint4*>(v_new + so);
+  if (piece == 0 && deg) deg[(int64_t)bh * cache.deg_stride + t] = 1;
+}
+
+__global__ void bump_lens_kernel(int32_t* __restrict__ lens, int batch, int capacity) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < batch && lens[b] >= 0 && lens[b] < capacity) lens[b] += 1;
+}
+
+__global__ void fill_deg_kernel(const int32_t* __restrict__ deg_in, int64_t in_stride, int32_t* __restrict__ deg_out,
                                 int64_t out_stride, int32_t* __restrict__ assign, int seq, int64_t total) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= total) return;
   const int t = (int)(e % seq);
   const int64_t bh = e / seq;
-  deg_out[bh * out_stride + t] = deg_in ? deg_in[e] : 1;
+  deg_out[bh * out_stride + t] = deg_in ? deg_in[bh * in_stride + t] : 1;
   if (assign) assign[e] = t;
 }
 
@@ -445,12 +469,31 @@ hipError_t launch_edges(const void* K, const void* V, const int32_t* deg_in, Ten
   return hipGetLastError();
 }
 
-hipError_t launch_fill_deg(const int32_t* deg_in, int32_t* deg_out, int64_t out_stride, int32_t* assign,
-                           int n_bh, int seq, hipStream_t st) {
+hipError_t launch_append(const void* k_new, const void* v_new, void* K, void* V, int32_t* deg, TensorView cache,
+                         int batch, int capacity, int32_t* lens, int pos, int row_bytes, int elem_bytes,
+                         hipStream_t st) {
+  const int ppr = row_bytes / 16;
+  const int total = batch * cache.heads * ppr;
+  {
+    ScopedTimer t("append", st);
+    hipLaunchKernelGGL(append_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const unsigned char*>(k_new), static_cast<const unsigned char*>(v_new),
+                       static_cast<unsigned char*>(K), static_cast<unsigned char*>(V), deg, cache, capacity, lens,
+                       pos, ppr, elem_bytes, total);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || !lens) return err;
+  }
+  ScopedTimer t("append_bump_lens", st);
+  hipLaunchKernelGGL(bump_lens_kernel, dim3((unsigned)((batch + 255) / 256)), dim3(256), 0, st, lens, batch, capacity);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_deg(const int32_t* deg_in, int64_t in_stride, int32_t* deg_out, int64_t out_stride,
+                           int32_t* assign, int n_bh, int seq, hipStream_t st) {
   const int64_t total = (int64_t)n_bh * seq;
   ScopedTimer t("fill_deg", st);
   hipLaunchKernelGGL(fill_deg_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, deg_in,
-                     deg_out, out_stride, assign, seq, total);
+                     in_stride, deg_out, out_stride, assign, seq, total);
   return hipGetLastError();
 }
 

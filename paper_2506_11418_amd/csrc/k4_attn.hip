@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void attn_partial_kernel(
   const int64_t base = (int64_t)b * kv.stride_b + (int64_t)kvh * kv.stride_h + piece * E;
   const T* Kp = K + base;
   const T* Vp = V + base;
-  const int32_t* dseq = deg ? deg + ((int64_t)b * kv_heads + kvh) * seq : nullptr;
+  const int32_t* dseq = deg ? deg + ((int64_t)b * kv_heads + kvh) * kv.deg_stride : nullptr;
 
   typename Elems<T>::Q qv[G];
 #pragma unroll

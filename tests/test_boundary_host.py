@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(ckv_[a-z_]+)\s*\(", header))
     assert {"ckv_plan", "ckv_match", "ckv_compress", "ckv_decode_attn", "ckv_decode_attn_workspace",
-            "ckv_version", "ckv_strerror"} <= names
+            "ckv_version", "ckv_strerror", "ckv_append", "ckv_schedule_annealed"} <= names
     L = ckv.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -54,6 +54,44 @@ def test_plan_with_sinks_and_recents(n_sink, n_recent):
     for seq, chunk, rounds in [(5000, 256, [1.0, 0.5]), (333, 32, [0.7]), (300, 64, [1.0, 1.0, 1.0]), (50, 16, [1.0])]:
         pl = ckv.plan(_lay(seq=seq), ckv.make_params(chunk, rounds=rounds, n_sink=n_sink, n_recent=n_recent))
         assert pl.round_len == round_lengths(seq, chunk, rounds, n_sink, n_recent)
+
+
+@pytest.mark.parametrize("seq,chunk,budget,n_sink,n_recent,r_floor", [
+    (10000, 1000, 6000, 0, 0, 0.0), (10000, 1000, 3024, 0, 0, 0.0), (10000, 1000, 2500, 0, 0, 0.2),
+    (4096, 256, 1024, 16, 64, 0.2), (32768, 1024, 8192, 16, 64, 0.4), (333, 32, 200, 4, 8, 0.0), (500, 64, 500, 0, 0, 0.0),
+])
+def test_annealed_schedule_matches_the_oracle_loop(seq, chunk, budget, n_sink, n_recent, r_floor):
+    from oracle import rounds_to_budget
+    got = ckv.schedule_annealed(seq, chunk, budget, 0.8, 0.2, r_floor, n_sink, n_recent)
+    assert got == rounds_to_budget(seq, chunk, budget, 0.8, 0.2, r_floor, n_sink, n_recent)
+    if got:
+        pl = ckv.plan(_lay(seq=seq), ckv.make_params(chunk, rounds=got, n_sink=n_sink, n_recent=n_recent))
+        assert pl.out_seq <= budget < pl.round_len[-2]
+
+
+def test_annealed_schedule_reports_a_budget_it_cannot_reach():
+    with pytest.raises(ckv.CkvError) as e:      # Eq. 4 as printed stalls at 30.24% with the defaults
+        ckv.schedule_annealed(10000, 1000, 2500, 0.8, 0.2, 0.0)
+    assert e.value.status == -5
+    with pytest.raises(ckv.CkvError):           # more than 8 rounds
+        ckv.schedule_annealed(1 << 20, 64, 100, 0.8, 0.2, 0.2)
+    p = ckv.Params()
+    L = ckv.lib()
+    assert L.ckv_schedule_annealed(1000, 63, 0, 0, 500, 0.8, 0.2, 0.0, C.byref(p)) == -1
+    assert L.ckv_schedule_annealed(1000, 64, 0, 0, 500, 1.5, 0.2, 0.0, C.byref(p)) == -1
+    assert L.ckv_schedule_annealed(1000, 64, 0, 0, 500, 0.8, 0.2, 0.0, None) == -1
+
+
+def test_append_rejects_bad_arguments_before_any_launch():
+    L = ckv.lib()
+    lay, z, a = _lay(seq=128), C.c_void_p(0), C.c_void_p(4096)
+    assert L.ckv_append(z, a, a, a, z, C.byref(lay), z, 0, z) == -1
+    assert L.ckv_append(a, a, C.c_void_p(4100), a, z, C.byref(lay), z, 0, z) == -3
+    assert L.ckv_append(a, a, a, a, z, C.byref(lay), z, 128, z) == -2          # row outside the capacity
+    assert L.ckv_append(a, a, a, a, z, C.byref(lay), z, -1, z) == -2
+    bad = _lay(seq=128)
+    bad.deg_stride = 100                                                       # rows would overlap
+    assert L.ckv_append(a, a, a, a, z, C.byref(bad), z, 0, z) == -2
 
 
 def test_plan_workspace_grows_with_rounds():
