@@ -29,8 +29,10 @@ Algorithm 1's decode loop against plain attention over the whole uncompressed
 history on caches made of runs of identical tokens (online loop).  Parity
 unpinned: the POLICY that picks r for a decode-time clustering call and the
 floor that lets the annealed loop reach its budget are readings, not facts of
-the paper (the arithmetic for a given r is pinned); global top-r is not
-implemented here.
+the paper (the arithmetic for a given r is pinned).  Selection over all chunks
+of a sequence (scope "head") is pinned by exhaustive search over merge sets on
+tiny inputs, by its agreement with the per-chunk rule at r = 1 and on a single
+chunk, and by the dominance of every kept edge over every dropped one.
 """
 from __future__ import annotations
 
@@ -146,6 +148,23 @@ def select(src, dst, score, s: int, c: int, r: float, tau: float = TAU):
     return keep, cut_ties
 
 
+def select_global(src, dst, score, r: float, tau: float = TAU):
+    """The other reading of Sec. 5.2-5.3 ('aggregates the edges from all chunks', 'rank all
+    candidate matches'): the edges of ALL chunks of the sequence are ranked together and the
+    m = floor(r * number of edges) best are merged; ties go to the lower A position.  Returns the
+    keep mask and (cut score, True when the first dropped edge is within tau of it)."""
+    keep = np.zeros(len(src), dtype=bool)
+    idx = np.nonzero(np.asarray(dst) >= 0)[0]
+    m = merge_count(r, len(idx))
+    if m == 0:
+        return keep, (np.inf, False)
+    order = idx[np.lexsort((idx, -score[idx]))]        # score descending, position ascending
+    keep[order[:m]] = True
+    cut = float(score[order[m - 1]])
+    near = m < len(idx) and cut - float(score[order[m]]) < tau
+    return keep, (cut, bool(near))
+
+
 # --------------------------------------------------------------------------
 # Sec. 5.3: degree-weighted merge, order-preserving output
 # --------------------------------------------------------------------------
@@ -192,14 +211,22 @@ def clusterable_range(s: int, n_sink: int, n_recent: int):
     return n_sink, s - n_recent
 
 
-def csm_round(K, V, deg, c: int, r: float, dtype: str, tau: float = TAU, n_sink: int = 0, n_recent: int = 0):
+def csm_round(K, V, deg, c: int, r: float, dtype: str, tau: float = TAU, n_sink: int = 0, n_recent: int = 0,
+              scope: str = "chunk"):
     """One clustering round on one (layer, KV head) sequence: set sinks / recents aside, chunk
-    the rest, alternating partition, cosine similarity, per-A argmax edge, per-chunk top-r,
-    merge, and put the result back between the untouched sinks and recents (Sec. 5.2 + 5.3).
-    K, V: [s, d] fp64 holding storage-type values."""
+    the rest, alternating partition, cosine similarity, per-A argmax edge, top-r (per chunk, or
+    over all chunks of the sequence when scope == "head"), merge, and put the result back
+    between the untouched sinks and recents (Sec. 5.2 + 5.3).
+    K, V: [s, d] fp64 holding storage-type values.  cut_ties: the chunks whose cut falls in a
+    near-tie (scope "chunk"), or (cut score, near-tie flag) of the one cut (scope "head")."""
     lo, hi = clusterable_range(K.shape[0], n_sink, n_recent)
     src, dst, score, near = match(K[lo:hi], c, tau)
-    keep, cut_ties = select(src, dst, score, hi - lo, c, r, tau)
+    if scope == "head":
+        keep, cut_ties = select_global(src, dst, score, r, tau)
+    elif scope == "chunk":
+        keep, cut_ties = select(src, dst, score, hi - lo, c, r, tau)
+    else:
+        raise ValueError(scope)
     src = src + lo
     dst = np.where(dst >= 0, dst + lo, dst)
     Ko, Vo, dego, assign, Kx, Vx = merge(K, V, deg, src, dst, keep, dtype)
@@ -225,21 +252,29 @@ def direct_schedule(retain_ratio: float):
     return [1.0] * (J - 1) + [2.0 * (1.0 - rho * 2.0 ** (J - 1))]
 
 
-def round_lengths(s: int, c: int, rounds, n_sink: int = 0, n_recent: int = 0):
+def round_lengths(s: int, c: int, rounds, n_sink: int = 0, n_recent: int = 0, scope: str = "chunk"):
     """Sequence length after each round (pure integer arithmetic)."""
     out = [s]
     for r in rounds:
         lo, hi = clusterable_range(out[-1], n_sink, n_recent)
         n = out[-1] - (hi - lo)
+        edges = 0
         for g0, g1 in chunk_bounds(hi - lo, c):
             L = g1 - g0
             n_a, n_b = (L + 1) // 2, L // 2
-            n += L - (merge_count(r, n_a) if n_b > 0 else 0)
+            if scope == "chunk":
+                n += L - (merge_count(r, n_a) if n_b > 0 else 0)
+            else:
+                n += L
+                edges += n_a if n_b > 0 else 0
+        if scope != "chunk":
+            n -= merge_count(r, edges)
         out.append(n)
     return out
 
 
-def compress(K, V, c: int, rounds, dtype: str, deg=None, tau: float = TAU, n_sink: int = 0, n_recent: int = 0):
+def compress(K, V, c: int, rounds, dtype: str, deg=None, tau: float = TAU, n_sink: int = 0, n_recent: int = 0,
+             scope: str = "chunk"):
     """Repeat csm_round on the CURRENT cache with the same chunk size
     (Algorithm 1, the while-loop after prefill).  Degrees start at 1 and
     accumulate; the assignment maps compose.  Each round's rounded output is
@@ -249,7 +284,7 @@ def compress(K, V, c: int, rounds, dtype: str, deg=None, tau: float = TAU, n_sin
     assign = np.arange(s, dtype=np.int64)
     per_round = []
     for r in rounds:
-        res = csm_round(K, V, deg, c, r, dtype, tau, n_sink, n_recent)
+        res = csm_round(K, V, deg, c, r, dtype, tau, n_sink, n_recent, scope)
         K, V, deg = res["K"], res["V"], res["deg"]
         assign = res["assign"][assign]
         per_round.append(res)

@@ -274,3 +274,76 @@ def test_sinks_and_recents_over_rounds_and_short_caches():
     short = compress(K[:70], V[:70], c, [1.0], "f32", n_sink=n1, n_recent=n2)
     assert np.array_equal(short["K"], K[:70].astype(np.float32).astype(np.float64))
     assert list(short["assign"]) == list(range(70))
+
+
+# ---- selection over all chunks of a sequence (scope "head") --------------------------------
+def test_global_selection_is_the_exhaustive_optimum_on_tiny_sequences():
+    """Two or three tiny chunks: over every set of m A-tokens (from any chunk) and every map of
+    each into a B token of ITS OWN chunk, the total similarity is maximal for the oracle's
+    choice (scope "head"), uniquely so when nothing is flagged as a near-tie."""
+    checked = 0
+    for c, s in ((4, 8), (4, 10), (2, 6), (4, 11)):
+        for r in (1.0, 0.6, 0.34):
+            for seed in range(5):
+                K, V = _kv(7000 + 10 * s + seed, s, 8)
+                res = csm_round(K, V, np.ones(s, dtype=np.int64), c, r, "f32", scope="head")
+                bounds = [(g, min(g + c, s)) for g in range(0, s, c)]
+                cand = []                                     # (a, [its chunk's B tokens])
+                for g0, g1 in bounds:
+                    Bs = list(range(g0 + 1, g1, 2))
+                    if Bs:
+                        cand += [(a, Bs) for a in range(g0, g1, 2)]
+                m = merge_count(r, len(cand))
+                assert res["keep"].sum() == m
+                best, arg, n_best = -np.inf, None, 0
+                for T in itertools.combinations(cand, m):
+                    for phi in itertools.product(*[Bs for _, Bs in T]):
+                        tot = sum(_cos(K[a], K[b]) for (a, _), b in zip(T, phi))
+                        if tot > best + 1e-12:
+                            best, arg, n_best = tot, (tuple(a for a, _ in T), phi), 1
+                        elif abs(tot - best) <= 1e-12:
+                            n_best += 1
+                kept = np.nonzero(res["keep"])[0]
+                got_T = tuple(int(res["src"][i]) for i in kept)
+                got_phi = tuple(int(res["dst"][i]) for i in kept)
+                got = sum(_cos(K[a], K[b]) for a, b in zip(got_T, got_phi))
+                assert abs(got - best) < 1e-12
+                if not res["near_tie"].any() and not res["cut_ties"][1] and n_best == 1:
+                    assert (got_T, got_phi) == arg
+                    checked += 1
+    assert checked > 40
+
+
+def test_global_selection_properties():
+    K, V = _kv(77, 1000, 16)
+    deg = np.ones(1000, dtype=np.int64)
+    # r = 1 merges every edge under both rules; one chunk covering the sequence: the rules coincide
+    for c, r in ((64, 1.0), (1000, 0.4)):
+        a = csm_round(K, V, deg, c, r, "f32")
+        b = csm_round(K, V, deg, c, r, "f32", scope="head")
+        assert np.array_equal(a["keep"], b["keep"]) and np.array_equal(a["K"], b["K"])
+    # every kept edge scores at least as high as every dropped one; the count is floor(r * edges)
+    res = csm_round(K, V, deg, 64, 0.3, "f32", scope="head")
+    has_b = res["dst"] >= 0
+    assert res["keep"].sum() == merge_count(0.3, int(has_b.sum()))
+    assert res["score"][res["keep"]].min() >= res["score"][has_b & ~res["keep"]].max()
+    assert res["K"].shape[0] == round_lengths(1000, 64, [0.3], scope="head")[-1] == 1000 - 150
+    # per-chunk counts now differ from chunk to chunk (that is the point of the global rule)
+    per_chunk = np.bincount(res["src"][res["keep"]] // 64, minlength=16)
+    assert per_chunk.min() < per_chunk.max()
+    # exact ties across chunks go to the lower position: identical chunks repeated
+    Kt = np.tile(K[:8], (4, 1))
+    res = csm_round(Kt, Kt.copy(), np.ones(32, dtype=np.int64), 8, 0.5, "f32", scope="head")
+    kept_pos = res["src"][res["keep"]]
+    assert len(kept_pos) == 8
+    best_in_chunk = np.argsort(-res["score"][:4], kind="stable")          # chunk 0's edges, best first
+    # all four copies of the best edge, then of the second best: 8 edges
+    expect = sorted(int(8 * g + 2 * best_in_chunk[k]) for k in range(2) for g in range(4))
+    assert sorted(kept_pos.tolist()) == expect
+    # a tail chunk of a single token has no edge and is never counted
+    assert round_lengths(9, 4, [1.0], scope="head") == [9, 5]
+    # with sinks / recents only the middle's edges are ranked
+    K = K.astype(np.float32).astype(np.float64)
+    res = csm_round(K, V, deg, 64, 0.3, "f32", n_sink=10, n_recent=20, scope="head")
+    assert res["K"].shape[0] == round_lengths(1000, 64, [0.3], 10, 20, scope="head")[-1]
+    assert np.array_equal(res["K"][:10], K[:10]) and np.array_equal(res["K"][-20:], K[-20:])
