@@ -68,7 +68,14 @@ typedef struct {
                                the round's output (Sec. 5.3); chunks, merge fractions and
                                retain_ratio's schedule apply to the tokens between them.  A cache
                                of at most n1+n2 tokens passes through a round unchanged.          */
+  int32_t scope;        /* how the top-r edges are chosen (Sec. 5.2-5.3 leave both readings open):
+                           CKV_SCOPE_CHUNK (0): the floor(r*|A|) best edges of every chunk;
+                           CKV_SCOPE_HEAD  (1): the edges of all chunks of a (batch, head)
+                           sequence ranked together, the floor(r*edges) best merged, ties to the
+                           lower position.  Equal at r = 1.                                     */
 } ckv_params;
+
+enum { CKV_SCOPE_CHUNK = 0, CKV_SCOPE_HEAD = 1 };
 
 typedef struct {
   int32_t out_seq;                       /* tokens per (batch, head) after the last round        */
@@ -120,12 +127,12 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
 /* Host only.  The annealed schedule of merge fractions (Eq. 4) run as Algorithm 1's loop after
  * prefill: starting from `seq` tokens, rounds j = 0, 1, ... with r_j = max(r_init - j*delta_r,
  * r_floor) are added while the cache is longer than `budget` tokens (budget = R*n in Algorithm 1).
- * Fills *out (chunk, n_sink, n_recent, n_rounds, r[]) for ckv_plan / ckv_compress; zero rounds
+ * Fills *out (chunk, n_sink, n_recent, scope, n_rounds, r[]) for ckv_plan / ckv_compress; zero rounds
  * (budget already met) gives the identity.  The paper states no floor: r_floor = 0 is Eq. 4 as
  * printed, and then CKV_EUNSUPPORTED is returned when a round removes nothing while the cache is
  * still above the budget, or when more than CKV_MAX_ROUNDS rounds would be needed. */
-int ckv_schedule_annealed(int32_t seq, int32_t chunk, int32_t n_sink, int32_t n_recent, int32_t budget,
-                          float r_init, float delta_r, float r_floor, ckv_params* out);
+int ckv_schedule_annealed(int32_t seq, int32_t chunk, int32_t n_sink, int32_t n_recent, int32_t scope,
+                          int32_t budget, float r_init, float delta_r, float r_floor, ckv_params* out);
 
 /* Cache update of one decode step (Algorithm 1, decoding part: K = [K, k], V = [V, v], N = [N, 1]).
  *   k_new, v_new [batch, heads, dim] contiguous, the cache's dtype, device.

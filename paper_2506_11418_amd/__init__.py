@@ -34,7 +34,8 @@ class Layout(C.Structure):
 
 class Params(C.Structure):
     _fields_ = [("chunk", C.c_int32), ("retain_ratio", C.c_float), ("n_rounds", C.c_int32),
-                ("r", C.c_float * MAX_ROUNDS), ("n_sink", C.c_int32), ("n_recent", C.c_int32)]
+                ("r", C.c_float * MAX_ROUNDS), ("n_sink", C.c_int32), ("n_recent", C.c_int32),
+                ("scope", C.c_int32)]
 
 
 class PlanT(C.Structure):
@@ -68,7 +69,7 @@ def lib() -> C.CDLL:
         L.ckv_decode_attn_workspace.argtypes = [C.POINTER(Layout), i32, C.POINTER(C.c_size_t)]
         L.ckv_decode_attn.argtypes = [vp, i32, vp, vp, C.POINTER(Layout), vp, vp, C.c_float, vp, i32,
                                       vp, C.c_size_t, vp]
-        L.ckv_schedule_annealed.argtypes = [i32, i32, i32, i32, i32, C.c_float, C.c_float, C.c_float,
+        L.ckv_schedule_annealed.argtypes = [i32, i32, i32, i32, i32, i32, C.c_float, C.c_float, C.c_float,
                                             C.POINTER(Params)]
         L.ckv_append.argtypes = [vp, vp, vp, vp, vp, C.POINTER(Layout), vp, i32, vp]
         L.ckv_timing_enable.argtypes = [C.c_int]
@@ -99,10 +100,14 @@ def layout_of(t: torch.Tensor, deg: Optional[torch.Tensor] = None) -> Layout:
                   _DT[t.dtype], deg_stride)
 
 
+SCOPES = {"chunk": 0, "head": 1}
+
+
 def make_params(chunk: int, retain_ratio: float = 1.0, rounds: Optional[Sequence[float]] = None,
-                n_sink: int = 0, n_recent: int = 0) -> Params:
+                n_sink: int = 0, n_recent: int = 0, scope: str = "chunk") -> Params:
     p = Params()
     p.chunk, p.retain_ratio, p.n_sink, p.n_recent = chunk, retain_ratio, n_sink, n_recent
+    p.scope = SCOPES[scope]
     if rounds is not None:
         if not 0 < len(rounds) <= MAX_ROUNDS:
             raise ValueError("rounds must have 1..8 entries")
@@ -153,16 +158,18 @@ def match(K: torch.Tensor, chunk: int):
 def compress(K: torch.Tensor, V: torch.Tensor, chunk: int, retain_ratio: float = 1.0,
              rounds: Optional[Sequence[float]] = None, deg: Optional[torch.Tensor] = None,
              want_assign: bool = True, out: Optional[tuple] = None,
-             workspace: Optional[torch.Tensor] = None, n_sink: int = 0, n_recent: int = 0):
+             workspace: Optional[torch.Tensor] = None, n_sink: int = 0, n_recent: int = 0,
+             scope: str = "chunk"):
     """ckv_compress: returns (K', V', deg', assign or None).  K, V: [B,H,S,D] on the GPU.
     The first n_sink and last n_recent tokens bypass the clustering in every round.
+    scope: "chunk" = top-r inside every chunk, "head" = one ranking over all chunks of a sequence.
 
     `out` may pass preallocated (K_out, V_out, deg_out, assign) and `workspace` a uint8 tensor, so
     that a timed loop allocates nothing."""
     lay = layout_of(K, deg)
     if layout_of(V).dtype != lay.dtype or V.shape != K.shape:
         raise ValueError("K and V must have the same shape and dtype")
-    params = make_params(chunk, retain_ratio, rounds, n_sink, n_recent)
+    params = make_params(chunk, retain_ratio, rounds, n_sink, n_recent, scope)
     pl = plan(lay, params)
     B, H, S, D = K.shape
     if out is None:
@@ -212,11 +219,12 @@ def decode_attn(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, lens: Optiona
 
 
 def schedule_annealed(seq: int, chunk: int, budget: int, r_init: float = 0.8, delta_r: float = 0.2,
-                      r_floor: float = 0.0, n_sink: int = 0, n_recent: int = 0) -> list:
+                      r_floor: float = 0.0, n_sink: int = 0, n_recent: int = 0, scope: str = "chunk") -> list:
     """ckv_schedule_annealed: the merge fractions Algorithm 1's loop after prefill uses to bring
     `seq` tokens within `budget` under the annealed schedule."""
     p = Params()
-    st = lib().ckv_schedule_annealed(seq, chunk, n_sink, n_recent, budget, r_init, delta_r, r_floor, C.byref(p))
+    st = lib().ckv_schedule_annealed(seq, chunk, n_sink, n_recent, SCOPES[scope], budget, r_init, delta_r, r_floor,
+                                     C.byref(p))
     if st != 0:
         raise CkvError(st, "ckv_schedule_annealed")
     return list(p.r[: p.n_rounds])

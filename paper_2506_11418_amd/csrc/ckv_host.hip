@@ -61,19 +61,23 @@ void clusterable(int len, int n_sink, int n_recent, int* lo, int* hi) {
   *hi = len - n_recent;
 }
 
-int seq_after_round(int len, int chunk, float r, int n_sink, int n_recent) {
+int seq_after_round(int len, int chunk, float r, int n_sink, int n_recent, int scope) {
   int lo, hi;
   clusterable(len, n_sink, n_recent, &lo, &hi);
   const int mid = hi - lo;
   const int full = mid / chunk, tail = mid % chunk;
+  if (scope == CKV_SCOPE_HEAD) {   // one ranking over the edges of all chunks
+    const int edges = full * (chunk / 2) + (tail >= 2 ? (tail + 1) / 2 : 0);
+    return len - merge_count(r, edges);
+  }
   return (len - mid) + full * chunk_out(chunk, r) + chunk_out(tail, r);
 }
 
 struct Workspace {
-  size_t dst, score, map, K[2], V[2], deg[2], total;
+  size_t dst, score, sel, map, K[2], V[2], deg[2], total;
 };
 
-Workspace carve(const ckv_layout* in, const ckv_plan_t* plan, int chunk) {
+Workspace carve(const ckv_layout* in, const ckv_plan_t* plan, int chunk, int scope) {
   Workspace w{};
   const size_t n_bh = (size_t)in->batch * in->heads;
   const size_t e = elem_bytes(in->dtype);
@@ -82,6 +86,7 @@ Workspace carve(const ckv_layout* in, const ckv_plan_t* plan, int chunk) {
   const size_t n_src0 = n_sources(in->seq, chunk);
   w.dst = take(n_bh * n_src0 * 4);
   w.score = take(n_bh * n_src0 * 4);
+  if (scope == CKV_SCOPE_HEAD) w.sel = take(n_bh * (size_t)div_up(in->seq, chunk) * 8);
   const int inter = plan->n_rounds - 1;   // intermediate caches
   if (inter >= 1) w.map = take(n_bh * (size_t)plan->round_len[1] * 4);
   for (int k = 0; k < 2 && k < inter; ++k) {
@@ -100,6 +105,7 @@ int make_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan) {
   if (!p || !plan) return CKV_EINVAL;
   if (p->chunk < 2 || p->chunk > 2048 || (p->chunk & 1)) return CKV_EINVAL;
   if (p->n_sink < 0 || p->n_recent < 0) return CKV_EINVAL;
+  if (p->scope != CKV_SCOPE_CHUNK && p->scope != CKV_SCOPE_HEAD) return CKV_EINVAL;
   if (p->n_rounds < 0 || p->n_rounds > CKV_MAX_ROUNDS) return CKV_EINVAL;
   memset(plan, 0, sizeof(*plan));
   if (p->n_rounds > 0) {
@@ -120,9 +126,10 @@ int make_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan) {
   }
   plan->round_len[0] = in->seq;
   for (int j = 0; j < plan->n_rounds; ++j)
-    plan->round_len[j + 1] = seq_after_round(plan->round_len[j], p->chunk, plan->round_r[j], p->n_sink, p->n_recent);
+    plan->round_len[j + 1] = seq_after_round(plan->round_len[j], p->chunk, plan->round_r[j], p->n_sink, p->n_recent,
+                                             p->scope);
   plan->out_seq = plan->round_len[plan->n_rounds];
-  plan->workspace_bytes = carve(in, plan, p->chunk).total;
+  plan->workspace_bytes = carve(in, plan, p->chunk, p->scope).total;
   return CKV_OK;
 }
 
@@ -257,7 +264,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     return hip_status(err);
   }
 
-  const Workspace w = carve(in, &plan, p->chunk);
+  const Workspace w = carve(in, &plan, p->chunk, p->scope);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   int32_t* dst = reinterpret_cast<int32_t*>(ws + w.dst);
   float* score = reinterpret_cast<float*>(ws + w.score);
@@ -274,6 +281,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     // rounds j and j+1 in one pass when the first merges every edge and the shape has a kernel
     const bool fuse = allow_fused && j + 1 < plan.n_rounds &&
                       p->n_sink == 0 && p->n_recent == 0 && curView.deg_stride == len &&
+                      p->scope == CKV_SCOPE_CHUNK &&
                       fused2_supported(in->dtype, in->dim, p->chunk, len, plan.round_r[j]) &&
                       curView.stride_s <= (1 << 18) && out->stride_s <= (1 << 18);
     const int jo = fuse ? j + 1 : j;                 // index of the round whose output is produced
@@ -299,10 +307,16 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
         const unsigned char* mV = static_cast<const unsigned char*>(curV) + (size_t)lo * curView.stride_s * e;
         err = launch_match(mK, in->dtype, in->dim, curView, n_bh, mid, p->chunk, dst, score, s);
         if (err != hipSuccess) return hip_status(err);
+        int32_t* sel = nullptr;
+        if (p->scope == CKV_SCOPE_HEAD) {
+          sel = reinterpret_cast<int32_t*>(ws + w.sel);
+          err = launch_global_select(score, n_bh, mid, p->chunk, plan.round_r[j], sel, s);
+          if (err != hipSuccess) return hip_status(err);
+        }
         err = launch_merge(mK, mV, curDeg ? curDeg + lo : nullptr, in->dtype, in->dim, curView, n_bh, mid, p->chunk,
                            plan.round_r[j], dst, score, static_cast<unsigned char*>(oK) + (size_t)lo * oView.stride_s * e,
                            static_cast<unsigned char*>(oV) + (size_t)lo * oView.stride_s * e, oDeg + lo, oView,
-                           oDegStride, map ? map + lo : nullptr, curView.deg_stride, len, lo, s);
+                           oDegStride, map ? map + lo : nullptr, curView.deg_stride, len, lo, sel, s);
         if (err != hipSuccess) return hip_status(err);
       }
       if (mid < len)   // sinks and recents (or a cache too short to cluster): straight copy
@@ -320,8 +334,9 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
   return CKV_OK;
 }
 
-int ckv_schedule_annealed(int32_t seq, int32_t chunk, int32_t n_sink, int32_t n_recent, int32_t budget,
-                          float r_init, float delta_r, float r_floor, ckv_params* out) {
+int ckv_schedule_annealed(int32_t seq, int32_t chunk, int32_t n_sink, int32_t n_recent, int32_t scope,
+                          int32_t budget, float r_init, float delta_r, float r_floor, ckv_params* out) {
+  if (scope != CKV_SCOPE_CHUNK && scope != CKV_SCOPE_HEAD) return CKV_EINVAL;
   if (!out || seq <= 0 || budget < 0 || n_sink < 0 || n_recent < 0) return CKV_EINVAL;
   if (chunk < 2 || chunk > 2048 || (chunk & 1)) return CKV_EINVAL;
   if (!(r_init >= 0.f && r_init <= 1.f) || !(delta_r >= 0.f) || !(r_floor >= 0.f && r_floor <= 1.f)) return CKV_EINVAL;
@@ -330,12 +345,13 @@ int ckv_schedule_annealed(int32_t seq, int32_t chunk, int32_t n_sink, int32_t n_
   out->retain_ratio = 1.0f;
   out->n_sink = n_sink;
   out->n_recent = n_recent;
+  out->scope = scope;
   int len = seq, j = 0;
   while (len > budget) {
     if (j == CKV_MAX_ROUNDS) return CKV_EUNSUPPORTED;
     const double want = (double)r_init - (double)j * (double)delta_r;
     const float r = (float)(want > (double)r_floor ? want : (double)r_floor);
-    const int next = seq_after_round(len, chunk, r, n_sink, n_recent);
+    const int next = seq_after_round(len, chunk, r, n_sink, n_recent, scope);
     if (next == len) return CKV_EUNSUPPORTED;   // the schedule has run dry above the budget
     out->r[j++] = r;
     len = next;

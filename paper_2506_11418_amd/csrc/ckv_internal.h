@@ -51,7 +51,14 @@ hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int
                         TensorView in, int n_bh, int seq, int chunk, float r,
                         const int32_t* dst_local, const float* score, void* K_out, void* V_out,
                         int32_t* deg_out, TensorView out, int64_t deg_out_stride, int32_t* map_out,
-                        int64_t deg_in_stride, int64_t map_stride, int map_offset, hipStream_t st);
+                        int64_t deg_in_stride, int64_t map_stride, int map_offset, const int32_t* sel_table,
+                        hipStream_t st);
+
+// Selection over all chunks of a sequence: from the match scores, table[bh, chunk] = (edges of the
+// chunk among the sequence's floor(r * edges) best, first output row of the chunk), two int32 each.
+// launch_merge with sel_table = table then merges exactly those.
+hipError_t launch_global_select(const float* score, int n_bh, int seq, int chunk, float r, int32_t* table,
+                                hipStream_t st);
 
 // Decode-step cache update: row lens[b] (device, then incremented) or `pos` of every (batch, head)
 // := (k_new, v_new, degree 1).  k_new, v_new: [batch, heads, dim] contiguous.

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     int seq, int chunk, int n_chunks, float r, const int32_t* __restrict__ dst_local,
     const float* __restrict__ score, T* __restrict__ K_out, T* __restrict__ V_out,
     int32_t* __restrict__ deg_out, TensorView out, int64_t deg_out_stride, int32_t* __restrict__ map_out,
-    int64_t deg_in_stride, int64_t map_stride, int map_offset) {
+    int64_t deg_in_stride, int64_t map_stride, int map_offset, const int2* __restrict__ sel_table) {
   constexpr int E = Row<T>::E;
   constexpr int LPR = D / E;                 // lanes per row
   constexpr int NRG = kThreads / LPR;        // row groups per workgroup
@@ -106,9 +106,18 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   const int tid = threadIdx.x;
   const int g0 = g * chunk, L = min(chunk, seq - g0);
   const int nA = (L + 1) >> 1, nB = L >> 1;
-  const int m = (nB > 0) ? merge_count(r, nA) : 0;
+  // edges merged in this chunk and its first output row: fixed by r alone for per-chunk selection,
+  // read from the table of the sequence-wide selection otherwise
+  int m, out_base;
+  if (sel_table) {
+    const int2 e = sel_table[(int64_t)bh * n_chunks + g];
+    m = e.x;
+    out_base = e.y;
+  } else {
+    m = (nB > 0) ? merge_count(r, nA) : 0;
+    out_base = g * chunk_out(chunk, r);
+  }
   const int n_out = L - m;
-  const int out_base = g * chunk_out(chunk, r);
   const int n_src = n_sources(seq, chunk);
   const int64_t src_base = (int64_t)bh * n_src + (int64_t)g * (chunk >> 1);
   const int nA_pad = (nA + 7) & ~7;
@@ -399,7 +408,7 @@ hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, T
                           int seq, int chunk, float r, const int32_t* dst_local, const float* score,
                           void* K_out, void* V_out, int32_t* deg_out, TensorView out,
                           int64_t deg_out_stride, int32_t* map_out, int64_t deg_in_stride, int64_t map_stride,
-                          int map_offset, hipStream_t st) {
+                          int map_offset, const int32_t* sel_table, hipStream_t st) {
   const int n_chunks = div_up(seq, chunk);
   const int64_t total = (int64_t)n_bh * n_chunks;
   if (total > (1 << 30)) return hipErrorInvalidValue;
@@ -407,7 +416,8 @@ hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, T
   hipLaunchKernelGGL((merge_kernel<T, D>), dim3((int)total), dim3(kThreads), 0, st,
                      static_cast<const T*>(K), static_cast<const T*>(V), deg_in, in, seq, chunk, n_chunks,
                      r, dst_local, score, static_cast<T*>(K_out), static_cast<T*>(V_out), deg_out, out,
-                     deg_out_stride, map_out, deg_in_stride, map_stride, map_offset);
+                     deg_out_stride, map_out, deg_in_stride, map_stride, map_offset,
+                     reinterpret_cast<const int2*>(sel_table));
   return hipGetLastError();
 }
 
@@ -417,10 +427,12 @@ hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int
                         TensorView in, int n_bh, int seq, int chunk, float r,
                         const int32_t* dst_local, const float* score, void* K_out, void* V_out,
                         int32_t* deg_out, TensorView out, int64_t deg_out_stride, int32_t* map_out,
-                        int64_t deg_in_stride, int64_t map_stride, int map_offset, hipStream_t st) {
+                        int64_t deg_in_stride, int64_t map_stride, int map_offset, const int32_t* sel_table,
+                        hipStream_t st) {
 #define CKV_MERGE(T, DD)                                                                             \
   return launch_merge_t<T, DD>(K, V, deg_in, in, n_bh, seq, chunk, r, dst_local, score, K_out, V_out, \
-                               deg_out, out, deg_out_stride, map_out, deg_in_stride, map_stride, map_offset, st)
+                               deg_out, out, deg_out_stride, map_out, deg_in_stride, map_stride, map_offset, \
+                               sel_table, st)
   if (dtype == CKV_BF16) {
     if (dim == 128) CKV_MERGE(__bf16, 128);
     if (dim == 64) CKV_MERGE(__bf16, 64);

@@ -77,9 +77,10 @@ def test_annealed_schedule_reports_a_budget_it_cannot_reach():
         ckv.schedule_annealed(1 << 20, 64, 100, 0.8, 0.2, 0.2)
     p = ckv.Params()
     L = ckv.lib()
-    assert L.ckv_schedule_annealed(1000, 63, 0, 0, 500, 0.8, 0.2, 0.0, C.byref(p)) == -1
-    assert L.ckv_schedule_annealed(1000, 64, 0, 0, 500, 1.5, 0.2, 0.0, C.byref(p)) == -1
-    assert L.ckv_schedule_annealed(1000, 64, 0, 0, 500, 0.8, 0.2, 0.0, None) == -1
+    assert L.ckv_schedule_annealed(1000, 63, 0, 0, 0, 500, 0.8, 0.2, 0.0, C.byref(p)) == -1
+    assert L.ckv_schedule_annealed(1000, 64, 0, 0, 0, 500, 1.5, 0.2, 0.0, C.byref(p)) == -1
+    assert L.ckv_schedule_annealed(1000, 64, 0, 0, 7, 500, 0.8, 0.2, 0.0, C.byref(p)) == -1
+    assert L.ckv_schedule_annealed(1000, 64, 0, 0, 0, 500, 0.8, 0.2, 0.0, None) == -1
 
 
 def test_append_rejects_bad_arguments_before_any_launch():
@@ -92,6 +93,20 @@ def test_append_rejects_bad_arguments_before_any_launch():
     bad = _lay(seq=128)
     bad.deg_stride = 100                                                       # rows would overlap
     assert L.ckv_append(a, a, a, a, z, C.byref(bad), z, 0, z) == -2
+
+
+@pytest.mark.parametrize("seq,chunk,rounds,n_sink,n_recent", [
+    (5000, 256, [0.3], 0, 0), (5001, 256, [0.7, 0.45], 16, 64), (777, 32, [1.0, 0.5, 0.25], 3, 0), (9, 4, [1.0], 0, 0),
+    (131072, 1024, [0.8, 0.6], 16, 64),
+])
+def test_plan_with_selection_over_the_whole_sequence(seq, chunk, rounds, n_sink, n_recent):
+    pl = ckv.plan(_lay(seq=seq), ckv.make_params(chunk, rounds=rounds, n_sink=n_sink, n_recent=n_recent, scope="head"))
+    assert pl.round_len == round_lengths(seq, chunk, rounds, n_sink, n_recent, scope="head")
+    per_chunk = ckv.plan(_lay(seq=seq), ckv.make_params(chunk, rounds=rounds, n_sink=n_sink, n_recent=n_recent))
+    assert pl.workspace_bytes > per_chunk.workspace_bytes or pl.round_len != per_chunk.round_len
+    bad = ckv.make_params(chunk, rounds=rounds)
+    bad.scope = 3
+    assert ckv.lib().ckv_plan(C.byref(_lay(seq=seq)), C.byref(bad), C.byref(ckv.PlanT())) == -1
 
 
 def test_plan_workspace_grows_with_rounds():

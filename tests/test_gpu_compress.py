@@ -200,6 +200,61 @@ def test_sinks_and_recents_with_strided_layout_and_retain_ratio():
     assert int(odeg.sum()) == int(deg.sum())
 
 
+# ---- top-r over all chunks of a sequence (the other reading of Sec. 5.2-5.3) --------------------
+@pytest.mark.parametrize("dtype,heads,seq,dim,chunk,rounds,n_sink,n_recent", [
+    ("bf16", 2, 8192, 128, 1024, [0.5], 0, 0),
+    ("bf16", 2, 4096 + 80, 128, 256, [0.8, 0.6], 16, 64),
+    ("bf16", 1, 3001, 128, 512, [0.3, 0.9], 0, 0),                # ragged tail chunk, odd length
+    ("bf16", 2, 1000, 64, 16, [0.5, 0.5], 4, 0),                  # many small chunks: a thread per chunk
+    ("bf16", 1, 4097, 128, 2, [0.25], 0, 0),                      # chunk 2: one edge per chunk, one-token tail
+    ("f32", 1, 1024, 64, 64, [0.7, 0.2], 0, 8),
+    ("bf16", 2, 2048, 128, 256, [1.0, 0.0], 0, 0),                # all edges / no edge
+    ("bf16", 1, 70000, 128, 2048, [0.45], 0, 0),                  # several scan tiles' worth of edges
+])
+def test_compress_with_selection_over_the_whole_sequence(dtype, heads, seq, dim, chunk, rounds, n_sink, n_recent):
+    _say(f"scope=head {dtype} H={heads} S={seq} D={dim} c={chunk} rounds={rounds} n1={n_sink} n2={n_recent}")
+    K, V, _ = kv_host(41, heads, seq, dim, dtype, alpha=0.9, n_outlier=4 if dim == 128 else 0)
+    K, V = K.to(DEV), V.to(DEV)
+    curK, curV, curdeg, maps, alt = K, V, None, [], 0
+    for j, r in enumerate(rounds):
+        gK, gV, gdeg, gas = ckv.compress(curK, curV, chunk, rounds=[r], deg=curdeg, n_sink=n_sink, n_recent=n_recent,
+                                         scope="head")
+        torch.cuda.synchronize()
+        for h in range(heads):
+            d_in = np.ones(curK.shape[2], dtype=np.int64) if curdeg is None else i64(curdeg[0, h])
+            alt += check_round_with_edges(f64(curK[0, h]), f64(curV[0, h]), d_in, chunk, r, dtype, n_sink, n_recent,
+                                          f64(gK[0, h]), f64(gV[0, h]), i64(gdeg[0, h]), i64(gas[0, h]),
+                                          what=f"scope=head round {j} h{h}", scope="head")
+        curK, curV, curdeg = gK, gV, gdeg
+        maps.append(gas.to(torch.int64))
+    _say(f"  {alt} edges inside the near-tie band resolved differently")
+    gK, gV, gdeg, gas = ckv.compress(K, V, chunk, rounds=rounds, n_sink=n_sink, n_recent=n_recent, scope="head")
+    torch.cuda.synchronize()
+    assert gK.shape[2] == oracle.round_lengths(seq, chunk, rounds, n_sink, n_recent, scope="head")[-1]
+    assert torch.equal(gK, curK) and torch.equal(gV, curV) and torch.equal(gdeg, curdeg)
+    comp = maps[0]
+    for m in maps[1:]:
+        comp = torch.gather(m, 2, comp)
+    assert torch.equal(gas.to(torch.int64), comp)
+    assert int(gdeg.sum()) == heads * seq
+
+
+def test_whole_sequence_selection_ties_across_identical_chunks():
+    """Identical chunks give exactly equal scores in every chunk: the quota of edges ON the cut
+    goes to the lowest positions, so the first chunks merge one edge more than the last."""
+    _say("scope=head exact ties")
+    base, _, _ = kv_host(43, 1, 64, 128, "bf16", alpha=0.9, n_outlier=4)
+    K = base.repeat(1, 1, 8, 1).to(DEV)                      # 8 identical chunks of 64
+    V = K.clone()
+    gK, gV, gdeg, gas = ckv.compress(K, V, 64, rounds=[0.3], scope="head")     # floor(0.3 * 256) = 76 = 9*8 + 4
+    torch.cuda.synchronize()
+    a = i64(gas[0, 0])
+    merged_per_chunk = [64 - len(np.unique(a[g * 64:(g + 1) * 64])) for g in range(8)]
+    assert merged_per_chunk == [10, 10, 10, 10, 9, 9, 9, 9]
+    check_round_with_edges(f64(K[0, 0]), f64(V[0, 0]), np.ones(512, dtype=np.int64), 64, 0.3, "bf16", 0, 0,
+                           f64(gK[0, 0]), f64(gV[0, 0]), i64(gdeg[0, 0]), a, what="ties", scope="head")
+
+
 # ---- layouts, degrees, degenerate inputs ------------------------------------------------------
 def test_bshd_layout_and_padded_output():
     _say("compress strided layout")

@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import paper_2506_11418_amd as ckv
-from parity_util import ATTN_TOL, assert_rows_close, check_round, f64, i64
+from parity_util import ATTN_TOL, assert_rows_close, check_round, check_round_with_edges, f64, i64
 from synth import kv_device
 
 pytestmark = pytest.mark.gpu
@@ -88,6 +88,40 @@ def test_decode_attention_over_the_compressed_layer(full_cache, layer):
     torch.cuda.synchronize()
     ref = oracle.app_attn(f64(q[0]), f64(cK[layer]), f64(cV[layer]), i64(cdeg[layer]))
     assert_rows_close(f64(o[0]), ref, ATTN_TOL, f"layer {layer}")
+
+
+# ---- the paper's default-style setting at 128k tokens: sinks 16, recents 64, annealed r, one ranking per head ----
+def test_128k_layer_with_sinks_recents_annealed_schedule_and_whole_sequence_selection():
+    """One layer (8 KV heads x 131072 tokens), chunk 1024, n1 = 16, n2 = 64, merge fractions 0.8 then
+    0.6 (Eq. 4), top-r over all chunks of a head.  Invariants on every head; two heads round by
+    round against the oracle, and the one call must equal the rounds issued one by one."""
+    _say("128k layer: sinks/recents, annealed schedule, scope=head")
+    n1, n2, rounds = 16, 64, [0.8, 0.6]
+    K = torch.empty((1, HEADS, SEQ, DIM), dtype=torch.bfloat16, device=DEV)
+    V = torch.empty_like(K)
+    kv_device(808, HEADS, SEQ, DIM, "bf16", 0.9, 4, layer=0, device=DEV, out_k=K[0], out_v=V[0])
+    cK, cV, cdeg, assign = ckv.compress(K, V, CHUNK, rounds=rounds, n_sink=n1, n_recent=n2, scope="head")
+    torch.cuda.synchronize()
+    out_len = oracle.round_lengths(SEQ, CHUNK, rounds, n1, n2, scope="head")[-1]
+    assert cK.shape == (1, HEADS, out_len, DIM)
+    assert torch.equal(cdeg.sum(dim=-1), torch.full((1, HEADS), SEQ, dtype=torch.int64, device=DEV))
+    assert torch.equal(cK[:, :, :n1], K[:, :, :n1]) and torch.equal(cV[:, :, -n2:], V[:, :, -n2:])
+    counts = torch.zeros((HEADS, out_len), dtype=torch.int32, device=DEV)
+    counts.scatter_add_(1, assign[0].to(torch.int64), torch.ones((HEADS, SEQ), dtype=torch.int32, device=DEV))
+    assert torch.equal(counts, cdeg[0])
+    for h in (2, 7):
+        _say(f"  oracle check of head {h}")
+        curK, curV, curdeg = K[:, h:h + 1].contiguous(), V[:, h:h + 1].contiguous(), None
+        for j, r in enumerate(rounds):
+            gK, gV, gdeg, gas = ckv.compress(curK, curV, CHUNK, rounds=[r], deg=curdeg, n_sink=n1, n_recent=n2,
+                                             scope="head")
+            torch.cuda.synchronize()
+            d_in = np.ones(curK.shape[2], dtype=np.int64) if curdeg is None else i64(curdeg[0, 0])
+            check_round_with_edges(f64(curK[0, 0]), f64(curV[0, 0]), d_in, CHUNK, r, "bf16", n1, n2, f64(gK[0, 0]),
+                                   f64(gV[0, 0]), i64(gdeg[0, 0]), i64(gas[0, 0]), what=f"head {h} round {j}",
+                                   scope="head")
+            curK, curV, curdeg = gK, gV, gdeg
+        assert torch.equal(cK[0, h], curK[0, 0]) and torch.equal(cdeg[0, h], curdeg[0, 0])
 
 
 # ---- serving decode shape (batch 16, pre-compressed caches, appended tokens) --------------------
