@@ -128,6 +128,17 @@ __device__ __forceinline__ uint4 round_div_pack_bf16(const float* acc, int n) {
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Streaming 16-byte accesses: rows that are read or written once and not reused by this kernel
+// are marked non-temporal so they do not displace reusable lines from the caches.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ldg16_stream(const void* p) {
+  const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stg16_stream(void* p, const uint4& r) {
+  __builtin_nontemporal_store(u32x4{r.x, r.y, r.z, r.w}, static_cast<u32x4*>(p));
+}
+
 // 16-byte load at a 32-bit byte offset from a workgroup-uniform base (the compiler then uses the
 // scalar-base + vector-offset addressing form: no 64-bit address arithmetic per lane).
 __device__ __forceinline__ uint4 ldg16(const void* base, uint32_t byte_off) {

@@ -49,12 +49,10 @@ struct Row<__bf16> {
   static constexpr int E = 8;
   typedef float Acc;
   typedef uint4 Raw;
-  __device__ static Raw load_raw(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
-  __device__ static void store_raw(__bf16* p, const Raw& r) { *reinterpret_cast<uint4*>(p) = r; }
+  __device__ static Raw load_raw(const __bf16* p) { return ldg16_stream(p); }
+  __device__ static void store_raw(__bf16* p, const Raw& r) { stg16_stream(p, r); }
   __device__ static void fma_into(Acc* acc, const Raw& u, int w) { fma_bf16x8(acc, u, w); }
-  __device__ static void store_div(__bf16* p, const Acc* acc, int n) {
-    *reinterpret_cast<uint4*>(p) = round_div_pack_bf16(acc, n);
-  }
+  __device__ static void store_div(__bf16* p, const Acc* acc, int n) { stg16_stream(p, round_div_pack_bf16(acc, n)); }
 };
 
 template <>

@@ -7,6 +7,7 @@
 #include <type_traits>
 
 #include "ckv_internal.h"
+#include "ckv_device.h"
 
 namespace ckv {
 namespace {
@@ -20,7 +21,7 @@ template <>
 struct Elems<__bf16> {
   static constexpr int E = 8;
   typedef uint4 Raw;
-  __device__ static Raw load_raw(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
+  __device__ static Raw load_raw(const __bf16* p) { return ldg16_stream(p); }
   __device__ static void unpack(const Raw& u, float* x) {
     const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
