@@ -265,6 +265,36 @@ def main():
                    "attn_partial_us": round(us, 2), "GBps": round(byts / us / 1e3, 1),
                    "frac_of_hbm_peak": round(byts / us / 1e3 / PEAK_HBM_GBS, 4),
                    "attn_combine_us": round(tt["attn_combine"][0] / tt["attn_combine"][1] * 1e3, 2)}
+        # the same tokens in a block-paged pool (blocks of 16 tokens, shuffled), read in place
+        bs = 16
+        nblk = Bs * Ls // bs
+        perm = torch.randperm(nblk, generator=gen, device=dev).to(torch.int32)
+        table = perm.reshape(Bs, Ls // bs).contiguous()
+        idx = table.to(torch.int64)
+        K_pool = torch.empty((nblk, H, bs, D), dtype=torch.bfloat16, device=dev)
+        V_pool = torch.empty_like(K_pool)
+        deg_pool = torch.empty((nblk, H, bs), dtype=torch.int32, device=dev)
+        K_pool[idx.flatten()] = gK.reshape(Bs, H, Ls // bs, bs, D).permute(0, 2, 1, 3, 4).reshape(nblk, H, bs, D)
+        V_pool[idx.flatten()] = gV.reshape(Bs, H, Ls // bs, bs, D).permute(0, 2, 1, 3, 4).reshape(nblk, H, bs, D)
+        deg_pool[idx.flatten()] = gdeg.reshape(Bs, H, Ls // bs, bs).permute(0, 2, 1, 3).reshape(nblk, H, bs)
+        plens = torch.full((Bs,), Ls, dtype=torch.int32, device=dev)
+        po = torch.empty_like(gq)
+        for _ in range(3):
+            ckv.paged_decode_attn(gq, K_pool, V_pool, deg_pool, table, plens, Ls, out=po, workspace=gws)
+        torch.cuda.synchronize()
+        if not torch.equal(po, go):
+            raise RuntimeError("paged attention differs from strided attention on the same tokens")
+        ckv.timing_reset()
+        ckv.timing_enable(True)
+        for _ in range(20):
+            ckv.paged_decode_attn(gq, K_pool, V_pool, deg_pool, table, plens, Ls, out=po, workspace=gws)
+        torch.cuda.synchronize()
+        ckv.timing_enable(False)
+        tp = ckv.timing_read()
+        pus = tp["attn_partial_paged_bf16"][0] / tp["attn_partial_paged_bf16"][1] * 1e3
+        serving["paged_block16_attn_partial_us"] = round(pus, 2)
+        serving["paged_block16_GBps"] = round(byts / pus / 1e3, 1)
+        del K_pool, V_pool, deg_pool
 
     dec_bytes = work["attn_partial_bf16"]
     out = {

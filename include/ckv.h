@@ -163,6 +163,54 @@ int ckv_decode_attn(const void* q, int32_t q_heads, const void* K, const void* V
                     void* o, int32_t o_dtype, void* workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/* ---- block-paged caches (the layout a serving engine's block manager keeps) ------------------
+ * Pool: K_pool, V_pool [n_blocks, heads, block_size, dim] contiguous (inside a block the tokens of
+ * one head are contiguous: block_size*dim elements per (block, head), which keeps a head's
+ * stream in long runs), deg_pool [n_blocks, heads, block_size] int32.  block_table [batch, max_blocks] int32 (device): token t of
+ * sequence b lives in block block_table[b][t / block_size] at offset t % block_size.  An entry
+ * outside [0, n_blocks) is never dereferenced: its tokens are masked (attention), read as zero rows
+ * of degree 1 (gather) or skipped (scatter). */
+typedef struct {
+  int32_t batch, heads, dim, dtype; /* dtype: ckv_dtype */
+  int32_t block_size;               /* tokens per block: a power of two, 1..1024 */
+  int32_t max_blocks;               /* entries per row of the block table */
+  int32_t n_blocks;                 /* blocks in the pool */
+} ckv_paged_layout;
+
+/* ckv_decode_attn (Eq. 3) reading the paged cache in place.  lens [batch] int32 (device, required):
+ * tokens of each sequence; max_len: host upper bound on them (sizes the split of the sequence;
+ * lengths are clamped to it and to max_blocks*block_size).  deg_pool NULL = all ones (Eq. 1). */
+int ckv_paged_decode_attn_workspace(const ckv_paged_layout* pl, int32_t q_heads, int32_t max_len, size_t* bytes);
+int ckv_paged_decode_attn(const void* q, int32_t q_heads, const void* K_pool, const void* V_pool,
+                          const int32_t* deg_pool, const int32_t* block_table, const int32_t* lens,
+                          const ckv_paged_layout* pl, int32_t max_len, float scale, void* o, int32_t o_dtype,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Copy the first `seq` tokens of every sequence from the pool into strided tensors K, V (layout
+ * `out`, out->seq >= seq) and deg (row stride out->deg_stride; may be NULL), or back. */
+int ckv_paged_gather(const void* K_pool, const void* V_pool, const int32_t* deg_pool, const int32_t* block_table,
+                     const ckv_paged_layout* pl, int32_t seq, void* K, void* V, int32_t* deg,
+                     const ckv_layout* out, void* hip_stream);
+/* Scatter writes tokens [0, in->seq) of every sequence into its blocks and RELEASES the blocks the
+ * sequence no longer needs: with old_seq the length before, table entries
+ * [ceil(in->seq / bs), ceil(old_seq / bs)) are copied to freed [batch, n_freed] (may be NULL) and
+ * set to -1; lens[b] := in->seq when lens != NULL. */
+int ckv_paged_scatter(const void* K, const void* V, const int32_t* deg, const ckv_layout* in, void* K_pool,
+                      void* V_pool, int32_t* deg_pool, int32_t* block_table, const ckv_paged_layout* pl,
+                      int32_t old_seq, int32_t* freed, int32_t* lens, void* hip_stream);
+
+/* ckv_compress on sequences of `seq` tokens each that live in a paged cache, written back into the
+ * sequences' own first blocks (compaction), the blocks behind them released as in
+ * ckv_paged_scatter.  Stages through the workspace: gather -> ckv_compress -> scatter, i.e. one
+ * extra read and write of the cache and of the result on top of the clustering's own traffic.
+ * ckv_paged_compress_plan (host only) gives the length after compression, the number of blocks
+ * every sequence releases and the workspace size.  deg_pool is required (it receives the degrees). */
+int ckv_paged_compress_plan(const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, int32_t* out_seq,
+                            int32_t* n_freed, size_t* workspace_bytes);
+int ckv_paged_compress(void* K_pool, void* V_pool, int32_t* deg_pool, int32_t* block_table, int32_t* lens,
+                       const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, int32_t* freed,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Per-kernel timing for benchmarks.  When enabled, every kernel launch of the calling process
  * is bracketed by HIP events on its stream (a few microseconds of host overhead per launch).
  * ckv_timing_read synchronises with the recorded events, then fills up to `max` entries with the

@@ -38,6 +38,11 @@ class Params(C.Structure):
                 ("scope", C.c_int32)]
 
 
+class PagedLayout(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("heads", C.c_int32), ("dim", C.c_int32), ("dtype", C.c_int32),
+                ("block_size", C.c_int32), ("max_blocks", C.c_int32), ("n_blocks", C.c_int32)]
+
+
 class PlanT(C.Structure):
     _fields_ = [("out_seq", C.c_int32), ("n_rounds", C.c_int32),
                 ("round_len", C.c_int32 * (MAX_ROUNDS + 1)), ("round_r", C.c_float * MAX_ROUNDS),
@@ -72,6 +77,15 @@ def lib() -> C.CDLL:
         L.ckv_schedule_annealed.argtypes = [i32, i32, i32, i32, i32, i32, C.c_float, C.c_float, C.c_float,
                                             C.POINTER(Params)]
         L.ckv_append.argtypes = [vp, vp, vp, vp, vp, C.POINTER(Layout), vp, i32, vp]
+        PL = C.POINTER(PagedLayout)
+        L.ckv_paged_decode_attn_workspace.argtypes = [PL, i32, i32, C.POINTER(C.c_size_t)]
+        L.ckv_paged_decode_attn.argtypes = [vp, i32, vp, vp, vp, vp, vp, PL, i32, C.c_float, vp, i32, vp,
+                                            C.c_size_t, vp]
+        L.ckv_paged_gather.argtypes = [vp, vp, vp, vp, PL, i32, vp, vp, vp, C.POINTER(Layout), vp]
+        L.ckv_paged_scatter.argtypes = [vp, vp, vp, C.POINTER(Layout), vp, vp, vp, vp, PL, i32, vp, vp, vp]
+        L.ckv_paged_compress_plan.argtypes = [PL, i32, C.POINTER(Params), C.POINTER(i32), C.POINTER(i32),
+                                              C.POINTER(C.c_size_t)]
+        L.ckv_paged_compress.argtypes = [vp, vp, vp, vp, vp, PL, i32, C.POINTER(Params), vp, vp, C.c_size_t, vp]
         L.ckv_timing_enable.argtypes = [C.c_int]
         L.ckv_timing_read.argtypes = [C.POINTER(KernelTime), C.c_int]
         _lib = L
@@ -246,6 +260,98 @@ def append(k_new: torch.Tensor, v_new: torch.Tensor, K: torch.Tensor, V: torch.T
                           pos, _stream())
     if st != 0:
         raise CkvError(st, "ckv_append")
+
+
+# ---- block-paged caches ------------------------------------------------------------------------
+def paged_layout_of(K_pool: torch.Tensor, block_table: torch.Tensor) -> PagedLayout:
+    """K_pool: [n_blocks, heads, block_size, dim] contiguous; block_table: int32 [batch, max_blocks]."""
+    if K_pool.dim() != 4 or not K_pool.is_contiguous() or K_pool.dtype not in _DT:
+        raise ValueError("pool must be a contiguous [n_blocks, heads, block_size, dim] float32/bfloat16 tensor")
+    if block_table.dim() != 2 or block_table.dtype != torch.int32 or not block_table.is_contiguous():
+        raise ValueError("block_table must be a contiguous int32 [batch, max_blocks] tensor")
+    nb, H, bs, D = K_pool.shape
+    return PagedLayout(block_table.shape[0], H, D, _DT[K_pool.dtype], bs, block_table.shape[1], nb)
+
+
+def paged_decode_attn(q, K_pool, V_pool, deg_pool, block_table, lens, max_len: int, scale: float = 0.0,
+                      out_dtype=None, out=None, workspace=None):
+    """ckv_paged_decode_attn: Eq. 3 over a block-paged cache read in place."""
+    pl = paged_layout_of(K_pool, block_table)
+    q_heads = q.shape[1]
+    if not q.is_contiguous() or q.dim() != 3 or q.dtype != K_pool.dtype:
+        raise ValueError("q must be a contiguous [batch, q_heads, dim] tensor of the cache dtype")
+    if out is None:
+        out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
+    if workspace is None:
+        n = C.c_size_t(0)
+        st = lib().ckv_paged_decode_attn_workspace(C.byref(pl), q_heads, max_len, C.byref(n))
+        if st != 0:
+            raise CkvError(st, "ckv_paged_decode_attn_workspace")
+        workspace = torch.empty(n.value, dtype=torch.uint8, device=q.device)
+    st = lib().ckv_paged_decode_attn(_ptr(q), q_heads, _ptr(K_pool), _ptr(V_pool), _ptr(deg_pool), _ptr(block_table),
+                                     _ptr(lens), C.byref(pl), max_len, scale, _ptr(out), _DT[out.dtype],
+                                     _ptr(workspace), workspace.numel(), _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_paged_decode_attn")
+    return out
+
+
+def paged_gather(K_pool, V_pool, deg_pool, block_table, seq: int):
+    """ckv_paged_gather: the first `seq` tokens of every sequence as [batch, heads, seq, dim] tensors."""
+    pl = paged_layout_of(K_pool, block_table)
+    K = torch.empty((pl.batch, pl.heads, seq, pl.dim), dtype=K_pool.dtype, device=K_pool.device)
+    V = torch.empty_like(K)
+    deg = torch.empty((pl.batch, pl.heads, seq), dtype=torch.int32, device=K_pool.device)
+    lay = layout_of(K, deg)
+    st = lib().ckv_paged_gather(_ptr(K_pool), _ptr(V_pool), _ptr(deg_pool), _ptr(block_table), C.byref(pl), seq,
+                                _ptr(K), _ptr(V), _ptr(deg), C.byref(lay), _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_paged_gather")
+    return K, V, deg
+
+
+def paged_scatter(K, V, deg, K_pool, V_pool, deg_pool, block_table, old_seq: int, lens=None):
+    """ckv_paged_scatter: write [batch, heads, seq, dim] tensors into the sequences' blocks and
+    release the blocks behind them; returns the freed block ids [batch, n_freed]."""
+    pl = paged_layout_of(K_pool, block_table)
+    lay = layout_of(K, deg)
+    n_freed = -(-old_seq // pl.block_size) - (-(-K.shape[2] // pl.block_size))
+    freed = torch.empty((pl.batch, max(n_freed, 0)), dtype=torch.int32, device=K.device)
+    st = lib().ckv_paged_scatter(_ptr(K), _ptr(V), _ptr(deg), C.byref(lay), _ptr(K_pool), _ptr(V_pool),
+                                 _ptr(deg_pool), _ptr(block_table), C.byref(pl), old_seq, _ptr(freed), _ptr(lens),
+                                 _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_paged_scatter")
+    return freed
+
+
+def paged_compress_plan(pl: PagedLayout, seq: int, params: Params):
+    """(length after compression, blocks released per sequence, workspace bytes)."""
+    out_seq, n_freed, nbytes = C.c_int32(0), C.c_int32(0), C.c_size_t(0)
+    st = lib().ckv_paged_compress_plan(C.byref(pl), seq, C.byref(params), C.byref(out_seq), C.byref(n_freed),
+                                       C.byref(nbytes))
+    if st != 0:
+        raise CkvError(st, "ckv_paged_compress_plan")
+    return out_seq.value, n_freed.value, nbytes.value
+
+
+def paged_compress(K_pool, V_pool, deg_pool, block_table, seq: int, chunk: int, retain_ratio: float = 1.0,
+                   rounds=None, lens=None, n_sink: int = 0, n_recent: int = 0, scope: str = "chunk",
+                   workspace=None):
+    """ckv_paged_compress: compress the sequences in place in the paged cache; returns
+    (new length, freed block ids [batch, n_freed])."""
+    pl = paged_layout_of(K_pool, block_table)
+    params = make_params(chunk, retain_ratio, rounds, n_sink, n_recent, scope)
+    out_seq, n_freed, nbytes = paged_compress_plan(pl, seq, params)
+    freed = torch.empty((pl.batch, n_freed), dtype=torch.int32, device=K_pool.device)
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=K_pool.device)
+    st = lib().ckv_paged_compress(_ptr(K_pool), _ptr(V_pool), _ptr(deg_pool), _ptr(block_table), _ptr(lens),
+                                  C.byref(pl), seq, C.byref(params), _ptr(freed), _ptr(workspace),
+                                  workspace.numel(), _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_paged_compress")
+    return out_seq, freed
 
 
 def timing_enable(on: bool) -> None:

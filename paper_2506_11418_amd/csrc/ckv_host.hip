@@ -377,7 +377,7 @@ int ckv_decode_attn_workspace(const ckv_layout* kv, int32_t q_heads, size_t* byt
   if (st != CKV_OK) return st;
   if (!bytes) return CKV_EINVAL;
   if (q_heads <= 0 || q_heads % kv->heads) return CKV_ESHAPE;
-  *bytes = align_up(attn_workspace_bytes(kv->batch, kv->heads, q_heads, kv->dim, kv->seq), 256);
+  *bytes = align_up(attn_workspace_bytes(kv->batch, kv->heads, q_heads, kv->dim, kv->seq, 0), 256);
   return CKV_OK;
 }
 
@@ -401,7 +401,174 @@ int ckv_decode_attn(const void* q, int32_t q_heads, const void* K, const void* V
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)kv->dim);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   return hip_status(launch_decode_attn(q, q_heads, K, V, kv->dtype, kv->dim, view_of(kv), kv->batch, kv->heads,
-                                       kv->seq, lens, deg, scale, o, o_dtype, workspace, s));
+                                       kv->seq, lens, deg, scale, o, o_dtype, workspace, PagedView{nullptr, 0, 0, 0},
+                                       s));
+}
+
+// ---- block-paged caches ------------------------------------------------------------------------
+namespace {
+int check_paged(const ckv_paged_layout* pl, int* shift) {
+  if (!pl) return CKV_EINVAL;
+  if (pl->dtype != CKV_F32 && pl->dtype != CKV_BF16) return CKV_EINVAL;
+  if (pl->batch <= 0 || pl->heads <= 0 || pl->dim <= 0 || pl->max_blocks <= 0 || pl->n_blocks <= 0) return CKV_ESHAPE;
+  if (pl->block_size < 1 || pl->block_size > 1024 || (pl->block_size & (pl->block_size - 1))) return CKV_ESHAPE;
+  if ((int64_t)pl->max_blocks * pl->block_size > INT32_MAX) return CKV_ESHAPE;
+  if ((pl->dim * ckv::elem_bytes(pl->dtype)) % 16) return CKV_EALIGN;
+  int sh = 0;
+  while ((1 << sh) < pl->block_size) ++sh;
+  *shift = sh;
+  return CKV_OK;
+}
+// the strided layout of a compact [batch, heads, seq, dim] staging tensor
+ckv_layout staging_layout(const ckv_paged_layout* pl, int seq) {
+  ckv_layout l{};
+  l.batch = pl->batch; l.heads = pl->heads; l.seq = seq; l.dim = pl->dim; l.dtype = pl->dtype;
+  l.stride_s = pl->dim; l.stride_h = (int64_t)seq * pl->dim; l.stride_b = (int64_t)pl->heads * seq * pl->dim;
+  l.deg_stride = 0;
+  return l;
+}
+ckv::TensorView pool_view(const ckv_paged_layout* pl) {
+  return ckv::TensorView{0, (int64_t)pl->block_size * pl->dim, (int64_t)pl->dim, pl->heads, 0};
+}
+}  // namespace
+
+int ckv_paged_decode_attn_workspace(const ckv_paged_layout* pl, int32_t q_heads, int32_t max_len, size_t* bytes) {
+  int shift;
+  int st = check_paged(pl, &shift);
+  if (st != CKV_OK) return st;
+  if (!bytes) return CKV_EINVAL;
+  if (max_len <= 0 || q_heads <= 0 || q_heads % pl->heads) return CKV_ESHAPE;
+  const int limit = ckv::attn_paged_span_limit(pl->block_size);
+  if ((int64_t)limit * 1024 < max_len) return CKV_EUNSUPPORTED;   // more table entries per slice than the kernel holds
+  *bytes = ckv::align_up(ckv::attn_workspace_bytes(pl->batch, pl->heads, q_heads, pl->dim, max_len, limit), 256);
+  return CKV_OK;
+}
+
+int ckv_paged_decode_attn(const void* q, int32_t q_heads, const void* K_pool, const void* V_pool,
+                          const int32_t* deg_pool, const int32_t* block_table, const int32_t* lens,
+                          const ckv_paged_layout* pl, int32_t max_len, float scale, void* o, int32_t o_dtype,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+  size_t need = 0;
+  int st = ckv_paged_decode_attn_workspace(pl, q_heads, max_len, &need);
+  if (st != CKV_OK) return st;
+  if (!q || !K_pool || !V_pool || !block_table || !lens || !o || !workspace) return CKV_EINVAL;
+  if (o_dtype != CKV_F32 && o_dtype != CKV_BF16) return CKV_EINVAL;
+  if (((uintptr_t)q) % 16 || ((uintptr_t)K_pool) % 16 || ((uintptr_t)V_pool) % 16 || ((uintptr_t)o) % 4 ||
+      ((uintptr_t)workspace) % 16 || ((uintptr_t)lens) % 4 || ((uintptr_t)deg_pool) % 4 ||
+      ((uintptr_t)block_table) % 4)
+    return CKV_EALIGN;
+  if (workspace_bytes < need) return CKV_EWORKSPACE;
+  const int G = q_heads / pl->heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return CKV_EUNSUPPORTED;
+  if (pl->dtype == CKV_BF16 ? !(pl->dim == 64 || pl->dim == 128) : !(pl->dim == 32 || pl->dim == 64 || pl->dim == 128))
+    return CKV_EUNSUPPORTED;
+  if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)pl->dim);
+  int shift;
+  check_paged(pl, &shift);
+  const int64_t cap = (int64_t)pl->max_blocks * pl->block_size;
+  const int seq = (int)(max_len < cap ? max_len : cap);
+  return ckv::hip_status(ckv::launch_decode_attn(q, q_heads, K_pool, V_pool, pl->dtype, pl->dim, pool_view(pl), pl->batch,
+                                                 pl->heads, seq, lens, deg_pool, scale, o, o_dtype, workspace,
+                                                 ckv::PagedView{block_table, pl->max_blocks, shift, pl->n_blocks},
+                                                 static_cast<hipStream_t>(hip_stream)));
+}
+
+int ckv_paged_gather(const void* K_pool, const void* V_pool, const int32_t* deg_pool, const int32_t* block_table,
+                     const ckv_paged_layout* pl, int32_t seq, void* K, void* V, int32_t* deg,
+                     const ckv_layout* out, void* hip_stream) {
+  int shift;
+  int st = check_paged(pl, &shift);
+  if (st == CKV_OK) st = ckv::check_layout(out);
+  if (st != CKV_OK) return st;
+  if (!K_pool || !V_pool || !block_table || !K || !V) return CKV_EINVAL;
+  if (out->batch != pl->batch || out->heads != pl->heads || out->dim != pl->dim || out->dtype != pl->dtype) return CKV_ESHAPE;
+  if (seq <= 0 || seq > out->seq || (int64_t)seq > (int64_t)pl->max_blocks * pl->block_size) return CKV_ESHAPE;
+  if (((uintptr_t)K_pool | (uintptr_t)V_pool | (uintptr_t)K | (uintptr_t)V) % 16) return CKV_EALIGN;
+  const int e = ckv::elem_bytes(pl->dtype);
+  return ckv::hip_status(ckv::launch_paged_gather(K_pool, V_pool, deg_pool,
+                                                  ckv::PagedView{block_table, pl->max_blocks, shift, pl->n_blocks},
+                                                  pl->batch, pl->heads, seq, pl->dim * e, K, V, deg, ckv::view_of(out), e,
+                                                  static_cast<hipStream_t>(hip_stream)));
+}
+
+int ckv_paged_scatter(const void* K, const void* V, const int32_t* deg, const ckv_layout* in, void* K_pool,
+                      void* V_pool, int32_t* deg_pool, int32_t* block_table, const ckv_paged_layout* pl,
+                      int32_t old_seq, int32_t* freed, int32_t* lens, void* hip_stream) {
+  int shift;
+  int st = check_paged(pl, &shift);
+  if (st == CKV_OK) st = ckv::check_layout(in);
+  if (st != CKV_OK) return st;
+  if (!K_pool || !V_pool || !block_table || !K || !V) return CKV_EINVAL;
+  if (in->batch != pl->batch || in->heads != pl->heads || in->dim != pl->dim || in->dtype != pl->dtype) return CKV_ESHAPE;
+  const int64_t cap = (int64_t)pl->max_blocks * pl->block_size;
+  if (old_seq < in->seq || old_seq > cap) return CKV_ESHAPE;
+  if (((uintptr_t)K_pool | (uintptr_t)V_pool | (uintptr_t)K | (uintptr_t)V) % 16) return CKV_EALIGN;
+  const int e = ckv::elem_bytes(pl->dtype);
+  const int keep = ckv::div_up(in->seq, pl->block_size), old_blocks = ckv::div_up(old_seq, pl->block_size);
+  return ckv::hip_status(ckv::launch_paged_scatter(K, V, deg, ckv::view_of(in), pl->batch, pl->heads, in->seq, pl->dim * e, e,
+                                                   K_pool, V_pool, deg_pool, block_table, pl->max_blocks, shift,
+                                                   pl->n_blocks, keep, old_blocks, freed, lens,
+                                                   static_cast<hipStream_t>(hip_stream)));
+}
+
+namespace {
+struct PagedWs { size_t K, V, deg, Ko, Vo, dego, inner, total; };
+int paged_plan(const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, ckv_plan_t* plan, PagedWs* w) {
+  int shift;
+  int st = check_paged(pl, &shift);
+  if (st != CKV_OK) return st;
+  if (seq <= 0 || (int64_t)seq > (int64_t)pl->max_blocks * pl->block_size) return CKV_ESHAPE;
+  const ckv_layout in = staging_layout(pl, seq);
+  st = ckv_plan(&in, p, plan);
+  if (st != CKV_OK) return st;
+  const size_t e = ckv::elem_bytes(pl->dtype), n_bh = (size_t)pl->batch * pl->heads;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = ckv::align_up(off + bytes, 256); return o; };
+  w->K = take(n_bh * seq * pl->dim * e);
+  w->V = take(n_bh * seq * pl->dim * e);
+  w->deg = take(n_bh * seq * 4);
+  w->Ko = take(n_bh * plan->out_seq * pl->dim * e);
+  w->Vo = take(n_bh * plan->out_seq * pl->dim * e);
+  w->dego = take(n_bh * plan->out_seq * 4);
+  w->inner = take(plan->workspace_bytes);
+  w->total = off;
+  return CKV_OK;
+}
+}  // namespace
+
+int ckv_paged_compress_plan(const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, int32_t* out_seq,
+                            int32_t* n_freed, size_t* workspace_bytes) {
+  ckv_plan_t plan;
+  PagedWs w;
+  int st = paged_plan(pl, seq, p, &plan, &w);
+  if (st != CKV_OK) return st;
+  if (out_seq) *out_seq = plan.out_seq;
+  if (n_freed) *n_freed = ckv::div_up(seq, pl->block_size) - ckv::div_up(plan.out_seq, pl->block_size);
+  if (workspace_bytes) *workspace_bytes = w.total;
+  return CKV_OK;
+}
+
+int ckv_paged_compress(void* K_pool, void* V_pool, int32_t* deg_pool, int32_t* block_table, int32_t* lens,
+                       const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, int32_t* freed,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  ckv_plan_t plan;
+  PagedWs w;
+  int st = paged_plan(pl, seq, p, &plan, &w);
+  if (st != CKV_OK) return st;
+  if (!K_pool || !V_pool || !deg_pool || !block_table || !workspace) return CKV_EINVAL;
+  if (((uintptr_t)workspace) % 256) return CKV_EALIGN;
+  if (workspace_bytes < w.total) return CKV_EWORKSPACE;
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const ckv_layout in = staging_layout(pl, seq), out = staging_layout(pl, plan.out_seq);
+  st = ckv_paged_gather(K_pool, V_pool, deg_pool, block_table, pl, seq, ws + w.K, ws + w.V,
+                        reinterpret_cast<int32_t*>(ws + w.deg), &in, hip_stream);
+  if (st != CKV_OK) return st;
+  st = ckv_compress(ws + w.K, ws + w.V, reinterpret_cast<int32_t*>(ws + w.deg), &in, p, ws + w.Ko, ws + w.Vo,
+                    reinterpret_cast<int32_t*>(ws + w.dego), &out, nullptr, ws + w.inner, plan.workspace_bytes,
+                    hip_stream);
+  if (st != CKV_OK) return st;
+  return ckv_paged_scatter(ws + w.Ko, ws + w.Vo, reinterpret_cast<int32_t*>(ws + w.dego), &out, K_pool, V_pool,
+                           deg_pool, block_table, pl, seq, freed, lens, hip_stream);
 }
 
 int ckv_timing_enable(int on) {

@@ -17,6 +17,13 @@ struct TensorView {
   }
 };
 
+// A block-paged cache: token t of sequence b lives in block table[b*max_blocks + (t >> shift)] at
+// offset t & ((1 << shift) - 1).  table == nullptr: not paged.
+struct PagedView {
+  const int32_t* table;
+  int32_t max_blocks, shift, n_blocks;
+};
+
 inline __host__ __device__ int div_up(int a, int b) { return (a + b - 1) / b; }
 
 // Number of A tokens (sources) in a sequence of `seq` tokens cut into chunks of `chunk` (even).
@@ -91,12 +98,27 @@ hipError_t launch_fill_deg(const int32_t* deg_in, int64_t in_stride, int32_t* de
                            int n_bh, int seq, hipStream_t st);
 
 // Decode attention: split-K partials then combine.
-int attn_splits(int n_b, int kv_heads, int seq);
-size_t attn_workspace_bytes(int n_b, int kv_heads, int q_heads, int dim, int seq);
+// span_limit > 0 (paged caches): no slice may cover more tokens than that
+int attn_splits(int n_b, int kv_heads, int seq, int span_limit);
+int attn_paged_span_limit(int block_size);
+size_t attn_workspace_bytes(int n_b, int kv_heads, int q_heads, int dim, int seq, int span_limit);
 hipError_t launch_decode_attn(const void* q, int q_heads, const void* K, const void* V, int dtype,
                               int dim, TensorView kv, int n_b, int kv_heads, int seq,
                               const int32_t* lens, const int32_t* deg, float scale, void* o,
-                              int o_dtype, void* workspace, hipStream_t st);
+                              int o_dtype, void* workspace, PagedView paged, hipStream_t st);
+
+// Block pool <-> strided tensors.  pool: [n_blocks, heads, block_size, dim] (deg pool
+// [n_blocks, heads, block_size]); the first `seq` tokens of every sequence are moved.  Gather writes
+// zeros (degree 1) for tokens whose table entry lies outside the pool; scatter skips them.
+hipError_t launch_paged_gather(const void* K_pool, const void* V_pool, const int32_t* deg_pool, PagedView paged,
+                               int n_b, int heads, int seq, int row_bytes, void* K, void* V, int32_t* deg,
+                               TensorView out, int elem_bytes, hipStream_t st);
+// Scatter also releases blocks: entries [keep_blocks, old_blocks) of every table row are copied to
+// freed[b*n_freed + k] (if freed != NULL) and set to -1, and lens[b] := seq (if lens != NULL).
+hipError_t launch_paged_scatter(const void* K, const void* V, const int32_t* deg, TensorView in, int n_b, int heads,
+                                int seq, int row_bytes, int elem_bytes, void* K_pool, void* V_pool,
+                                int32_t* deg_pool, int32_t* table, int max_blocks, int shift, int n_blocks,
+                                int keep_blocks, int old_blocks, int32_t* freed, int32_t* lens, hipStream_t st);
 
 // ---- timing hooks ----------------------------------------------------------------------------
 void timing_begin(const char* name, hipStream_t st);

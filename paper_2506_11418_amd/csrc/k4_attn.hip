@@ -100,12 +100,17 @@ __device__ inline uint16_t f32_to_bf16_rne(float f) {
 // the first use (bytes in flight hide HBM latency), the logits of the kUnroll tokens share one
 // running-max update, so the accumulators are rescaled once per kUnroll tokens.
 constexpr int kUnroll = 4;
+constexpr int kMaxTableLds = 2048;   // block-table entries of one slice kept in LDS (paged caches)
 
-template <typename T, int D, int G>
-__global__ __launch_bounds__(kThreads) void attn_partial_kernel(
+// PAGED: K, V are a block pool [n_blocks, heads, block_size, dim] (kv.stride_s = dim, kv.stride_h =
+// block_size*dim: the tokens of one head are contiguous inside a block), token t of sequence b
+// lives in block table[b][t / block_size] at offset t % block_size, degrees in a pool
+// [n_blocks, heads, block_size].  A table entry outside the pool masks its tokens.
+template <typename T, int D, int G, bool PAGED>
+__global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
     const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V, TensorView kv, int kv_heads,
     int seq, const int32_t* __restrict__ lens, const int32_t* __restrict__ deg, float scale_log2e,
-    int n_splits, int span, float* __restrict__ o_part, float* __restrict__ ml_part) {
+    int n_splits, int span, float* __restrict__ o_part, float* __restrict__ ml_part, PagedView paged) {
   constexpr int E = Elems<T>::E;
   constexpr int LPR = D / E;
   constexpr int NRG = kThreads / LPR;
@@ -118,10 +123,22 @@ __global__ __launch_bounds__(kThreads) void attn_partial_kernel(
   const int tid = threadIdx.x, rg = tid / LPR, piece = tid % LPR;
   const int len = lens ? min(lens[b], seq) : seq;
   const int t0 = split * span, t1 = min(t0 + span, len);
-  const int64_t base = (int64_t)b * kv.stride_b + (int64_t)kvh * kv.stride_h + piece * E;
+  const int64_t base = (PAGED ? 0 : (int64_t)b * kv.stride_b) + (int64_t)kvh * kv.stride_h + piece * E;
   const T* Kp = K + base;
   const T* Vp = V + base;
-  const int32_t* dseq = deg ? deg + ((int64_t)b * kv_heads + kvh) * kv.deg_stride : nullptr;
+  const int32_t* dseq = !deg ? nullptr : PAGED ? deg + ((int64_t)kvh << paged.shift)
+                                               : deg + ((int64_t)b * kv_heads + kvh) * kv.deg_stride;
+  const int32_t* tbl = PAGED ? paged.table + (int64_t)b * paged.max_blocks : nullptr;
+  const int bs_mask = (1 << paged.shift) - 1;
+  // the slice's block ids go to LDS first, so that a row's address does not wait for a second
+  // trip to memory (the host sizes the slices so that their table entries fit)
+  __shared__ int32_t s_tbl[PAGED ? kMaxTableLds : 1];
+  const int blk0 = t0 >> paged.shift;
+  if (PAGED && t0 < t1) {
+    const int n_ent = min(((t1 - 1) >> paged.shift) - blk0 + 1, kMaxTableLds);
+    for (int i = tid; i < n_ent; i += kThreads) s_tbl[i] = tbl[blk0 + i];
+    __syncthreads();
+  }
 
   typename Elems<T>::Q qv[G];
 #pragma unroll
@@ -146,9 +163,20 @@ __global__ __launch_bounds__(kThreads) void attn_partial_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int tc = min(tb + u * NRG + rg, t1 - 1);   // clamp: always a valid row, masked at use
-      st.kr[u] = Elems<T>::load_raw(Kp + (int64_t)tc * kv.stride_s);
-      st.vr[u] = Elems<T>::load_raw(Vp + (int64_t)tc * kv.stride_s);
-      st.dg[u] = dseq ? dseq[tc] : 1;
+      if (PAGED) {
+        const int blk = s_tbl[min((tc >> paged.shift) - blk0, kMaxTableLds - 1)];
+        const bool in_pool = (unsigned)blk < (unsigned)paged.n_blocks;
+        // row 0 when outside the pool: always a valid address, masked through the degree
+        const int64_t row = in_pool ? (((int64_t)blk * kv_heads) << paged.shift) + (tc & bs_mask) : 0;
+        st.kr[u] = Elems<T>::load_raw(Kp + row * kv.stride_s);
+        st.vr[u] = Elems<T>::load_raw(Vp + row * kv.stride_s);
+        const int d = dseq ? dseq[row] : 1;
+        st.dg[u] = in_pool ? d : 0;
+      } else {
+        st.kr[u] = Elems<T>::load_raw(Kp + (int64_t)tc * kv.stride_s);
+        st.vr[u] = Elems<T>::load_raw(Vp + (int64_t)tc * kv.stride_s);
+        st.dg[u] = dseq ? dseq[tc] : 1;
+      }
     }
   };
   auto consume = [&](const Stage& st, int tb) {
@@ -158,7 +186,7 @@ __global__ __launch_bounds__(kThreads) void attn_partial_kernel(
 #pragma unroll
       for (int g = 0; g < G; ++g) z[u][g] = row_sum<LPR>(Elems<T>::dot(qv[g], st.kr[u]));
       const float lb = dseq ? __log2f((float)st.dg[u]) : 0.f;
-      const bool ok = (tb + u * NRG + rg) < t1;
+      const bool ok = (tb + u * NRG + rg) < t1 && (!PAGED || st.dg[u] > 0);
 #pragma unroll
       for (int g = 0; g < G; ++g) z[u][g] = ok ? fmaf(z[u][g], scale_log2e, lb) : -INFINITY;
     }
@@ -290,16 +318,23 @@ __global__ void attn_combine_kernel(const float* __restrict__ o_part, const floa
 template <typename T, int D, int G>
 hipError_t launch_attn_t(const void* q, const void* K, const void* V, TensorView kv, int n_b, int kv_heads,
                          int seq, const int32_t* lens, const int32_t* deg, float scale, void* o, int o_dtype,
-                         void* workspace, hipStream_t st) {
-  const int n_splits = attn_splits(n_b, kv_heads, seq);
+                         void* workspace, PagedView paged, hipStream_t st) {
+  const int n_splits = attn_splits(n_b, kv_heads, seq, paged.table ? (kMaxTableLds << paged.shift) : 0);
   const int span = div_up(seq, n_splits);
+  if (paged.table && span > (kMaxTableLds << paged.shift)) return hipErrorInvalidValue;
   float* o_part = static_cast<float*>(workspace);
   float* ml_part = o_part + (size_t)n_b * kv_heads * n_splits * G * D;
   {
-    ScopedTimer t(sizeof(T) == 2 ? "attn_partial_bf16" : "attn_partial_f32", st);
-    hipLaunchKernelGGL((attn_partial_kernel<T, D, G>), dim3(n_splits, kv_heads, n_b), dim3(kThreads), 0, st,
-                       static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), kv,
-                       kv_heads, seq, lens, deg, scale * kLog2e, n_splits, span, o_part, ml_part);
+    ScopedTimer t(paged.table ? (sizeof(T) == 2 ? "attn_partial_paged_bf16" : "attn_partial_paged_f32")
+                              : (sizeof(T) == 2 ? "attn_partial_bf16" : "attn_partial_f32"), st);
+    if (paged.table)
+      hipLaunchKernelGGL((attn_partial_kernel<T, D, G, true>), dim3(n_splits, kv_heads, n_b), dim3(kThreads), 0,
+                         st, static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), kv,
+                         kv_heads, seq, lens, deg, scale * kLog2e, n_splits, span, o_part, ml_part, paged);
+    else
+      hipLaunchKernelGGL((attn_partial_kernel<T, D, G, false>), dim3(n_splits, kv_heads, n_b), dim3(kThreads), 0,
+                         st, static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), kv,
+                         kv_heads, seq, lens, deg, scale * kLog2e, n_splits, span, o_part, ml_part, paged);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -312,19 +347,19 @@ hipError_t launch_attn_t(const void* q, const void* K, const void* V, TensorView
 template <typename T, int D>
 hipError_t launch_attn_g(int G, const void* q, const void* K, const void* V, TensorView kv, int n_b,
                          int kv_heads, int seq, const int32_t* lens, const int32_t* deg, float scale, void* o,
-                         int o_dtype, void* workspace, hipStream_t st) {
+                         int o_dtype, void* workspace, PagedView paged, hipStream_t st) {
   switch (G) {
-    case 1: return launch_attn_t<T, D, 1>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, st);
-    case 2: return launch_attn_t<T, D, 2>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, st);
-    case 4: return launch_attn_t<T, D, 4>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, st);
-    case 8: return launch_attn_t<T, D, 8>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, st);
+    case 1: return launch_attn_t<T, D, 1>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st);
+    case 2: return launch_attn_t<T, D, 2>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st);
+    case 4: return launch_attn_t<T, D, 4>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st);
+    case 8: return launch_attn_t<T, D, 8>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st);
   }
   return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-int attn_splits(int n_b, int kv_heads, int seq) {
+int attn_splits(int n_b, int kv_heads, int seq, int span_limit) {
   // about two workgroups per CU (each has a fixed merge/write cost), at least 256 tokens per slice
   const int64_t bh = (int64_t)n_b * kv_heads;
   int want = (int)((512 + bh - 1) / bh);
@@ -332,21 +367,26 @@ int attn_splits(int n_b, int kv_heads, int seq) {
   if (cap > 1024) cap = 1024;   // the combine kernel keeps one weight per split in LDS
   if (want > cap) want = cap;
   if (want < 1) want = 1;
+  // paged caches: a slice's block-table entries must fit the kernel's LDS table
+  if (span_limit > 0 && (seq + want - 1) / want > span_limit) want = (seq + span_limit - 1) / span_limit;
+  if (want > 1024) want = 1024;
   return want;
 }
 
-size_t attn_workspace_bytes(int n_b, int kv_heads, int q_heads, int dim, int seq) {
-  const size_t rows = (size_t)n_b * q_heads * attn_splits(n_b, kv_heads, seq);
+int attn_paged_span_limit(int block_size) { return kMaxTableLds * block_size; }
+
+size_t attn_workspace_bytes(int n_b, int kv_heads, int q_heads, int dim, int seq, int span_limit) {
+  const size_t rows = (size_t)n_b * q_heads * attn_splits(n_b, kv_heads, seq, span_limit);
   return rows * (dim + 2) * sizeof(float);
 }
 
 hipError_t launch_decode_attn(const void* q, int q_heads, const void* K, const void* V, int dtype, int dim,
                               TensorView kv, int n_b, int kv_heads, int seq, const int32_t* lens,
                               const int32_t* deg, float scale, void* o, int o_dtype, void* workspace,
-                              hipStream_t st) {
+                              PagedView paged, hipStream_t st) {
   const int G = q_heads / kv_heads;
 #define CKV_ATTN(T, DD) \
-  return launch_attn_g<T, DD>(G, q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, st)
+  return launch_attn_g<T, DD>(G, q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st)
   if (dtype == CKV_BF16) {
     if (dim == 128) CKV_ATTN(__bf16, 128);
     if (dim == 64) CKV_ATTN(__bf16, 64);

@@ -1,0 +1,105 @@
+// Block-paged KV caches (the layout of a serving engine's block manager): moving a sequence's tokens
+// between a block pool and the strided tensors the clustering kernels work on, and releasing the
+// blocks a compressed sequence no longer needs.  Pure data movement: 16-byte pieces, one table
+// lookup per row.
+#include "ckv_internal.h"
+#include "ckv_device.h"
+
+namespace ckv {
+namespace {
+
+// one thread per 16-byte piece of one (batch, head, token) row
+template <bool TO_POOL>
+__global__ void paged_move_kernel(unsigned char* __restrict__ K_pool, unsigned char* __restrict__ V_pool,
+                                  int32_t* __restrict__ deg_pool, const int32_t* __restrict__ table, int max_blocks,
+                                  int shift, int n_blocks, int heads, int seq, int pieces_per_row,
+                                  unsigned char* __restrict__ K, unsigned char* __restrict__ V,
+                                  int32_t* __restrict__ deg, TensorView view, int elem_bytes, int64_t total) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= total) return;
+  // piece fastest, then token, then head: consecutive threads walk one head's tokens, which are
+  // contiguous in the tensor and, block by block, in the pool
+  const int piece = (int)(e % pieces_per_row);
+  int64_t x = e / pieces_per_row;
+  const int t = (int)(x % seq);
+  x /= seq;
+  const int h = (int)(x % heads), b = (int)(x / heads);
+  const int blk = table[(int64_t)b * max_blocks + (t >> shift)];
+  const bool in_pool = (unsigned)blk < (unsigned)n_blocks;
+  // pool: [n_blocks, heads, block_size, dim]
+  const int64_t row = in_pool ? ((((int64_t)blk * heads + h) << shift) + (t & ((1 << shift) - 1))) : 0;
+  const int64_t poff = (row * pieces_per_row + piece) * 16;
+  const int64_t toff = ((int64_t)b * view.stride_b + (int64_t)h * view.stride_h + (int64_t)t * view.stride_s) *
+                           elem_bytes + piece * 16;
+  const int64_t doff = ((int64_t)b * heads + h) * view.deg_stride + t;
+  if (TO_POOL) {
+    if (!in_pool) return;
+    stg16_stream(K_pool + poff, *reinterpret_cast<const uint4*>(K + toff));
+    stg16_stream(V_pool + poff, *reinterpret_cast<const uint4*>(V + toff));
+    if (piece == 0 && deg_pool) deg_pool[row] = deg ? deg[doff] : 1;
+  } else {
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(K + toff) = in_pool ? ldg16_stream(K_pool + poff) : zero;
+    *reinterpret_cast<uint4*>(V + toff) = in_pool ? ldg16_stream(V_pool + poff) : zero;
+    if (piece == 0 && deg) deg[doff] = (in_pool && deg_pool) ? deg_pool[row] : 1;
+  }
+}
+
+__global__ void paged_release_kernel(int32_t* __restrict__ table, int max_blocks, int n_b, int keep_blocks,
+                                     int old_blocks, int32_t* __restrict__ freed, int32_t* __restrict__ lens,
+                                     int seq) {
+  const int n_freed = old_blocks - keep_blocks;
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < n_b * n_freed) {
+    const int b = e / n_freed, k = e % n_freed;
+    int32_t* slot = table + (int64_t)b * max_blocks + keep_blocks + k;
+    if (freed) freed[e] = *slot;
+    *slot = -1;
+  }
+  if (lens && e < n_b) lens[e] = seq;
+}
+
+}  // namespace
+
+hipError_t launch_paged_gather(const void* K_pool, const void* V_pool, const int32_t* deg_pool, PagedView paged,
+                               int n_b, int heads, int seq, int row_bytes, void* K, void* V, int32_t* deg,
+                               TensorView out, int elem_bytes, hipStream_t st) {
+  const int ppr = row_bytes / 16;
+  const int64_t total = (int64_t)n_b * heads * seq * ppr;
+  if (total == 0) return hipSuccess;
+  ScopedTimer t("paged_gather", st);
+  hipLaunchKernelGGL(paged_move_kernel<false>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     static_cast<unsigned char*>(const_cast<void*>(K_pool)),
+                     static_cast<unsigned char*>(const_cast<void*>(V_pool)), const_cast<int32_t*>(deg_pool),
+                     paged.table, paged.max_blocks, paged.shift, paged.n_blocks, heads, seq, ppr,
+                     static_cast<unsigned char*>(K), static_cast<unsigned char*>(V), deg, out, elem_bytes, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_paged_scatter(const void* K, const void* V, const int32_t* deg, TensorView in, int n_b, int heads,
+                                int seq, int row_bytes, int elem_bytes, void* K_pool, void* V_pool,
+                                int32_t* deg_pool, int32_t* table, int max_blocks, int shift, int n_blocks,
+                                int keep_blocks, int old_blocks, int32_t* freed, int32_t* lens, hipStream_t st) {
+  const int ppr = row_bytes / 16;
+  const int64_t total = (int64_t)n_b * heads * seq * ppr;
+  if (total > 0) {
+    ScopedTimer t("paged_scatter", st);
+    hipLaunchKernelGGL(paged_move_kernel<true>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       static_cast<unsigned char*>(K_pool), static_cast<unsigned char*>(V_pool), deg_pool, table,
+                       max_blocks, shift, n_blocks, heads, seq, ppr,
+                       static_cast<unsigned char*>(const_cast<void*>(K)),
+                       static_cast<unsigned char*>(const_cast<void*>(V)), const_cast<int32_t*>(deg), in, elem_bytes,
+                       total);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const int work = n_b * (old_blocks - keep_blocks);
+  const int n = work > n_b ? work : n_b;
+  if (n <= 0) return hipSuccess;
+  ScopedTimer t("paged_release", st);
+  hipLaunchKernelGGL(paged_release_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, table, max_blocks,
+                     n_b, keep_blocks, old_blocks, freed, lens, seq);
+  return hipGetLastError();
+}
+
+}  // namespace ckv

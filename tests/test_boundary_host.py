@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(ckv_[a-z_]+)\s*\(", header))
     assert {"ckv_plan", "ckv_match", "ckv_compress", "ckv_decode_attn", "ckv_decode_attn_workspace",
-            "ckv_version", "ckv_strerror", "ckv_append", "ckv_schedule_annealed"} <= names
+            "ckv_version", "ckv_strerror", "ckv_append", "ckv_schedule_annealed", "ckv_paged_decode_attn",
+            "ckv_paged_gather", "ckv_paged_scatter", "ckv_paged_compress", "ckv_paged_compress_plan"} <= names
     L = ckv.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -107,6 +108,29 @@ def test_plan_with_selection_over_the_whole_sequence(seq, chunk, rounds, n_sink,
     bad = ckv.make_params(chunk, rounds=rounds)
     bad.scope = 3
     assert ckv.lib().ckv_plan(C.byref(_lay(seq=seq)), C.byref(bad), C.byref(ckv.PlanT())) == -1
+
+
+def test_paged_plan_and_argument_checks():
+    L = ckv.lib()
+    pl = ckv.PagedLayout(2, 8, 128, ckv.BF16, 16, 300, 1000)
+    out_seq, n_freed, nbytes = ckv.paged_compress_plan(pl, 4096 + 80, ckv.make_params(256, 0.25, n_sink=16, n_recent=64))
+    assert out_seq == round_lengths(4176, 256, [1.0, 1.0], 16, 64)[-1]
+    assert n_freed == -(-4176 // 16) - (-(-out_seq // 16))
+    # staging: the gathered cache and the result, K and V, plus degrees, plus ckv_compress's own workspace
+    assert nbytes >= 2 * 8 * (4176 + out_seq) * (2 * 128 * 2 + 4)
+    z, a = C.c_void_p(0), C.c_void_p(4096)
+    bad = ckv.PagedLayout(2, 8, 128, ckv.BF16, 24, 300, 1000)              # block size not a power of two
+    assert L.ckv_paged_compress_plan(C.byref(bad), 4096, C.byref(ckv.make_params(256, 0.5)), None, None, None) == -2
+    assert L.ckv_paged_compress_plan(C.byref(pl), 16 * 300 + 1, C.byref(ckv.make_params(256, 0.5)), None, None, None) == -2
+    n = C.c_size_t(0)
+    assert L.ckv_paged_decode_attn_workspace(C.byref(pl), 32, 4096, C.byref(n)) == 0 and n.value > 0
+    assert L.ckv_paged_decode_attn_workspace(C.byref(pl), 30, 4096, C.byref(n)) == -2
+    assert L.ckv_paged_decode_attn(a, 32, a, a, z, a, z, C.byref(pl), 4096, 0.0, a, 0, a, n.value, z) == -1   # lens required
+    assert L.ckv_paged_decode_attn(a, 32, a, a, z, a, a, C.byref(pl), 4096, 0.0, a, 0, a, 16, z) == -4
+    lay = _lay(batch=2, heads=8, seq=512)
+    assert L.ckv_paged_gather(a, a, z, a, C.byref(pl), 1024, a, a, z, C.byref(lay), z) == -2                 # seq > out->seq
+    assert L.ckv_paged_scatter(a, a, z, C.byref(lay), a, a, z, a, C.byref(pl), 100, z, z, z) == -2           # old_seq < seq
+    assert L.ckv_paged_compress(a, a, z, a, z, C.byref(pl), 4096, C.byref(ckv.make_params(256, 0.5)), z, a, 1 << 30, z) == -1
 
 
 def test_plan_workspace_grows_with_rounds():
