@@ -30,6 +30,22 @@ __device__ inline float sumsq8(const Piece& x) {
 // 1/sqrt(ss) by the hardware reciprocal square root (1 ulp), 0 for a zero key.
 __device__ inline float inv_norm(float ss) { return ss > 0.f ? __builtin_amdgcn_rsqf(ss) : 0.f; }
 
+// 1/|k| of a row held as MFMA operand fragments: a lane holds the pieces of its lane half, the lane
+// 32 away the other pieces of the same row.  Every kernel that scores with this row's norm uses
+// this one summation order, so their scores agree bit for bit.
+template <int KSTEPS>
+__device__ __forceinline__ float inv_norm_of_operand_row(const bf16x8 (&frag)[KSTEPS]) {
+  float ss = 0.f;
+#pragma unroll
+  for (int s = 0; s < KSTEPS; ++s) {
+    Piece pc;
+    pc.v = frag[s];
+    ss += sumsq8(pc);
+  }
+  ss += __shfl_xor(ss, 32);
+  return inv_norm(ss);
+}
+
 // Sum over the LANES lanes (8 or 16, aligned) that hold one key row, with DPP adds: xor 1 and
 // xor 2 inside each quad, then the mirrored half-row and row (after the quad steps all lanes of
 // a quad agree, so a mirror brings in exactly the other quad's / other half's sum).

@@ -36,7 +36,6 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* panel0 = smem;                                // 2 panels of kPanel rows; the A
   float* invb = reinterpret_cast<float*>(smem + 2 * kPanel * ROWB);  // block is staged over both
-  float* inva = invb + 2 * kPanel;
 
   const int w = xcd_remap(blockIdx.x, per_xcd);
   if (w >= total_work) return;
@@ -122,11 +121,8 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
         if (a0 + r0 + it * ROWS_PER_PASS >= nA) xa[it].u = make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
-    for (int it = 0; it < APIECES; ++it) {
-      const float ss = row_sum<OCT>(sumsq8(xa[it]));
+    for (int it = 0; it < APIECES; ++it)
       *reinterpret_cast<uint4*>(panel0 + lds_piece0 + it * ROWS_PER_PASS * ROWB) = xa[it].u;
-      if (piece == 0) inva[r0 + it * ROWS_PER_PASS] = inv_norm(ss);
-    }
   }
   __syncthreads();
   bf16x8 afrag[2][KSTEPS];
@@ -138,8 +134,8 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
     for (int s = 0; s < KSTEPS; ++s)
       afrag[rt][s] = *reinterpret_cast<const bf16x8*>(panel0 + swz(row, 2 * s + half));
   }
-  const float my_inva0 = inva[wave * kRowsPerWave + col];
-  const float my_inva1 = inva[wave * kRowsPerWave + 32 + col];
+  // 1/|k_i| of this lane's two A rows, from the operand registers
+  const float my_inva[2] = {inv_norm_of_operand_row<KSTEPS>(afrag[0]), inv_norm_of_operand_row<KSTEPS>(afrag[1])};
   __syncthreads();
 
   // ---- stream B panels -----------------------------------------------------------------------
@@ -217,7 +213,7 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
       const int a = a0 + wave * kRowsPerWave + rt * 32 + col;
       if (half == 0 && a < nA) {
         dst_local[out_base + a] = j;
-        score[out_base + a] = b * (rt ? my_inva1 : my_inva0);
+        score[out_base + a] = b * my_inva[rt];
       }
     }
   }
@@ -312,7 +308,7 @@ __global__ void dst_positions_kernel(const int32_t* __restrict__ dst_local, int3
 template <int D>
 hipError_t launch_match_bf16(const void* K, TensorView kv, int n_bh, int seq, int chunk,
                              int32_t* dst_local, float* score, hipStream_t st) {
-  constexpr size_t lds = 2 * kPanel * D * 2 + (2 * kPanel + kABlock) * sizeof(float);
+  constexpr size_t lds = 2 * kPanel * D * 2 + 2 * kPanel * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&match_bf16_kernel<D>),

@@ -342,8 +342,9 @@ __global__ __launch_bounds__(kThreads, 2) void fused2_kernel(
 #pragma unroll
         for (int s = 0; s < kKSteps; ++s)
           afrag[rt][s] = *reinterpret_cast<const bf16x8*>(R + swz(row, 2 * s + half));
-        inva1[rt] = inva_s[row];
       }
+      inva1[0] = inv_norm_of_operand_row<kKSteps>(afrag[0]);
+      inva1[1] = inv_norm_of_operand_row<kKSteps>(afrag[1]);
       __syncthreads();
     }
   }
