@@ -4,10 +4,12 @@
 // For every A token i:  j*(i) = argmax_j  k_i.k_j / (|k_i||k_j|)  (lowest j on ties) and that
 // maximum.  The |A| x |B| similarity matrix lives only in MFMA accumulators.
 //
-// bf16 kernel: one workgroup = (sequence, chunk, block of 256 A rows); 4 waves x 64 A rows.  The
+// bf16 kernel: one workgroup = (sequence, chunk, block of A rows), 64 A rows per wave; 8 waves
+// (512 A rows: a whole 1024-token chunk) for chunks above 512 tokens, 4 waves otherwise.  The
 // A rows are staged once through LDS into registers in MFMA operand order; the chunk's B rows
 // stream through two LDS panels of 128 rows (global -> registers -> LDS, one barrier per panel).
-// Inverse norms come from the same staged bytes (v_dot2 on the packed pairs).  The MFMA computes
+// Inverse norms come from the same bytes (v_dot2 on the packed pairs): the B rows' while they
+// are staged, the A rows' from the operand registers.  The MFMA computes
 // S^T (B index on the M side) so that a lane's 16 accumulators of a 32x32 tile all belong to ONE
 // A row: the running maximum costs one multiply (by 1/|k_j|) and half a max3 per element, and the
 // exact index is only resolved for tiles that raise some lane's maximum.
@@ -20,22 +22,26 @@ namespace ckv {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kWaves = 4;
 constexpr int kRowsPerWave = 64;                 // two 32-row MFMA tiles
-constexpr int kABlock = kWaves * kRowsPerWave;   // A rows per workgroup
 constexpr int kPanel = 128;                      // B rows per LDS panel
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
+// NW waves x 64 A rows per workgroup: 4 waves (two workgroups per CU) for chunks of up to 512 tokens,
+// 8 waves (one workgroup per CU) for larger chunks, so that the B rows of a 1024-token chunk are
+// fetched, normed and written to LDS once instead of once per 256 A rows.
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
     const __bf16* __restrict__ K, TensorView kv, int seq, int chunk, int n_chunks, int a_blocks,
     int total_work, int per_xcd, int32_t* __restrict__ dst_local, float* __restrict__ score) {
   constexpr int OCT = D / 8;                       // 16-byte pieces per key row
   constexpr int ROWB = D * 2;                      // bytes per row
   constexpr int KEYSHIFT = (ROWB == 256) ? 0 : 1;  // rows per 256 B of LDS = 1 << KEYSHIFT
   constexpr int KSTEPS = D / 16;
+  constexpr int THREADS = NW * 64;
+  constexpr int ABLOCK = NW * kRowsPerWave;        // A rows per workgroup
+  constexpr int PANELS_B = (ABLOCK > 2 * kPanel ? ABLOCK : 2 * kPanel) * ROWB;   // staging area: A block or 2 panels
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* panel0 = smem;                                // 2 panels of kPanel rows; the A
-  float* invb = reinterpret_cast<float*>(smem + 2 * kPanel * ROWB);  // block is staged over both
+  float* invb = reinterpret_cast<float*>(smem + PANELS_B);           // block is staged over them
 
   const int w = xcd_remap(blockIdx.x, per_xcd);
   if (w >= total_work) return;
@@ -45,7 +51,7 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
   const int g0 = g * chunk;
   const int L = min(chunk, seq - g0);
   const int nA = (L + 1) >> 1, nB = L >> 1;
-  const int a0 = ab * kABlock;
+  const int a0 = ab * ABLOCK;
   if (a0 >= nA) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_src = n_sources(seq, chunk);
@@ -63,10 +69,10 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
   // ---- stage the A block (even offsets) and its inverse norms --------------------------------
   // All global loads are issued before the first use (rows past the end re-read the last valid
   // row and are zeroed), together with the first B panel, so one memory latency covers both.
-  constexpr int PIECES = kPanel * OCT / kThreads;   // 16-byte pieces per thread per panel
+  constexpr int PIECES = kPanel * OCT / THREADS;   // 16-byte pieces per thread per panel
   Piece stage[PIECES];
   const int piece = tid % OCT, r0 = tid / OCT;
-  constexpr int ROWS_PER_PASS = kThreads / OCT;
+  constexpr int ROWS_PER_PASS = THREADS / OCT;
   // every thread walks its own column of 16-byte pieces: row r0 + it*ROWS_PER_PASS of a panel
   const __bf16* Bcol = Kseq + kv.stride_s + piece * 8;          // B row j lives at token 2j+1
   const int64_t row_pitch = 2 * kv.stride_s;
@@ -107,7 +113,7 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
   const int n_panels = div_up(nB, kPanel);
   const int p_first = min(a0 / kPanel, n_panels - 1);
   {
-    constexpr int APIECES = kABlock * OCT / kThreads;
+    constexpr int APIECES = ABLOCK * OCT / THREADS;
     Piece xa[APIECES];
 #pragma unroll
     for (int it = 0; it < APIECES; ++it) {
@@ -115,7 +121,7 @@ __global__ __launch_bounds__(kThreads, 2) void match_bf16_kernel(
       xa[it].u = *reinterpret_cast<const uint4*>(Kseq + (int64_t)(2 * a) * kv.stride_s + piece * 8);
     }
     load_panel(p_first * kPanel);
-    if (a0 + kABlock > nA) {
+    if (a0 + ABLOCK > nA) {
 #pragma unroll
       for (int it = 0; it < APIECES; ++it)
         if (a0 + r0 + it * ROWS_PER_PASS >= nA) xa[it].u = make_uint4(0, 0, 0, 0);
@@ -305,27 +311,35 @@ __global__ void dst_positions_kernel(const int32_t* __restrict__ dst_local, int3
   dst_pos[e] = (j < 0) ? -1 : g * chunk + 2 * j + 1;
 }
 
-template <int D>
-hipError_t launch_match_bf16(const void* K, TensorView kv, int n_bh, int seq, int chunk,
-                             int32_t* dst_local, float* score, hipStream_t st) {
-  constexpr size_t lds = 2 * kPanel * D * 2 + 2 * kPanel * sizeof(float);
+template <int D, int NW>
+hipError_t launch_match_bf16_nw(const void* K, TensorView kv, int n_bh, int seq, int chunk,
+                                int32_t* dst_local, float* score, hipStream_t st) {
+  constexpr int ABLOCK = NW * kRowsPerWave;
+  constexpr size_t lds = (size_t)(ABLOCK > 2 * kPanel ? ABLOCK : 2 * kPanel) * D * 2 + 2 * kPanel * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&match_bf16_kernel<D>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&match_bf16_kernel<D, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int n_chunks = div_up(seq, chunk);
-  const int a_blocks = div_up(chunk / 2, kABlock);
+  const int a_blocks = div_up(chunk / 2, ABLOCK);
   const int64_t total = (int64_t)n_bh * n_chunks * a_blocks;
   if (total > (1 << 30)) return hipErrorInvalidValue;
   const int per_xcd = div_up((int)total, 8);
   ScopedTimer t("match_bf16", st);
-  hipLaunchKernelGGL(match_bf16_kernel<D>, dim3(per_xcd * 8), dim3(kThreads), lds, st,
+  hipLaunchKernelGGL((match_bf16_kernel<D, NW>), dim3(per_xcd * 8), dim3(NW * 64), lds, st,
                      static_cast<const __bf16*>(K), kv, seq, chunk, n_chunks, a_blocks, (int)total,
                      per_xcd, dst_local, score);
   return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_match_bf16(const void* K, TensorView kv, int n_bh, int seq, int chunk,
+                             int32_t* dst_local, float* score, hipStream_t st) {
+  if (chunk > 512) return launch_match_bf16_nw<D, 8>(K, kv, n_bh, seq, chunk, dst_local, score, st);
+  return launch_match_bf16_nw<D, 4>(K, kv, n_bh, seq, chunk, dst_local, score, st);
 }
 
 }  // namespace
