@@ -5,13 +5,16 @@
  *
  * Conventions for every function
  *   - returns CKV_OK (0) or a negative ckv_status; never throws, aborts or prints;
- *   - pointers named K, V, q, o, deg, lens, assign, dst, score, workspace are DEVICE pointers
- *     (HIP global memory of the current device); ckv_layout / ckv_params / ckv_plan_t and
- *     other struct pointers are HOST pointers;
+ *   - pointers named K, V, q, o, deg, lens, assign, dst, score, freed, block_table, workspace
+ *     and the *_pool / *_new / *_out buffers are DEVICE pointers (HIP global memory of the current
+ *     device); ckv_layout / ckv_paged_layout / ckv_params / ckv_plan_t and other struct or
+ *     scalar-result pointers are HOST pointers;
  *   - the caller owns every buffer; the library allocates and frees no device memory;
  *   - work is enqueued on `hip_stream` (a hipStream_t, NULL = the default stream) and the call
  *     returns without synchronising; argument errors are detected on the host before any launch;
- *   - inputs are never written; outputs and workspace must not overlap inputs (CKV_EINVAL);
+ *   - buffers passed through const pointers are never written; outputs and workspace must not
+ *     overlap inputs (CKV_EINVAL where the host can tell); ckv_append and the ckv_paged_* calls
+ *     update the cache they are given in place, as stated with each of them;
  *   - base pointers and row strides (in bytes) of K/V tensors are multiples of 16 (CKV_EALIGN).
  *
  * Tensor layout ("layout"): element (b, h, t, :) of a [batch, heads, seq, dim] tensor lives at
