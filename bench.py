@@ -48,15 +48,21 @@ WORKLOADS = {
 }
 
 
-def algorithmic_work(cfg, plan, fused=True):
+def algorithmic_work(cfg, plan, fused=True, deferred=False):
     """Algorithmic bytes / flops of one step, per kernel (whole launch set of that kernel).
+
+    deferred: a round with r = 1 that is followed by another round writes keys and degrees only
+    (kernel merge_keys_bf16, which also exports 3 bytes of member lists per token) and the next
+    round (merge_origin_bf16) reads its keys and degrees, and every ORIGINAL value row once.
 
     Mirrors the library's schedule: two consecutive rounds whose first merges every edge (r = 1)
     run as ONE pass (kernel fused2_bf16: reads K, V once, writes the final rows) when chunk = 1024,
     bf16, dim 128 and the length is a multiple of 2048; other rounds run as match + merge."""
     n_bh = cfg["layers"] * cfg["kv_heads"]
     d, e, c = cfg["dim"], 2, cfg["chunk"]
-    work = {"match_bf16": 0.0, "merge_bf16": 0.0, "fused2_bf16": 0.0, "attn_partial_bf16": 0.0}
+    work = {"match_bf16": 0.0, "merge_bf16": 0.0, "merge_keys_bf16": 0.0, "merge_origin_bf16": 0.0,
+            "fused2_bf16": 0.0, "attn_partial_bf16": 0.0}
+    origin_len = None       # length of the cache whose values the current round rebuilds from
     flops = {"fused2_bf16": 0.0}
     j, J = 0, len(plan.round_r)
 
@@ -77,7 +83,16 @@ def algorithmic_work(cfg, plan, fused=True):
         full, tail = divmod(s_in, c)
         work["match_bf16"] += n_bh * match_flops(s_in)                       # 2*|A|*|B|*d per chunk
         n_src = full * (c // 2) + (tail + 1) // 2
-        work["merge_bf16"] += n_bh * (s_in * (2 * d * e + deg_in + 4) + n_src * 8 + s_out * (2 * d * e + 4))
+        if origin_len is not None:      # second round of a deferred pair
+            org_deg = 0 if j == 1 else 4
+            work["merge_origin_bf16"] += n_bh * (s_in * (d * e + 4 + 4) + n_src * 8 + origin_len * (d * e + org_deg + 3)
+                                                 + s_out * (2 * d * e + 4))
+            origin_len = None
+        elif deferred and j + 1 < J and plan.round_r[j] == 1.0:
+            work["merge_keys_bf16"] += n_bh * (s_in * (d * e + deg_in + 4 + 3) + n_src * 8 + s_out * (d * e + 4))
+            origin_len = s_in
+        else:
+            work["merge_bf16"] += n_bh * (s_in * (2 * d * e + deg_in + 4) + n_src * 8 + s_out * (2 * d * e + 4))
         j += 1
     work["attn_partial_bf16"] = n_bh * plan.out_seq * (2 * d * e + 4)        # K', V' rows + degree
     work["_fused2_flops"] = flops["fused2_bf16"]
@@ -182,7 +197,7 @@ def main():
     dec_ms = float(np.mean([ev[3 * i + 1].elapsed_time(ev[3 * i + 2]) for i in range(args.steps)]))
 
     # ---- per-kernel roofline figures ------------------------------------------------------------
-    work = algorithmic_work(cfg, plan, fused="fused2_bf16" in ktimes)
+    work = algorithmic_work(cfg, plan, fused="fused2_bf16" in ktimes, deferred="merge_keys_bf16" in ktimes)
     kernels = {}
     for name, (tot_ms, launches) in ktimes.items():
         per_step_ms = tot_ms / args.steps

@@ -74,7 +74,7 @@ int seq_after_round(int len, int chunk, float r, int n_sink, int n_recent, int s
 }
 
 struct Workspace {
-  size_t dst, score, sel, map, K[2], V[2], deg[2], total;
+  size_t dst, score, sel, lists, map, K[2], V[2], deg[2], total;
 };
 
 Workspace carve(const ckv_layout* in, const ckv_plan_t* plan, int chunk, int scope) {
@@ -89,6 +89,8 @@ Workspace carve(const ckv_layout* in, const ckv_plan_t* plan, int chunk, int sco
   if (scope == CKV_SCOPE_HEAD) w.sel = take(n_bh * (size_t)div_up(in->seq, chunk) * 8);
   const int inter = plan->n_rounds - 1;   // intermediate caches
   if (inter >= 1) w.map = take(n_bh * (size_t)plan->round_len[1] * 4);
+  // member lists a keys-only merge hands to the next round (3 int16 per source of a chunk)
+  if (inter >= 1) w.lists = take(n_bh * (size_t)div_up(in->seq, chunk) * 3 * (chunk / 2) * 2);
   for (int k = 0; k < 2 && k < inter; ++k) {
     const size_t len = plan->round_len[k + 1];
     w.K[k] = take(n_bh * len * in->dim * e);
@@ -276,6 +278,15 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
   // workgroup per CU, currently slower on MI355X; it runs only when CKV_ENABLE_FUSED=1.
   const char* fuse_env = getenv("CKV_ENABLE_FUSED");
   const bool allow_fused = fuse_env && fuse_env[0] == '1';
+  // Deferred values: when round j merges every edge (r = 1) and another round follows, round j
+  // writes keys and degrees only and round j+1 rebuilds the value rows it needs from round j's
+  // value input (bit-identical; the intermediate value cache is neither written nor read).
+  // CKV_DISABLE_DEFERRED_VALUES=1 runs every round in full (used by the tests to compare).
+  const char* defer_env = getenv("CKV_DISABLE_DEFERRED_VALUES");
+  const bool allow_defer = !(defer_env && defer_env[0] == '1');
+  int16_t* lists = reinterpret_cast<int16_t*>(ws + w.lists);
+  ValueOrigin org{};
+  bool have_org = false;
   for (int j = 0; j < plan.n_rounds; ++j) {
     const int len = plan.round_len[j];
     // rounds j and j+1 in one pass when the first merges every edge and the shape has a kernel
@@ -284,6 +295,9 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
                       p->scope == CKV_SCOPE_CHUNK &&
                       fused2_supported(in->dtype, in->dim, p->chunk, len, plan.round_r[j]) &&
                       curView.stride_s <= (1 << 18) && out->stride_s <= (1 << 18);
+    const bool keys_only = allow_defer && !fuse && !have_org && j + 1 < plan.n_rounds &&
+                           plan.round_r[j] == 1.0f && p->scope == CKV_SCOPE_CHUNK && p->n_sink == 0 &&
+                           p->n_recent == 0;
     const int jo = fuse ? j + 1 : j;                 // index of the round whose output is produced
     const int next = plan.round_len[jo + 1];
     const bool last = (jo == plan.n_rounds - 1);
@@ -316,7 +330,8 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
         err = launch_merge(mK, mV, curDeg ? curDeg + lo : nullptr, in->dtype, in->dim, curView, n_bh, mid, p->chunk,
                            plan.round_r[j], dst, score, static_cast<unsigned char*>(oK) + (size_t)lo * oView.stride_s * e,
                            static_cast<unsigned char*>(oV) + (size_t)lo * oView.stride_s * e, oDeg + lo, oView,
-                           oDegStride, map ? map + lo : nullptr, curView.deg_stride, len, lo, sel, s);
+                           oDegStride, map ? map + lo : nullptr, curView.deg_stride, len, lo, sel,
+                           keys_only ? lists : nullptr, have_org ? &org : nullptr, s);
         if (err != hipSuccess) return hip_status(err);
       }
       if (mid < len)   // sinks and recents (or a cache too short to cluster): straight copy
@@ -328,7 +343,14 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
       err = launch_compose(assign, map, n_bh, in->seq, len, s);
       if (err != hipSuccess) return hip_status(err);
     }
-    curK = oK; curV = oV; curDeg = oDeg; curView = oView;
+    if (keys_only) {   // the values stay where they are; the next round reads them through the lists
+      org = ValueOrigin{curV, curView, curDeg, lists, len, div_up(len, p->chunk)};
+      have_org = true;
+    } else {
+      curV = oV;
+      have_org = false;
+    }
+    curK = oK; curDeg = oDeg; curView = oView;
     j = jo;
   }
   return CKV_OK;

@@ -51,15 +51,30 @@ hipError_t launch_match(const void* K, int dtype, int dim, TensorView kv, int n_
 hipError_t launch_dst_positions(const int32_t* dst_local, int32_t* dst_pos, int n_bh, int seq,
                                 int chunk, hipStream_t st);
 
+// Two consecutive rounds whose first merges every edge (r = 1) can skip the intermediate VALUE
+// cache.  The first round's merge then writes keys and degrees only and exports every chunk's
+// member lists (lists_out: per (sequence, chunk) 3*(chunk/2) int16: count | start | members); the
+// second round's merge rebuilds each value row of its input from the original values through
+// those lists (same arithmetic, same single rounding: bit-identical results).
+struct ValueOrigin {
+  const void* V0;         // the first round's value input, at the first clustered token
+  TensorView view0;       // its layout (deg_stride: row stride of deg0)
+  const int32_t* deg0;    // the first round's degree input at the first clustered token, or NULL (= 1)
+  const int16_t* lists;   // what the first round's merge exported
+  int32_t seq0;           // tokens the first round clustered
+  int32_t n_chunks0;      // its chunks per sequence
+};
+
 // Per-chunk top-r selection + degree-weighted merge + order-preserving compaction.
 // map_out[bh*map_stride + t] (t < seq) = map_offset + output index of the centroid input token t
-// joined; may be NULL.  deg_in[bh*deg_in_stride + t].
+// joined; may be NULL.  deg_in[bh*deg_in_stride + t].  lists_out != NULL: keys-only first round of a
+// deferred-value pair (V, V_out unused); org != NULL: its second round (V unused).
 hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int dtype, int dim,
                         TensorView in, int n_bh, int seq, int chunk, float r,
                         const int32_t* dst_local, const float* score, void* K_out, void* V_out,
                         int32_t* deg_out, TensorView out, int64_t deg_out_stride, int32_t* map_out,
                         int64_t deg_in_stride, int64_t map_stride, int map_offset, const int32_t* sel_table,
-                        hipStream_t st);
+                        int16_t* lists_out, const ValueOrigin* org, hipStream_t st);
 
 // Selection over all chunks of a sequence: from the match scores, table[bh, chunk] = (edges of the
 // chunk among the sequence's floor(r * edges) best, first output row of the chunk), two int32 each.

@@ -52,7 +52,8 @@ struct Row<__bf16> {
   __device__ static Raw load_raw(const __bf16* p) { return ldg16_stream(p); }
   __device__ static void store_raw(__bf16* p, const Raw& r) { stg16_stream(p, r); }
   __device__ static void fma_into(Acc* acc, const Raw& u, int w) { fma_bf16x8(acc, u, w); }
-  __device__ static void store_div(__bf16* p, const Acc* acc, int n) { stg16_stream(p, round_div_pack_bf16(acc, n)); }
+  __device__ static Raw div_raw(const Acc* acc, int n) { return round_div_pack_bf16(acc, n); }
+  __device__ static void store_div(__bf16* p, const Acc* acc, int n) { stg16_stream(p, div_raw(acc, n)); }
 };
 
 template <>
@@ -66,26 +67,40 @@ struct Row<float> {
     const double w = (double)wi;
     acc[0] += w * (double)u.x; acc[1] += w * (double)u.y; acc[2] += w * (double)u.z; acc[3] += w * (double)u.w;
   }
-  __device__ static void store_div(float* p, const Acc* acc, int n) {
+  __device__ static Raw div_raw(const Acc* acc, int n) {
     const double dn = (double)n;
-    *reinterpret_cast<float4*>(p) = make_float4((float)(acc[0] / dn), (float)(acc[1] / dn),
-                                                (float)(acc[2] / dn), (float)(acc[3] / dn));
+    return make_float4((float)(acc[0] / dn), (float)(acc[1] / dn), (float)(acc[2] / dn), (float)(acc[3] / dn));
   }
+  __device__ static void store_div(float* p, const Acc* acc, int n) { *reinterpret_cast<float4*>(p) = div_raw(acc, n); }
 };
 
 constexpr int kRowsInFlight = 2;   // output rows a row group works on at once
+constexpr int kRowsInFlightOrigin = 2;   // ... when every value row is itself rebuilt from several rows
 
-template <typename T, int D>
+// MODE (two consecutive rounds whose first merges every edge, r = 1, can skip the intermediate
+// VALUE cache: a round-0 chunk then keeps exactly its B tokens, so a round-1 chunk is fed by two
+// round-0 chunks):
+//   kMergeFull    keys and values of this round's input -> this round's output;
+//   kMergeKeys    first round of such a pair: keys and degrees only, and the member lists of
+//                 every chunk are exported (lists_out: per chunk cnt | start | members, int16);
+//   kMergeOrigin  second round of the pair: keys as usual, while every value row of the input
+//                 (a round-0 centroid that was never written) is rebuilt from the ORIGINAL values
+//                 through the exported lists, in the same fp32 order and with the same single
+//                 rounding the first round would have used, so the results are bit-identical.
+enum { kMergeFull = 0, kMergeKeys = 1, kMergeOrigin = 2 };
+
+template <typename T, int D, int MODE>
 __global__ __launch_bounds__(kThreads) void merge_kernel(
     const T* __restrict__ K, const T* __restrict__ V, const int32_t* __restrict__ deg_in, TensorView in,
     int seq, int chunk, int n_chunks, float r, const int32_t* __restrict__ dst_local,
     const float* __restrict__ score, T* __restrict__ K_out, T* __restrict__ V_out,
     int32_t* __restrict__ deg_out, TensorView out, int64_t deg_out_stride, int32_t* __restrict__ map_out,
-    int64_t deg_in_stride, int64_t map_stride, int map_offset, const int2* __restrict__ sel_table) {
+    int64_t deg_in_stride, int64_t map_stride, int map_offset, const int2* __restrict__ sel_table,
+    int16_t* __restrict__ lists_out, ValueOrigin org) {
   constexpr int E = Row<T>::E;
   constexpr int LPR = D / E;                 // lanes per row
   constexpr int NRG = kThreads / LPR;        // row groups per workgroup
-  constexpr int U = kRowsInFlight;
+  constexpr int U = (MODE == kMergeOrigin) ? kRowsInFlightOrigin : kRowsInFlight;
   typedef typename Row<T>::Acc Acc;
   typedef typename Row<T>::Raw Raw;
 
@@ -103,6 +118,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   const int g = blockIdx.x % n_chunks, bh = blockIdx.x / n_chunks;
   const int tid = threadIdx.x;
   const int g0 = g * chunk, L = min(chunk, seq - g0);
+  const int half = chunk >> 1;
   const int nA = (L + 1) >> 1, nB = L >> 1;
   // edges merged in this chunk and its first output row: fixed by r alone for per-chunk selection,
   // read from the table of the sequence-wide selection otherwise
@@ -242,6 +258,15 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   }
   __syncthreads();
 
+  if (MODE == kMergeKeys) {   // member lists of this chunk for the next round's value rebuild
+    int16_t* lst = lists_out + ((int64_t)bh * n_chunks + g) * 3 * half;
+    for (int i = tid; i < half; i += kThreads) {
+      lst[i] = (i < nB) ? (int16_t)s_cnt[i] : (int16_t)0;
+      lst[half + i] = (i < nB) ? s_start[i] : (int16_t)0;
+      lst[2 * half + i] = (i < m) ? s_members[i] : (int16_t)0;
+    }
+  }
+
   // ---- assignment map of this round ----------------------------------------------------------
   if (map_out != nullptr) {
     int32_t* mp = map_out + (int64_t)bh * map_stride + g0;
@@ -252,15 +277,96 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     }
   }
 
+  // kMergeOrigin: the member lists of the two previous-round chunks that feed this chunk, staged in
+  // LDS arrays the bookkeeping above no longer needs (scores, fill counters, local output slots)
+  int16_t (*s0_cnt)[kMaxHalf] = reinterpret_cast<int16_t (*)[kMaxHalf]>(s_score);
+  int16_t (*s0_start)[kMaxHalf] = reinterpret_cast<int16_t (*)[kMaxHalf]>(s_fill);
+  int16_t (*s0_mem)[kMaxHalf] = reinterpret_cast<int16_t (*)[kMaxHalf]>(s_local_out);
+  if (MODE == kMergeOrigin) {
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c0 = 2 * g + h;
+      if (c0 < org.n_chunks0) {
+        const int16_t* lst = org.lists + ((int64_t)bh * org.n_chunks0 + c0) * 3 * half;
+        for (int i = tid; i < half; i += kThreads) {
+          s0_cnt[h][i] = lst[i];
+          s0_start[h][i] = lst[half + i];
+          s0_mem[h][i] = lst[2 * half + i];
+        }
+      }
+    }
+    __syncthreads();
+  }
+
   // ---- emit rows: every row group works on U output rows at once; the loads of their own rows
   // and of their first merged source are all in flight before anything is consumed ---------------
   const int rg = tid / LPR, piece = tid % LPR;
   const T* Kin = K + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E;
-  const T* Vin = V + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E;
+  const T* Vin = (MODE == kMergeFull) ? V + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E : nullptr;
   T* Ko = K_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
-  T* Vo = V_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
+  T* Vo = (MODE == kMergeKeys) ? nullptr : V_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
   const int32_t* dseq = deg_in ? deg_in + (int64_t)bh * deg_in_stride + g0 : nullptr;
   int32_t* dout = deg_out + (int64_t)bh * deg_out_stride + out_base;
+
+  // The value row of input row p of this chunk.  kMergeFull: a load.  kMergeOrigin: the previous
+  // round's centroid p, rebuilt: p is B token j of previous-round chunk 2g+h (a one-token tail chunk
+  // kept its only token); its own row and its first member are loaded at once, the rest on demand.
+  const T* V0p = (MODE == kMergeOrigin) ? static_cast<const T*>(org.V0) + org.view0.seq_base(bh) + piece * E : nullptr;
+  const int32_t* d0p = (MODE == kMergeOrigin && org.deg0) ? org.deg0 + (int64_t)bh * org.view0.deg_stride : nullptr;
+  constexpr int kEager = 1;   // members of a previous-round cluster loaded together with its own row
+  struct VLoad {
+    Raw b, m[kEager];
+    int db, dm[kEager], n, base;
+    const int16_t* mem;
+  };
+  auto v_issue = [&](int p) -> VLoad {
+    VLoad x;
+    if (MODE == kMergeFull) {
+      x.b = Row<T>::load_raw(Vin + (int64_t)p * in.stride_s);
+      x.n = 0;
+    } else if (MODE == kMergeOrigin) {
+      const int h = (p >= half) ? 1 : 0, jj = p - h * half;
+      x.base = (2 * g + h) * chunk;
+      const bool single = (org.seq0 - x.base) == 1;
+      const int tb = x.base + (single ? 0 : 2 * jj + 1);
+      x.n = single ? 0 : (int)s0_cnt[h][jj];
+      x.mem = &s0_mem[h][s0_start[h][jj]];
+      x.b = Row<T>::load_raw(V0p + (int64_t)tb * org.view0.stride_s);
+      x.db = d0p ? d0p[tb] : 1;
+#pragma unroll
+      for (int q = 0; q < kEager; ++q) {
+        if (q < x.n) {
+          const int ta = x.base + 2 * (int)x.mem[q];
+          x.m[q] = Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s);
+          x.dm[q] = d0p ? d0p[ta] : 1;
+        }
+      }
+    }
+    return x;
+  };
+  auto v_finish = [&](const VLoad& x) -> Raw {
+    if (MODE != kMergeOrigin || x.n == 0) return x.b;
+    Acc a[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) a[e] = 0;
+    Row<T>::fma_into(a, x.b, x.db);
+    int nd = x.db;
+#pragma unroll
+    for (int q = 0; q < kEager; ++q)
+      if (q < x.n) {
+        Row<T>::fma_into(a, x.m[q], x.dm[q]);
+        nd += x.dm[q];
+      }
+    for (int q = kEager; q < x.n; ++q) {
+      const int ta = x.base + 2 * (int)x.mem[q];
+      const int da = d0p ? d0p[ta] : 1;
+      Row<T>::fma_into(a, Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s), da);
+      nd += da;
+    }
+    return Row<T>::div_raw(a, nd);
+  };
+
   for (int ob = 0; ob < n_out; ob += NRG * U) {
     int tok[U], nmem[U], first[U], mem0[U], du[U], dm[U];
     bool valid[U];
@@ -274,13 +380,16 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       first[u] = isB ? (int)s_start[tok[u] >> 1] : 0;
       mem0[u] = (nmem[u] > 0) ? 2 * (int)s_members[first[u]] : tok[u];   // no source: re-read own row
     }
-    Raw kb[U], vb[U], km[U], vm[U];
+    Raw kb[U], km[U];
+    VLoad vb[U], vm[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       kb[u] = Row<T>::load_raw(Kin + (int64_t)tok[u] * in.stride_s);
-      vb[u] = Row<T>::load_raw(Vin + (int64_t)tok[u] * in.stride_s);
       km[u] = Row<T>::load_raw(Kin + (int64_t)mem0[u] * in.stride_s);
-      vm[u] = Row<T>::load_raw(Vin + (int64_t)mem0[u] * in.stride_s);
+      if (MODE != kMergeKeys) {
+        vb[u] = v_issue(tok[u]);
+        vm[u] = v_issue(mem0[u]);
+      }
       du[u] = dseq ? dseq[tok[u]] : 1;
       dm[u] = dseq ? dseq[mem0[u]] : 1;
     }
@@ -290,7 +399,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       const int o = ob + u * NRG + rg;
       if (nmem[u] == 0) {  // untouched token: bit copy
         Row<T>::store_raw(Ko + (int64_t)o * out.stride_s, kb[u]);
-        Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, vb[u]);
+        if (MODE != kMergeKeys) Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, v_finish(vb[u]));
         if (piece == 0) dout[o] = du[u];
         continue;
       }
@@ -298,21 +407,22 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 #pragma unroll
       for (int e = 0; e < E; ++e) { ak[e] = 0; av[e] = 0; }
       Row<T>::fma_into(ak, kb[u], du[u]);
-      Row<T>::fma_into(av, vb[u], du[u]);
       Row<T>::fma_into(ak, km[u], dm[u]);
-      Row<T>::fma_into(av, vm[u], dm[u]);
+      if (MODE != kMergeKeys) {
+        Row<T>::fma_into(av, v_finish(vb[u]), du[u]);
+        Row<T>::fma_into(av, v_finish(vm[u]), dm[u]);
+      }
       int ndeg = du[u] + dm[u];
       for (int q = 1; q < nmem[u]; ++q) {
         const int ua = 2 * (int)s_members[first[u] + q];
         const int da = dseq ? dseq[ua] : 1;
         const Raw kx = Row<T>::load_raw(Kin + (int64_t)ua * in.stride_s);
-        const Raw vx = Row<T>::load_raw(Vin + (int64_t)ua * in.stride_s);
         Row<T>::fma_into(ak, kx, da);
-        Row<T>::fma_into(av, vx, da);
+        if (MODE != kMergeKeys) Row<T>::fma_into(av, v_finish(v_issue(ua)), da);
         ndeg += da;
       }
       Row<T>::store_div(Ko + (int64_t)o * out.stride_s, ak, ndeg);
-      Row<T>::store_div(Vo + (int64_t)o * out.stride_s, av, ndeg);
+      if (MODE != kMergeKeys) Row<T>::store_div(Vo + (int64_t)o * out.stride_s, av, ndeg);
       if (piece == 0) dout[o] = ndeg;
     }
   }
@@ -406,16 +516,29 @@ hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, T
                           int seq, int chunk, float r, const int32_t* dst_local, const float* score,
                           void* K_out, void* V_out, int32_t* deg_out, TensorView out,
                           int64_t deg_out_stride, int32_t* map_out, int64_t deg_in_stride, int64_t map_stride,
-                          int map_offset, const int32_t* sel_table, hipStream_t st) {
+                          int map_offset, const int32_t* sel_table, int16_t* lists_out, const ValueOrigin* org,
+                          hipStream_t st) {
   const int n_chunks = div_up(seq, chunk);
   const int64_t total = (int64_t)n_bh * n_chunks;
   if (total > (1 << 30)) return hipErrorInvalidValue;
-  ScopedTimer t(sizeof(T) == 2 ? "merge_bf16" : "merge_f32", st);
-  hipLaunchKernelGGL((merge_kernel<T, D>), dim3((int)total), dim3(kThreads), 0, st,
-                     static_cast<const T*>(K), static_cast<const T*>(V), deg_in, in, seq, chunk, n_chunks,
-                     r, dst_local, score, static_cast<T*>(K_out), static_cast<T*>(V_out), deg_out, out,
-                     deg_out_stride, map_out, deg_in_stride, map_stride, map_offset,
-                     reinterpret_cast<const int2*>(sel_table));
+  const ValueOrigin o = org ? *org : ValueOrigin{};
+#define CKV_LAUNCH(MODE)                                                                                      \
+  hipLaunchKernelGGL((merge_kernel<T, D, MODE>), dim3((int)total), dim3(kThreads), 0, st,                    \
+                     static_cast<const T*>(K), static_cast<const T*>(V), deg_in, in, seq, chunk, n_chunks, r, \
+                     dst_local, score, static_cast<T*>(K_out), static_cast<T*>(V_out), deg_out, out,          \
+                     deg_out_stride, map_out, deg_in_stride, map_stride, map_offset,                          \
+                     reinterpret_cast<const int2*>(sel_table), lists_out, o)
+  if (org) {
+    ScopedTimer t(sizeof(T) == 2 ? "merge_origin_bf16" : "merge_origin_f32", st);
+    CKV_LAUNCH(kMergeOrigin);
+  } else if (lists_out) {
+    ScopedTimer t(sizeof(T) == 2 ? "merge_keys_bf16" : "merge_keys_f32", st);
+    CKV_LAUNCH(kMergeKeys);
+  } else {
+    ScopedTimer t(sizeof(T) == 2 ? "merge_bf16" : "merge_f32", st);
+    CKV_LAUNCH(kMergeFull);
+  }
+#undef CKV_LAUNCH
   return hipGetLastError();
 }
 
@@ -426,11 +549,11 @@ hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int
                         const int32_t* dst_local, const float* score, void* K_out, void* V_out,
                         int32_t* deg_out, TensorView out, int64_t deg_out_stride, int32_t* map_out,
                         int64_t deg_in_stride, int64_t map_stride, int map_offset, const int32_t* sel_table,
-                        hipStream_t st) {
+                        int16_t* lists_out, const ValueOrigin* org, hipStream_t st) {
 #define CKV_MERGE(T, DD)                                                                             \
   return launch_merge_t<T, DD>(K, V, deg_in, in, n_bh, seq, chunk, r, dst_local, score, K_out, V_out, \
                                deg_out, out, deg_out_stride, map_out, deg_in_stride, map_stride, map_offset, \
-                               sel_table, st)
+                               sel_table, lists_out, org, st)
   if (dtype == CKV_BF16) {
     if (dim == 128) CKV_MERGE(__bf16, 128);
     if (dim == 64) CKV_MERGE(__bf16, 64);

@@ -397,3 +397,69 @@ def test_fused_kernel_on_duplicate_keys():
     assert np.array_equal(i64(gas[0, 0]), ref["assign"])
     assert np.array_equal(i64(gdeg[0, 0]), ref["deg"])
     assert np.array_equal(f64(gV[0, 0]), ref["V"])
+
+
+# ---- deferred values: rounds after an r = 1 round rebuild their value rows from the original cache ----
+@pytest.mark.parametrize("dtype,heads,seq,dim,chunk,rounds,use_deg", [
+    ("bf16", 3, 8192, 128, 1024, [1.0, 1.0], False),
+    ("bf16", 2, 5000, 128, 1024, [1.0, 0.6], True),          # ragged tail chunk in both rounds
+    ("bf16", 2, 4097, 128, 256, [1.0, 1.0, 1.0], False),     # odd length: a one-token tail chunk; pair + one full round
+    ("bf16", 1, 6000, 128, 2048, [1.0, 1.0, 1.0, 0.5], True),  # two pairs
+    ("bf16", 2, 1026, 64, 2, [1.0, 1.0], False),             # chunk 2
+    ("bf16", 1, 3000, 64, 512, [0.5, 1.0, 1.0], True),       # a full round first, then a pair
+    ("f32", 2, 1500, 64, 64, [1.0, 0.75], True),
+    ("f32", 1, 1024, 128, 128, [1.0, 1.0], False),
+])
+def test_deferred_values_are_bit_identical_to_full_rounds(dtype, heads, seq, dim, chunk, rounds, use_deg):
+    """By default a round that merges every edge (r = 1) and is followed by another writes keys and
+    degrees only, and the next round rebuilds the value rows it needs from the original values.
+    With CKV_DISABLE_DEFERRED_VALUES=1 every round runs in full; both must give the same bits (the
+    full rounds are checked against the oracle above)."""
+    import os
+    _say(f"deferred values {dtype} H={heads} S={seq} D={dim} c={chunk} rounds={rounds} deg={use_deg}")
+    K, V, _ = kv_host(51, heads, seq, dim, dtype, alpha=0.9, n_outlier=4 if dim == 128 else 0)
+    K, V = K.to(DEV), V.to(DEV)
+    deg = None
+    if use_deg:
+        deg = torch.from_numpy(np.random.default_rng(2).integers(1, 7, (1, heads, seq)).astype(np.int32)).to(DEV)
+    ckv.timing_reset()
+    ckv.timing_enable(True)
+    got = ckv.compress(K, V, chunk, rounds=rounds, deg=deg)
+    torch.cuda.synchronize()
+    ckv.timing_enable(False)
+    names = ckv.timing_read()
+    suffix = "bf16" if dtype == "bf16" else "f32"
+    assert f"merge_keys_{suffix}" in names and f"merge_origin_{suffix}" in names      # the deferred path really ran
+    os.environ["CKV_DISABLE_DEFERRED_VALUES"] = "1"
+    try:
+        ckv.timing_reset()
+        ckv.timing_enable(True)
+        ref = ckv.compress(K, V, chunk, rounds=rounds, deg=deg)
+        torch.cuda.synchronize()
+        ckv.timing_enable(False)
+        assert f"merge_keys_{suffix}" not in ckv.timing_read()
+    finally:
+        del os.environ["CKV_DISABLE_DEFERRED_VALUES"]
+    for n, a, b in zip(["K'", "V'", "deg'", "assign"], got, ref):
+        assert a.shape == b.shape, n
+        assert torch.equal(a, b), f"{n} differs between deferred and full rounds"
+
+
+def test_deferred_values_with_strided_input_and_padded_output():
+    _say("deferred values, [B,S,H,D] input")
+    B, H, S, D, c = 2, 2, 3072, 128, 512
+    K0, V0, _ = kv_host(52, B * H, S, D, "bf16", alpha=0.9, n_outlier=4)
+    Kb = K0.reshape(B, H, S, D).permute(0, 2, 1, 3).contiguous().to(DEV)
+    Vb = V0.reshape(B, H, S, D).permute(0, 2, 1, 3).contiguous().to(DEV)
+    K, V = Kb.permute(0, 2, 1, 3), Vb.permute(0, 2, 1, 3)
+    out_len = S // 4
+    oK = torch.zeros((B, H, out_len + 24, D), dtype=torch.bfloat16, device=DEV)
+    oV = torch.zeros_like(oK)
+    odeg = torch.zeros((B, H, out_len + 24), dtype=torch.int32, device=DEV)
+    oas = torch.empty((B, H, S), dtype=torch.int32, device=DEV)
+    ckv.compress(K, V, c, retain_ratio=0.25, out=(oK, oV, odeg, oas))
+    ref = ckv.compress(K.contiguous(), V.contiguous(), c, rounds=[1.0])
+    ref = ckv.compress(ref[0], ref[1], c, rounds=[1.0], deg=ref[2])         # two full single-round calls
+    torch.cuda.synchronize()
+    assert torch.equal(oK[:, :, :out_len], ref[0]) and torch.equal(oV[:, :, :out_len], ref[1])
+    assert torch.equal(odeg[:, :, :out_len], ref[2]) and not bool(oV[:, :, out_len:].any())
