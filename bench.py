@@ -31,8 +31,9 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 # size; see profiles/bench_config3_hbm_traffic.txt for the runs and the factors.  Filled in by hand
 # from those runs: {(workload, kernel): bytes per launch averaged over the launches of one step}.
 MEASURED_TRAFFIC = {
-    ("config3", "merge_bf16"): int((6339703.5 * 2.0 + 6439271.6) * 1024),
-    ("config3", "match_bf16"): int((3145922.9 * 2.0 + 98304.0) * 1024),
+    ("config3", "merge_keys_bf16"): int((4227366.8 * 2.0 + 4489246.6) * 1024),
+    ("config3", "merge_origin_bf16"): int((6398504.8 * 2.0 + 4292620.3) * 1024),
+    ("config3", "match_bf16"): int((3145922.7 * 2.0 + 98304.0) * 1024),
     ("config3", "attn_partial_bf16"): int((66217.0 * 2.0 + 1040.0) * 1024),
 }
 

@@ -122,14 +122,22 @@ __device__ __forceinline__ uint4 round_div_pack_bf16(const float* acc, int n) {
   const float rcp = 1.0f / fn;   // correctly rounded: quotients that divide evenly then come out exact
   const bool pow2 = (n & (n - 1)) == 0;          // then acc*rcp IS the quotient: no second rounding
   float qv[8];
-  bool risky = false;
+  bool window = false;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     qv[i] = acc[i] * rcp;
-    const bool window = ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
-    risky |= window & (fmaf(-qv[i], fn, acc[i]) != 0.f);
+    window |= ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
   }
-  risky &= !pow2;
+  window &= !pow2;
+  bool risky = false;
+  if (__any(window)) {   // rare (a few 1e-4 per element): only then pay for the exactness test
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool win = ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
+      risky |= win & (fmaf(-qv[i], fn, acc[i]) != 0.f);
+    }
+    risky &= !pow2;
+  }
   uint32_t w[4];
   if (__any(risky)) {
 #pragma unroll
