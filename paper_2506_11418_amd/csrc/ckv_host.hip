@@ -287,6 +287,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
   int16_t* lists = reinterpret_cast<int16_t*>(ws + w.lists);
   ValueOrigin org{};
   bool have_org = false;
+  const void* edgesV = V;   // where the current cache's sink / recent value rows live
   for (int j = 0; j < plan.n_rounds; ++j) {
     const int len = plan.round_len[j];
     // rounds j and j+1 in one pass when the first merges every edge and the shape has a kernel
@@ -295,9 +296,8 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
                       p->scope == CKV_SCOPE_CHUNK &&
                       fused2_supported(in->dtype, in->dim, p->chunk, len, plan.round_r[j]) &&
                       curView.stride_s <= (1 << 18) && out->stride_s <= (1 << 18);
-    const bool keys_only = allow_defer && !fuse && !have_org && j + 1 < plan.n_rounds &&
-                           plan.round_r[j] == 1.0f && p->scope == CKV_SCOPE_CHUNK && p->n_sink == 0 &&
-                           p->n_recent == 0;
+    const bool defer_ok = allow_defer && !fuse && !have_org && j + 1 < plan.n_rounds &&
+                          plan.round_r[j] == 1.0f && p->scope == CKV_SCOPE_CHUNK;
     const int jo = fuse ? j + 1 : j;                 // index of the round whose output is produced
     const int next = plan.round_len[jo + 1];
     const bool last = (jo == plan.n_rounds - 1);
@@ -311,6 +311,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     int lo, hi;
     clusterable(len, p->n_sink, p->n_recent, &lo, &hi);
     const int mid = hi - lo;
+    const bool keys_only = defer_ok && mid > 0;
     hipError_t err = hipSuccess;
     if (fuse) {
       err = launch_fused2(curK, curV, curDeg, curView, n_bh, len, plan.round_r[j + 1], oK, oV, oDeg, oView,
@@ -335,7 +336,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
         if (err != hipSuccess) return hip_status(err);
       }
       if (mid < len)   // sinks and recents (or a cache too short to cluster): straight copy
-        err = launch_edges(curK, curV, curDeg, curView, len, oK, oV, oDeg, oView, oDegStride, next, map,
+        err = launch_edges(curK, edgesV, curDeg, curView, len, oK, oV, oDeg, oView, oDegStride, next, map,
                            mid > 0 ? lo : len, mid > 0 ? len - hi : 0, n_bh, in->dim * e, e, s);
     }
     if (err != hipSuccess) return hip_status(err);
@@ -343,13 +344,15 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
       err = launch_compose(assign, map, n_bh, in->seq, len, s);
       if (err != hipSuccess) return hip_status(err);
     }
-    if (keys_only) {   // the values stay where they are; the next round reads them through the lists
-      org = ValueOrigin{curV, curView, curDeg, lists, len, div_up(len, p->chunk)};
+    if (keys_only) {   // the clustered values stay where they are; the next round reads them through the lists
+      org = ValueOrigin{static_cast<const unsigned char*>(curV) + (size_t)lo * curView.stride_s * e, curView,
+                        curDeg ? curDeg + lo : nullptr, lists, mid, div_up(mid, p->chunk)};
       have_org = true;
     } else {
       curV = oV;
       have_org = false;
     }
+    edgesV = oV;       // sinks and recents are copied in every round, deferred or not
     curK = oK; curDeg = oDeg; curView = oView;
     j = jo;
   }

@@ -400,23 +400,30 @@ def test_fused_kernel_on_duplicate_keys():
 
 
 # ---- deferred values: rounds after an r = 1 round rebuild their value rows from the original cache ----
-@pytest.mark.parametrize("dtype,heads,seq,dim,chunk,rounds,use_deg", [
-    ("bf16", 3, 8192, 128, 1024, [1.0, 1.0], False),
-    ("bf16", 2, 5000, 128, 1024, [1.0, 0.6], True),          # ragged tail chunk in both rounds
-    ("bf16", 2, 4097, 128, 256, [1.0, 1.0, 1.0], False),     # odd length: a one-token tail chunk; pair + one full round
-    ("bf16", 1, 6000, 128, 2048, [1.0, 1.0, 1.0, 0.5], True),  # two pairs
-    ("bf16", 2, 1026, 64, 2, [1.0, 1.0], False),             # chunk 2
-    ("bf16", 1, 3000, 64, 512, [0.5, 1.0, 1.0], True),       # a full round first, then a pair
-    ("f32", 2, 1500, 64, 64, [1.0, 0.75], True),
-    ("f32", 1, 1024, 128, 128, [1.0, 1.0], False),
+@pytest.mark.parametrize("dtype,heads,seq,dim,chunk,rounds,use_deg,n_sink,n_recent", [
+    ("bf16", 3, 8192, 128, 1024, [1.0, 1.0], False, 0, 0),
+    ("bf16", 2, 8192 + 80, 128, 1024, [1.0, 1.0], False, 16, 64),     # the paper's sinks / recents
+    ("bf16", 2, 3000, 128, 256, [1.0, 1.0, 0.5], True, 5, 37),
+    ("f32", 1, 700, 64, 64, [1.0, 1.0, 1.0, 1.0], False, 100, 150),    # the middle shrinks to a few tokens
+    ("bf16", 1, 260, 128, 16, [1.0, 1.0], False, 100, 159),            # one clustered token: nothing to defer to
+    ("bf16", 2, 5000, 128, 1024, [1.0, 0.6], True, 0, 0),          # ragged tail chunk in both rounds
+    ("bf16", 2, 4097, 128, 256, [1.0, 1.0, 1.0], False, 0, 0),     # odd length: a one-token tail chunk; pair + one full round
+    ("bf16", 1, 6000, 128, 2048, [1.0, 1.0, 1.0, 0.5], True, 0, 0),  # two pairs
+    ("bf16", 2, 1026, 64, 2, [1.0, 1.0], False, 0, 0),             # chunk 2
+    ("bf16", 1, 3000, 64, 512, [0.5, 1.0, 1.0], True, 0, 0),       # a full round first, then a pair
+    ("f32", 2, 1500, 64, 64, [1.0, 0.75], True, 0, 0),
+    ("f32", 1, 1024, 128, 128, [1.0, 1.0], False, 0, 0),
 ])
-def test_deferred_values_are_bit_identical_to_full_rounds(dtype, heads, seq, dim, chunk, rounds, use_deg):
+def test_deferred_values_are_bit_identical_to_full_rounds(dtype, heads, seq, dim, chunk, rounds, use_deg, n_sink,
+                                                          n_recent):
     """By default a round that merges every edge (r = 1) and is followed by another writes keys and
     degrees only, and the next round rebuilds the value rows it needs from the original values.
     With CKV_DISABLE_DEFERRED_VALUES=1 every round runs in full; both must give the same bits (the
     full rounds are checked against the oracle above)."""
     import os
-    _say(f"deferred values {dtype} H={heads} S={seq} D={dim} c={chunk} rounds={rounds} deg={use_deg}")
+    _say(f"deferred values {dtype} H={heads} S={seq} D={dim} c={chunk} rounds={rounds} deg={use_deg} "
+         f"n1={n_sink} n2={n_recent}")
+    kw = dict(n_sink=n_sink, n_recent=n_recent)
     K, V, _ = kv_host(51, heads, seq, dim, dtype, alpha=0.9, n_outlier=4 if dim == 128 else 0)
     K, V = K.to(DEV), V.to(DEV)
     deg = None
@@ -424,7 +431,7 @@ def test_deferred_values_are_bit_identical_to_full_rounds(dtype, heads, seq, dim
         deg = torch.from_numpy(np.random.default_rng(2).integers(1, 7, (1, heads, seq)).astype(np.int32)).to(DEV)
     ckv.timing_reset()
     ckv.timing_enable(True)
-    got = ckv.compress(K, V, chunk, rounds=rounds, deg=deg)
+    got = ckv.compress(K, V, chunk, rounds=rounds, deg=deg, **kw)
     torch.cuda.synchronize()
     ckv.timing_enable(False)
     names = ckv.timing_read()
@@ -434,7 +441,7 @@ def test_deferred_values_are_bit_identical_to_full_rounds(dtype, heads, seq, dim
     try:
         ckv.timing_reset()
         ckv.timing_enable(True)
-        ref = ckv.compress(K, V, chunk, rounds=rounds, deg=deg)
+        ref = ckv.compress(K, V, chunk, rounds=rounds, deg=deg, **kw)
         torch.cuda.synchronize()
         ckv.timing_enable(False)
         assert f"merge_keys_{suffix}" not in ckv.timing_read()
