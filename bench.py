@@ -326,6 +326,44 @@ def main():
         serving["paged_block16_attn_partial_us"] = round(pus, 2)
         serving["paged_block16_GBps"] = round(byts / pus / 1e3, 1)
         del K_pool, V_pool, deg_pool
+        # in-place compression of a paged cache (gather -> compress -> scatter) against the strided call on
+        # the same tokens: 16 sequences x 8 KV heads x 32768 tokens, blocks of 16, retain 25%
+        Sp = 32768
+        nblk = Bs * Sp // bs
+        ptable0 = torch.randperm(nblk, generator=gen, device=dev).to(torch.int32).reshape(Bs, Sp // bs).contiguous()
+        K_pool = torch.randn((nblk, H, bs, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        V_pool = torch.randn((nblk, H, bs, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        deg_pool = torch.ones((nblk, H, bs), dtype=torch.int32, device=dev)
+        pl = ckv.paged_layout_of(K_pool, ptable0)
+        _, _, pbytes = ckv.paged_compress_plan(pl, Sp, ckv.make_params(cfg["chunk"], cfg["retain"]))
+        pws = torch.empty(pbytes, dtype=torch.uint8, device=dev)
+        sK, sV, _ = ckv.paged_gather(K_pool, V_pool, deg_pool, ptable0, Sp)          # the same tokens, strided
+        s_out = ckv.compress(sK, sV, cfg["chunk"], retain_ratio=cfg["retain"], want_assign=False)
+        sws = torch.empty(ckv.plan(ckv.layout_of(sK), ckv.make_params(cfg["chunk"], cfg["retain"])).workspace_bytes,
+                          dtype=torch.uint8, device=dev)
+        times = {}
+        for kind in ("paged", "strided"):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            tot = 0.0
+            for it in range(4):
+                ptable = ptable0.clone()
+                deg_pool.fill_(1)
+                torch.cuda.synchronize()
+                e0.record()
+                if kind == "paged":      # the cache is compacted in place: every repetition starts from a fresh table
+                    ckv.paged_compress(K_pool, V_pool, deg_pool, ptable, Sp, cfg["chunk"], retain_ratio=cfg["retain"],
+                                       workspace=pws)
+                else:
+                    ckv.compress(sK, sV, cfg["chunk"], retain_ratio=cfg["retain"], want_assign=False,
+                                 out=(s_out[0], s_out[1], s_out[2], None), workspace=sws)
+                e1.record()
+                torch.cuda.synchronize()
+                if it > 0:
+                    tot += e0.elapsed_time(e1)
+            times[kind] = tot / 3
+        serving["paged_compress_16x8x32768_ms"] = round(times["paged"], 3)
+        serving["strided_compress_16x8x32768_ms"] = round(times["strided"], 3)
+        del K_pool, V_pool, deg_pool, sK, sV, s_out, pws, sws
 
     dec_bytes = work["attn_partial_bf16"]
     out = {
