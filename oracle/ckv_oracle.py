@@ -3,7 +3,7 @@
 A plain, slow, fp64 numpy statement of what the path computes, written from the
 paper (arXiv 2506.11418): one clustering round of Chunked Soft Matching
 (Sec. 5.2) with the degree-weighted merge (Sec. 5.3, centroid equation), the
-multi-round "compress until the budget is met" loop (Algorithm 1, prefill
+multi-round loop that compresses until the budget is met (Algorithm 1, prefill
 part), and approximate attention over centroids (Eq. 3).  Nothing here is
 tiled, fused or reordered, it shares no code with the HIP library and imports
 nothing from it; only tests, the smoke check and the benchmark's cpu_baseline
@@ -131,7 +131,7 @@ def merge_count(r: float, n_a: int) -> int:
 
 def select(src, dst, score, s: int, c: int, r: float, tau: float = TAU):
     """Keep, per chunk, the m = floor(r * |A|) highest-scoring edges; ties go to
-    the lower A index (Sec. 5.3, 'only merge the top fraction').  Returns the
+    the lower A index (Sec. 5.3, top-r selection).  Returns the
     keep mask and the list of chunks whose cut falls inside a near-tie."""
     keep = np.zeros(len(src), dtype=bool)
     cut_ties = []
@@ -149,8 +149,8 @@ def select(src, dst, score, s: int, c: int, r: float, tau: float = TAU):
 
 
 def select_global(src, dst, score, r: float, tau: float = TAU):
-    """The other reading of Sec. 5.2-5.3 ('aggregates the edges from all chunks', 'rank all
-    candidate matches'): the edges of ALL chunks of the sequence are ranked together and the
+    """The other reading of Sec. 5.2-5.3 (edges collected over all chunks, one ranking): the
+    edges of ALL chunks of the sequence are ranked together and the
     m = floor(r * number of edges) best are merged; ties go to the lower A position.  Returns the
     keep mask and (cut score, True when the first dropped edge is within tau of it)."""
     keep = np.zeros(len(src), dtype=bool)
@@ -170,7 +170,7 @@ def select_global(src, dst, score, r: float, tau: float = TAU):
 # --------------------------------------------------------------------------
 def merge(K, V, deg, src, dst, keep, dtype: str):
     """Merge every kept A token into its B partner with degree weights
-    (centroid equation of Sec. 5.3; values 'analogously'), leave the rest
+    (centroid equation of Sec. 5.3; values with the same weights), leave the rest
     unchanged, and emit the retained tokens in their original order.
 
     Returns K', V' (rounded to the storage type, as fp64), deg', the round's

@@ -1,5 +1,5 @@
-// Top-r over ALL chunks of a sequence (Sec. 5.2: the edges of all chunks are aggregated; Sec. 5.3:
-// all candidate matches are ranked by similarity and the top fraction r is merged).
+// Top-r over ALL chunks of a sequence: the reading of Sec. 5.2-5.3 in which the candidate edges of
+// every chunk of a sequence enter one common ranking and the best fraction r of them is merged.
 //
 // One workgroup per (batch, head) sequence finds the cut of the ranking (score descending, position
 // ascending) below its m = floor(r * edges) best edges with a 4-pass radix select over the fp32

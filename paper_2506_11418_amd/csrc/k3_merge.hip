@@ -1,5 +1,5 @@
 // Top-r selection, degree-weighted merge and order-preserving compaction of one clustering round
-// (Sec. 5.3: "rank all candidate matches by similarity and only merge the top fraction"; the
+// (Sec. 5.3: candidate edges are ranked by similarity and only the best fraction r is merged; the
 // centroid equation; values merged with the same weights).
 //
 // One workgroup per (sequence, chunk).  Integer bookkeeping lives in LDS:
