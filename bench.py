@@ -38,11 +38,11 @@ MEASURED_TRAFFIC = {
 }
 
 WORKLOADS = {
-    # benchmark configs[2]: full-model prefill compression, Llama-3-8B KV shape, 128k tokens
+    # the headline configuration: full-model prefill compression, Llama-3-8B KV shape, 128k tokens
     "config3": dict(layers=32, kv_heads=8, q_heads=32, dim=128, seq=131072, chunk=1024, retain=0.25,
                     alpha=0.9, n_outlier=4, desc="llama3-8b 32Lx8KVx128 bf16, seq 131072, chunk 1024, "
                     "retain 25% (rounds [1,1]) + 1 GQA decode step (32 q heads) over the compressed cache"),
-    # benchmark configs[1]: one layer, 32k tokens (small: one launch is a few microseconds)
+    # one layer, 32k tokens (small: one launch is a few microseconds)
     "config2": dict(layers=1, kv_heads=8, q_heads=32, dim=128, seq=32768, chunk=1024, retain=0.25,
                     alpha=0.9, n_outlier=4, desc="llama3-8b single layer 8KVx128 bf16, seq 32768, chunk 1024, "
                     "retain 25% + 1 GQA decode step"),
@@ -268,7 +268,7 @@ def main():
                "sample": f"{n_heads} of {Ly * H} (layer, KV head) sequences of {S} tokens: oracle.compress "
                          f"(rounds {plan.round_r}) + oracle.app_attn, {c1 - c0:.1f} s; scaled to whole-model tokens"}
 
-    # ---- context figure: one layer of the batch-16 serving shape (BASELINE configs[3]) ------------
+    # ---- context figure: one layer of the batch-16 serving shape ---------------------------------
     # 16 sequences x 8 KV heads x 8192 centroids (32768 tokens at 25%), 32 query heads; kernel time
     # from the library's events.  Not part of `value`.
     serving = None

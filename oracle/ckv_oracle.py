@@ -12,8 +12,8 @@ leg may call it.  The product path never does.
 The method is a greedy heuristic, so the oracle is the algorithm itself taken
 step by step; only attention has a closed definition, and it is that
 definition.  Readings where the paper is silent (tie-breaks, floor of the merge
-count, output order, per-chunk selection, schedule for a retain ratio) are the
-ones listed in the design doc; each function names the passage it follows.
+count, output order, per-chunk selection, schedule for a retain ratio) are
+stated where they are taken; each function names the passage it follows.
 
 Pins (tests/test_oracle_*.py): Theorem A.1 by brute force and the closed form
 c_{2n,l} printed in its proof (partition); unit self-similarity, scale
