@@ -296,6 +296,28 @@ def main():
                    "attn_partial_us": round(us, 2), "GBps": round(byts / us / 1e3, 1),
                    "frac_of_hbm_peak": round(byts / us / 1e3 / PEAK_HBM_GBS, 4),
                    "attn_combine_us": round(tt["attn_combine"][0] / tt["attn_combine"][1] * 1e3, 2)}
+        # the same batch attending over UNCOMPRESSED caches of 32768 tokens (degrees NULL): what the
+        # compression buys a decode step.  Attention only, one layer; the rest of a model is not here.
+        uK = torch.randn((Bs, H, 4 * Ls, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        uV = torch.randn((Bs, H, 4 * Ls, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        uws = torch.empty(ckv.decode_attn_workspace(ckv.layout_of(uK), Hq), dtype=torch.uint8, device=dev)
+        for _ in range(2):
+            ckv.decode_attn(gq, uK, uV, out=go, workspace=uws)
+        torch.cuda.synchronize()
+        ckv.timing_reset()
+        ckv.timing_enable(True)
+        for _ in range(10):
+            ckv.decode_attn(gq, uK, uV, out=go, workspace=uws)
+        torch.cuda.synchronize()
+        ckv.timing_enable(False)
+        tu = ckv.timing_read()
+        uus = (tu["attn_partial_bf16"][0] / tu["attn_partial_bf16"][1] + tu["attn_combine"][0] / tu["attn_combine"][1]) * 1e3
+        cus = us + serving["attn_combine_us"]
+        serving["uncompressed_32768_attn_us"] = round(uus, 2)
+        serving["attention_only_tokens_per_s_32_layers"] = {"compressed": round(Bs / (32 * cus * 1e-6), 1),
+                                                            "uncompressed": round(Bs / (32 * uus * 1e-6), 1)}
+        del uK, uV, uws
+        ckv.decode_attn(gq, gK, gV, deg=gdeg, out=go, workspace=gws)     # `go` again holds the compressed result
         # the same tokens in a block-paged pool (blocks of 16 tokens, shuffled), read in place
         bs = 16
         nblk = Bs * Ls // bs
