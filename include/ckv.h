@@ -189,6 +189,13 @@ int ckv_paged_decode_attn(const void* q, int32_t q_heads, const void* K_pool, co
                           const ckv_paged_layout* pl, int32_t max_len, float scale, void* o, int32_t o_dtype,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ckv_append on pages (Algorithm 1, decoding part): the new token of sequence b (k_new, v_new
+ * [batch, heads, dim] contiguous) goes to position lens[b] of every head with degree 1, and lens[b]
+ * is incremented on the stream afterwards.  The caller's block manager must have put a block at
+ * block_table[b][lens[b] / block_size]; a sequence without one there is left untouched. */
+int ckv_paged_append(const void* k_new, const void* v_new, void* K_pool, void* V_pool, int32_t* deg_pool,
+                     const int32_t* block_table, int32_t* lens, const ckv_paged_layout* pl, void* hip_stream);
+
 /* Copy the first `seq` tokens of every sequence from the pool into strided tensors K, V (layout
  * `out`, out->seq >= seq) and deg (row stride out->deg_stride; may be NULL), or back. */
 int ckv_paged_gather(const void* K_pool, const void* V_pool, const int32_t* deg_pool, const int32_t* block_table,

@@ -81,6 +81,7 @@ def lib() -> C.CDLL:
         L.ckv_paged_decode_attn_workspace.argtypes = [PL, i32, i32, C.POINTER(C.c_size_t)]
         L.ckv_paged_decode_attn.argtypes = [vp, i32, vp, vp, vp, vp, vp, PL, i32, C.c_float, vp, i32, vp,
                                             C.c_size_t, vp]
+        L.ckv_paged_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, PL, vp]
         L.ckv_paged_gather.argtypes = [vp, vp, vp, vp, PL, i32, vp, vp, vp, C.POINTER(Layout), vp]
         L.ckv_paged_scatter.argtypes = [vp, vp, vp, C.POINTER(Layout), vp, vp, vp, vp, PL, i32, vp, vp, vp]
         L.ckv_paged_compress_plan.argtypes = [PL, i32, C.POINTER(Params), C.POINTER(i32), C.POINTER(i32),
@@ -294,6 +295,18 @@ def paged_decode_attn(q, K_pool, V_pool, deg_pool, block_table, lens, max_len: i
     if st != 0:
         raise CkvError(st, "ckv_paged_decode_attn")
     return out
+
+
+def paged_append(k_new, v_new, K_pool, V_pool, deg_pool, block_table, lens) -> None:
+    """ckv_paged_append: one new token per sequence at position lens[b] (then lens[b] += 1)."""
+    pl = paged_layout_of(K_pool, block_table)
+    for t in (k_new, v_new):
+        if tuple(t.shape) != (pl.batch, pl.heads, pl.dim) or not t.is_contiguous() or t.dtype != K_pool.dtype:
+            raise ValueError("k_new, v_new must be contiguous [batch, heads, dim] tensors of the cache dtype")
+    st = lib().ckv_paged_append(_ptr(k_new), _ptr(v_new), _ptr(K_pool), _ptr(V_pool), _ptr(deg_pool),
+                                _ptr(block_table), _ptr(lens), C.byref(pl), _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_paged_append")
 
 
 def paged_gather(K_pool, V_pool, deg_pool, block_table, seq: int):

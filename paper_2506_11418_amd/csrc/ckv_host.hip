@@ -498,6 +498,20 @@ int ckv_paged_decode_attn(const void* q, int32_t q_heads, const void* K_pool, co
                                                  static_cast<hipStream_t>(hip_stream)));
 }
 
+int ckv_paged_append(const void* k_new, const void* v_new, void* K_pool, void* V_pool, int32_t* deg_pool,
+                     const int32_t* block_table, int32_t* lens, const ckv_paged_layout* pl, void* hip_stream) {
+  int shift;
+  int st = check_paged(pl, &shift);
+  if (st != CKV_OK) return st;
+  if (!k_new || !v_new || !K_pool || !V_pool || !block_table || !lens) return CKV_EINVAL;
+  if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)K_pool | (uintptr_t)V_pool) % 16) return CKV_EALIGN;
+  const int e = ckv::elem_bytes(pl->dtype);
+  return ckv::hip_status(ckv::launch_paged_append(k_new, v_new, K_pool, V_pool, deg_pool,
+                                                  ckv::PagedView{block_table, pl->max_blocks, shift, pl->n_blocks},
+                                                  pl->batch, pl->heads, pl->dim * e, lens,
+                                                  static_cast<hipStream_t>(hip_stream)));
+}
+
 int ckv_paged_gather(const void* K_pool, const void* V_pool, const int32_t* deg_pool, const int32_t* block_table,
                      const ckv_paged_layout* pl, int32_t seq, void* K, void* V, int32_t* deg,
                      const ckv_layout* out, void* hip_stream) {

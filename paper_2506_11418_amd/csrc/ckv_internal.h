@@ -128,6 +128,10 @@ hipError_t launch_decode_attn(const void* q, int q_heads, const void* K, const v
 hipError_t launch_paged_gather(const void* K_pool, const void* V_pool, const int32_t* deg_pool, PagedView paged,
                                int n_b, int heads, int seq, int row_bytes, void* K, void* V, int32_t* deg,
                                TensorView out, int elem_bytes, hipStream_t st);
+// Decode-step update of a paged cache: token lens[b] of every head := (k_new, v_new, degree 1), then
+// lens[b] += 1; a sequence whose next position has no block inside the pool is left alone.
+hipError_t launch_paged_append(const void* k_new, const void* v_new, void* K_pool, void* V_pool, int32_t* deg_pool,
+                               PagedView paged, int n_b, int heads, int row_bytes, int32_t* lens, hipStream_t st);
 // Scatter also releases blocks: entries [keep_blocks, old_blocks) of every table row are copied to
 // freed[b*n_freed + k] (if freed != NULL) and set to -1, and lens[b] := seq (if lens != NULL).
 hipError_t launch_paged_scatter(const void* K, const void* V, const int32_t* deg, TensorView in, int n_b, int heads,

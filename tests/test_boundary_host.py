@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(ckv_[a-z_]+)\s*\(", header))
     assert {"ckv_plan", "ckv_match", "ckv_compress", "ckv_decode_attn", "ckv_decode_attn_workspace",
             "ckv_version", "ckv_strerror", "ckv_append", "ckv_schedule_annealed", "ckv_paged_decode_attn",
-            "ckv_paged_gather", "ckv_paged_scatter", "ckv_paged_compress", "ckv_paged_compress_plan"} <= names
+            "ckv_paged_gather", "ckv_paged_scatter", "ckv_paged_append", "ckv_paged_compress", "ckv_paged_compress_plan"} <= names
     L = ckv.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -127,6 +127,8 @@ def test_paged_plan_and_argument_checks():
     assert L.ckv_paged_decode_attn_workspace(C.byref(pl), 30, 4096, C.byref(n)) == -2
     assert L.ckv_paged_decode_attn(a, 32, a, a, z, a, z, C.byref(pl), 4096, 0.0, a, 0, a, n.value, z) == -1   # lens required
     assert L.ckv_paged_decode_attn(a, 32, a, a, z, a, a, C.byref(pl), 4096, 0.0, a, 0, a, 16, z) == -4
+    assert L.ckv_paged_append(a, a, a, a, z, a, z, C.byref(pl), z) == -1                                      # lens required
+    assert L.ckv_paged_append(a, a, C.c_void_p(4100), a, z, a, a, C.byref(pl), z) == -3
     lay = _lay(batch=2, heads=8, seq=512)
     assert L.ckv_paged_gather(a, a, z, a, C.byref(pl), 1024, a, a, z, C.byref(lay), z) == -2                 # seq > out->seq
     assert L.ckv_paged_scatter(a, a, z, C.byref(lay), a, a, z, a, C.byref(pl), 100, z, z, z) == -2           # old_seq < seq

@@ -161,3 +161,66 @@ def test_paged_compress_equals_strided_compress(seq, chunk, kw):
     for b in range(B):
         ref = oracle.app_attn(f64(q[b]), f64(cK[b]), f64(cV[b]), i64(cdeg[b]))
         assert_rows_close(f64(o[b]), ref, ATTN_TOL, f"attention over compacted pages b{b}")
+
+
+def test_algorithm1_decode_loop_on_a_paged_cache():
+    """The decode loop of Algorithm 1 kept entirely in pages: ckv_paged_append, attention over the
+    pages, in-place compression with block release once the cache holds budget + g tokens, blocks
+    handed back and out again by a toy free list.  Every step's output must equal, bit for bit,
+    the strided OnlineCache on the same tokens (that loop is checked against the oracle in
+    test_gpu_online.py); at the end the pages hold exactly the strided cache."""
+    from paper_2506_11418_amd.online import OnlineCache
+    _say("online loop on pages")
+    B, H, G, D, bs = 2, 2, 2, 128, 16
+    n, chunk, R, g, n_sink, n_recent, steps = 1024, 128, 0.5, 16, 4, 8, 120
+    K, V, _ = kv_host(95, B * H, n + steps, D, "bf16", alpha=0.9, n_outlier=4)
+    K, V = K.reshape(B, H, n + steps, D).to(DEV), V.reshape(B, H, n + steps, D).to(DEV)
+    qs = torch.randn((steps, B, H * G, D), generator=torch.Generator().manual_seed(5)).to(torch.bfloat16).to(DEV)
+    ref = OnlineCache(K[:, :, :n], V[:, :, :n], chunk, R, g, H * G, 0.8, 0.2, 0.2, n_sink, n_recent)
+    budget = ref.budget
+
+    # pages: a pool with a free list on the host
+    n_blocks, max_blocks = 200, (n + bs - 1) // bs + 2
+    free = list(range(n_blocks))[::-1]
+    K_pool = torch.zeros((n_blocks, H, bs, D), dtype=torch.bfloat16, device=DEV)
+    V_pool = torch.zeros_like(K_pool)
+    deg_pool = torch.zeros((n_blocks, H, bs), dtype=torch.int32, device=DEV)
+    table_h = torch.full((B, max_blocks), -1, dtype=torch.int32)
+    for b in range(B):
+        for i in range((n + bs - 1) // bs):
+            table_h[b, i] = free.pop()
+    table = table_h.to(DEV)
+    lens = torch.full((B,), n, dtype=torch.int32, device=DEV)
+    ones = torch.ones((B, H, n), dtype=torch.int32, device=DEV)
+    ckv.paged_scatter(K[:, :, :n].contiguous(), V[:, :, :n].contiguous(), ones, K_pool, V_pool, deg_pool, table, n)
+    # first clustering after prefill (same schedule as the reference helper)
+    s, freed = ckv.paged_compress(K_pool, V_pool, deg_pool, table, n, chunk, rounds=ref.rounds_prefill, lens=lens,
+                                  n_sink=n_sink, n_recent=n_recent)
+    free.extend(freed.flatten().tolist())
+    assert s == ref.s
+    n_rounds = 0
+    for i in range(steps):
+        if s % bs == 0:                                   # the next token opens a block: take one from the free list
+            for b in range(B):
+                table[b, s // bs] = free.pop()
+        ckv.paged_append(K[:, :, n + i].contiguous(), V[:, :, n + i].contiguous(), K_pool, V_pool, deg_pool, table, lens)
+        s += 1
+        # max_len = the current length: the same split of the sequence as the strided call, hence the same bits
+        o = ckv.paged_decode_attn(qs[i], K_pool, V_pool, deg_pool, table, lens, max_len=s, out_dtype=torch.float32)
+        o_ref = ref.step(qs[i], K[:, :, n + i].contiguous(), V[:, :, n + i].contiguous(), out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert lens.tolist() == [s] * B
+        assert torch.equal(o, o_ref), f"step {i}"
+        if s >= budget + g:
+            s, freed = ckv.paged_compress(K_pool, V_pool, deg_pool, table, s, chunk, rounds=[0.8], lens=lens,
+                                          n_sink=n_sink, n_recent=n_recent)
+            free.extend(freed.flatten().tolist())
+            n_rounds += 1
+            assert s == ref.s
+    assert n_rounds == ref.n_clusterings and n_rounds >= 1
+    gK, gV, gdeg = ckv.paged_gather(K_pool, V_pool, deg_pool, table, s)
+    rK, rV, rdeg = ref.view()
+    torch.cuda.synchronize()
+    assert torch.equal(gK, rK) and torch.equal(gV, rV) and torch.equal(gdeg, rdeg)
+    used = set(table[table >= 0].flatten().tolist())
+    assert len(used) == B * ((s + bs - 1) // bs) and used.isdisjoint(free) and len(used) + len(free) == n_blocks
