@@ -177,9 +177,10 @@ __device__ __forceinline__ void stg16(void* base, uint32_t byte_off, const uint4
 // exact, the other lane of the pair contributes an exact zero, and the single fp32 rounding is
 // that of fmaf (for finite data; a non-finite element also poisons its pair partner).  Larger
 // weights take the unpack + fma route.
-__device__ __forceinline__ void fma_bf16x8(float* acc, const uint4& u, int w) {
+template <bool WIDE>
+__device__ __forceinline__ void fma_bf16x8_t(float* acc, const uint4& u, int w) {
   const uint32_t x[4] = {u.x, u.y, u.z, u.w};
-  if (__any(w > 256)) {
+  if (WIDE) {
     const float fw = (float)w;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -196,6 +197,12 @@ __device__ __forceinline__ void fma_bf16x8(float* acc, const uint4& u, int w) {
       acc[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(xi, w_hi, acc[2 * i + 1], false);
     }
   }
+}
+// Both routes give the same bits, so which one runs is a matter of speed only: the caller may
+// decide per call (here) or once for a whole workgroup (the merge kernel's two emit versions).
+__device__ __forceinline__ void fma_bf16x8(float* acc, const uint4& u, int w) {
+  if (__any(w > 256)) fma_bf16x8_t<true>(acc, u, w);
+  else fma_bf16x8_t<false>(acc, u, w);
 }
 
 }  // namespace ckv

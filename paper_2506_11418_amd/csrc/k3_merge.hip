@@ -9,6 +9,8 @@
 //   local_out[]  prefix sum over retained tokens (all B tokens, unkept A tokens).
 // Rows are then produced gather-style: 16-byte pieces, one row per group of row_bytes/16 lanes,
 // fp32 accumulation for bf16 (fp64 for fp32 storage), one rounding to the storage type.
+#include <type_traits>
+
 #include "ckv_internal.h"
 #include "ckv_device.h"
 
@@ -51,7 +53,8 @@ struct Row<__bf16> {
   typedef uint4 Raw;
   __device__ static Raw load_raw(const __bf16* p) { return ldg16_stream(p); }
   __device__ static void store_raw(__bf16* p, const Raw& r) { stg16_stream(p, r); }
-  __device__ static void fma_into(Acc* acc, const Raw& u, int w) { fma_bf16x8(acc, u, w); }
+  template <bool WIDE>
+  __device__ static void fma_into(Acc* acc, const Raw& u, int w) { fma_bf16x8_t<WIDE>(acc, u, w); }
   __device__ static Raw div_raw(const Acc* acc, int n) { return round_div_pack_bf16(acc, n); }
   __device__ static void store_div(__bf16* p, const Acc* acc, int n) { stg16_stream(p, div_raw(acc, n)); }
 };
@@ -63,6 +66,7 @@ struct Row<float> {
   typedef float4 Raw;
   __device__ static Raw load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
   __device__ static void store_raw(float* p, const Raw& r) { *reinterpret_cast<float4*>(p) = r; }
+  template <bool WIDE>
   __device__ static void fma_into(Acc* acc, const Raw& u, int wi) {
     const double w = (double)wi;
     acc[0] += w * (double)u.x; acc[1] += w * (double)u.y; acc[2] += w * (double)u.z; acc[3] += w * (double)u.w;
@@ -345,28 +349,31 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     }
     return x;
   };
-  auto v_finish = [&](const VLoad& x) -> Raw {
+  auto v_finish = [&](auto wide_c, const VLoad& x) -> Raw {
+    constexpr bool WIDE = decltype(wide_c)::value;
     if (MODE != kMergeOrigin || x.n == 0) return x.b;
     Acc a[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) a[e] = 0;
-    Row<T>::fma_into(a, x.b, x.db);
+    Row<T>::template fma_into<WIDE>(a, x.b, x.db);
     int nd = x.db;
 #pragma unroll
     for (int q = 0; q < kEager; ++q)
       if (q < x.n) {
-        Row<T>::fma_into(a, x.m[q], x.dm[q]);
+        Row<T>::template fma_into<WIDE>(a, x.m[q], x.dm[q]);
         nd += x.dm[q];
       }
     for (int q = kEager; q < x.n; ++q) {
       const int ta = x.base + 2 * (int)x.mem[q];
       const int da = d0p ? d0p[ta] : 1;
-      Row<T>::fma_into(a, Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s), da);
+      Row<T>::template fma_into<WIDE>(a, Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s), da);
       nd += da;
     }
     return Row<T>::div_raw(a, nd);
   };
 
+  auto emit = [&](auto wide_c) {
+  constexpr bool WIDE = decltype(wide_c)::value;
   for (int ob = 0; ob < n_out; ob += NRG * U) {
     int tok[U], nmem[U], first[U], mem0[U], du[U], dm[U];
     bool valid[U];
@@ -399,26 +406,26 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       const int o = ob + u * NRG + rg;
       if (nmem[u] == 0) {  // untouched token: bit copy
         Row<T>::store_raw(Ko + (int64_t)o * out.stride_s, kb[u]);
-        if (MODE != kMergeKeys) Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, v_finish(vb[u]));
+        if (MODE != kMergeKeys) Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, v_finish(wide_c, vb[u]));
         if (piece == 0) dout[o] = du[u];
         continue;
       }
       Acc ak[E], av[E];
 #pragma unroll
       for (int e = 0; e < E; ++e) { ak[e] = 0; av[e] = 0; }
-      Row<T>::fma_into(ak, kb[u], du[u]);
-      Row<T>::fma_into(ak, km[u], dm[u]);
+      Row<T>::template fma_into<WIDE>(ak, kb[u], du[u]);
+      Row<T>::template fma_into<WIDE>(ak, km[u], dm[u]);
       if (MODE != kMergeKeys) {
-        Row<T>::fma_into(av, v_finish(vb[u]), du[u]);
-        Row<T>::fma_into(av, v_finish(vm[u]), dm[u]);
+        Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, vb[u]), du[u]);
+        Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, vm[u]), dm[u]);
       }
       int ndeg = du[u] + dm[u];
       for (int q = 1; q < nmem[u]; ++q) {
         const int ua = 2 * (int)s_members[first[u] + q];
         const int da = dseq ? dseq[ua] : 1;
         const Raw kx = Row<T>::load_raw(Kin + (int64_t)ua * in.stride_s);
-        Row<T>::fma_into(ak, kx, da);
-        if (MODE != kMergeKeys) Row<T>::fma_into(av, v_finish(v_issue(ua)), da);
+        Row<T>::template fma_into<WIDE>(ak, kx, da);
+        if (MODE != kMergeKeys) Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, v_issue(ua)), da);
         ndeg += da;
       }
       Row<T>::store_div(Ko + (int64_t)o * out.stride_s, ak, ndeg);
@@ -426,6 +433,23 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       if (piece == 0) dout[o] = ndeg;
     }
   }
+  };
+  // Two versions of the emit loop: weights up to 256 ride in a packed bf16 operand (one v_dot2 per
+  // element); a chunk that holds a larger degree takes the general route.  Same bits either way.
+  bool wide;
+  {
+    int big = 0;
+    if (deg_in) {
+      for (int u = tid; u < L; u += kThreads) big |= dseq[u] > 256;
+    }
+    if (MODE == kMergeOrigin && d0p) {
+      const int t_lo = 2 * g * chunk, t_hi = min(org.seq0, t_lo + 2 * chunk);
+      for (int t = t_lo + tid; t < t_hi; t += kThreads) big |= d0p[t] > 256;
+    }
+    wide = __syncthreads_or(big) != 0;
+  }
+  if (wide) emit(std::true_type{});
+  else emit(std::false_type{});
 }
 
 __global__ void compose_kernel(int32_t* __restrict__ assign, const int32_t* __restrict__ map, int seq0,

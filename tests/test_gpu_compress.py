@@ -283,6 +283,24 @@ def test_incoming_degrees_weight_the_merge():
     _run_rounds_teacher_forced(K, V, 128, [0.75, 0.5], "deg_in", deg=deg)
 
 
+def test_large_incoming_degrees():
+    """Degrees far above 256 (the limit of the packed-weight accumulation route) in some chunks and
+    small ones in others, through full rounds and through a deferred pair."""
+    _say("large degrees")
+    heads, seq, chunk = 2, 3000, 256
+    K, V, _ = kv_host(61, heads, seq, 128, "bf16", alpha=0.9, n_outlier=4)
+    K, V = K.to(DEV), V.to(DEV)
+    d = np.random.default_rng(9).integers(1, 4, (1, heads, seq))
+    d[0, 0, 700:1400] = np.random.default_rng(10).integers(200, 70000, 700)          # some chunks with wide weights
+    d[0, 1, 2990:] = 100000
+    deg = torch.from_numpy(d.astype(np.int32)).to(DEV)
+    fK, fV, fdeg, _ = _run_rounds_teacher_forced(K, V, chunk, [1.0, 0.7], "large degrees", deg=deg)
+    gK, gV, gdeg, _ = ckv.compress(K, V, chunk, rounds=[1.0, 0.7], deg=deg)            # deferred pair
+    torch.cuda.synchronize()
+    assert torch.equal(gK, fK) and torch.equal(gV, fV) and torch.equal(gdeg, fdeg)
+    assert int(gdeg.sum()) == int(d.sum())
+
+
 def test_duplicate_keys_merge_losslessly_on_gpu():
     _say("compress duplicate keys")
     k = torch.randn(128, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16)
