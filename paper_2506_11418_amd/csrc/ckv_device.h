@@ -92,31 +92,26 @@ __device__ __forceinline__ void tile_argmax(const f32x16& acc, const f32x4 (&ib)
 }
 
 
-// Quotient S/n rounded to bf16 with a single nearest-even rounding: the fp32 quotient is
-// correctly rounded, so a second rounding can only go wrong when it sits exactly on a bf16
-// midpoint; the sign of the exact residual S - q*n then says on which side the true value lies.
-__device__ inline uint32_t div_round_bf16(float S, float n) {
-  const float q = S / n;
+// acc[0..8)/n as 8 packed bf16, ONE nearest-even rounding (n < 2^21).
+// q = acc * (1/n) with a correctly rounded reciprocal lies within 3 ulp(fp32) of the true quotient
+// t.  For n a power of two q = t.  Otherwise the converter's rounding of q can differ from that of
+// t only if q sits within those 3 ulp of a bf16 midpoint M (low 16 bits in 0x7ffd..0x8003), and not
+// even then if q*n == acc exactly (sums of bf16 values divide evenly quite often; q = t then).
+// The remaining elements are decided exactly: r = acc - q*n is representable, so fma gives it
+// without error; q - M is exact; and (t - M)*n = (q - M)*n + r, whose sign one more fma delivers
+// (rounding keeps signs and zeros).  |t| > |M| rounds away from zero, a zero means t = M (tie to
+// even).  That path is taken for the whole wave only when some element needs it.
+__device__ __forceinline__ uint32_t round_bf16_near_midpoint(float S, float fn, float q) {
   const uint32_t u = __float_as_uint(q);
-  const uint32_t low = u & 0xffffu;
-  uint32_t up;
-  if (low == 0x8000u) {
-    const float res = fmaf(-q, n, S);
-    up = (res == 0.f) ? ((u >> 16) & 1u) : (((res > 0.f) == (q > 0.f)) ? 1u : 0u);
-  } else {
-    up = low > 0x8000u;
-  }
-  return ((u >> 16) + up) & 0xffffu;
+  const uint32_t H = u & 0xffff0000u;
+  const float M = __uint_as_float(H | 0x8000u);
+  const float r = fmaf(-q, fn, S);
+  const float d = fmaf(q - M, fn, r);
+  const bool away = (d > 0.f) == ((u >> 31) == 0u);
+  const uint32_t up = (d == 0.f) ? ((H >> 16) & 1u) : (away ? 1u : 0u);
+  return ((H >> 16) + up) & 0xffffu;
 }
 
-
-// acc[0..8)/n as 8 packed bf16, ONE nearest-even rounding.  Fast path: multiply by the fp32
-// reciprocal and let the packed converter round.  For n a power of two the product is exact,
-// midpoints included.  Otherwise the product q is within 3 ulp(fp32) of the true quotient: if its
-// low 16 bits are farther than that from a bf16 midpoint, or if q*n == acc exactly (sums of bf16
-// values divide evenly quite often, and exact midpoints are then rounded correctly by the
-// converter), the result is the correctly rounded quotient; the few remaining elements take the
-// exact path.
 __device__ __forceinline__ uint4 round_div_pack_bf16(const float* acc, int n) {
   const float fn = (float)n;
   const float rcp = 1.0f / fn;   // correctly rounded: quotients that divide evenly then come out exact
@@ -129,24 +124,29 @@ __device__ __forceinline__ uint4 round_div_pack_bf16(const float* acc, int n) {
     window |= ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
   }
   window &= !pow2;
-  bool risky = false;
-  if (__any(window)) {   // rare (a few 1e-4 per element): only then pay for the exactness test
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x2 v = {qv[2 * i], qv[2 * i + 1]};
+    w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+  }
+  if (__any(window)) {   // some element sits next to a midpoint: does it divide evenly (then q is exact)?
+    bool risky = false;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const bool win = ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
       risky |= win & (fmaf(-qv[i], fn, acc[i]) != 0.f);
     }
     risky &= !pow2;
-  }
-  uint32_t w[4];
-  if (__any(risky)) {
+    if (__any(risky)) {  // rare (a few 1e-4 per element): decide those elements exactly
 #pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = div_round_bf16(acc[2 * i], fn) | (div_round_bf16(acc[2 * i + 1], fn) << 16);
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const f32x2 v = {qv[2 * i], qv[2 * i + 1]};
-      w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+      for (int i = 0; i < 8; ++i) {
+        const bool win = !pow2 && ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
+        if (win) {
+          const uint32_t h = round_bf16_near_midpoint(acc[i], fn, qv[i]);
+          w[i >> 1] = (i & 1) ? ((w[i >> 1] & 0x0000ffffu) | (h << 16)) : ((w[i >> 1] & 0xffff0000u) | h);
+        }
+      }
     }
   }
   return make_uint4(w[0], w[1], w[2], w[3]);
