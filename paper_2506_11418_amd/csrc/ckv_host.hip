@@ -281,9 +281,16 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
   // Deferred values: when round j merges every edge (r = 1) and another round follows, round j
   // writes keys and degrees only and round j+1 rebuilds the value rows it needs from round j's
   // value input (bit-identical; the intermediate value cache is neither written nor read).
-  // CKV_DISABLE_DEFERRED_VALUES=1 runs every round in full (used by the tests to compare).
+  // It pays once the second round has enough workgroups (one per chunk, each rebuilding the values
+  // of 2*chunk original tokens) to fill the chip: from about 4 per CU on MI355X (measured
+  // crossover at 1024 chunks); smaller jobs run every round in full.
+  // CKV_DISABLE_DEFERRED_VALUES=1 runs every round in full, CKV_FORCE_DEFERRED_VALUES=1 defers
+  // whatever the size (both used by the tests to compare the two paths).
   const char* defer_env = getenv("CKV_DISABLE_DEFERRED_VALUES");
+  const char* force_env = getenv("CKV_FORCE_DEFERRED_VALUES");
   const bool allow_defer = !(defer_env && defer_env[0] == '1');
+  const bool force_defer = force_env && force_env[0] == '1';
+  const int64_t kDeferMinChunks = 1024;
   int16_t* lists = reinterpret_cast<int16_t*>(ws + w.lists);
   ValueOrigin org{};
   bool have_org = false;
@@ -297,7 +304,8 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
                       fused2_supported(in->dtype, in->dim, p->chunk, len, plan.round_r[j]) &&
                       curView.stride_s <= (1 << 18) && out->stride_s <= (1 << 18);
     const bool defer_ok = allow_defer && !fuse && !have_org && j + 1 < plan.n_rounds &&
-                          plan.round_r[j] == 1.0f && p->scope == CKV_SCOPE_CHUNK;
+                          plan.round_r[j] == 1.0f && p->scope == CKV_SCOPE_CHUNK &&
+                          (force_defer || (int64_t)n_bh * div_up(plan.round_len[j + 1], p->chunk) >= kDeferMinChunks);
     const int jo = fuse ? j + 1 : j;                 // index of the round whose output is produced
     const int next = plan.round_len[jo + 1];
     const bool last = (jo == plan.n_rounds - 1);

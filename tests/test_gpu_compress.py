@@ -328,8 +328,13 @@ def test_large_incoming_degrees():
     d[0, 1, 2990:] = 100000
     deg = torch.from_numpy(d.astype(np.int32)).to(DEV)
     fK, fV, fdeg, _ = _run_rounds_teacher_forced(K, V, chunk, [1.0, 0.7], "large degrees", deg=deg)
-    gK, gV, gdeg, _ = ckv.compress(K, V, chunk, rounds=[1.0, 0.7], deg=deg)            # deferred pair
-    torch.cuda.synchronize()
+    import os
+    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"
+    try:
+        gK, gV, gdeg, _ = ckv.compress(K, V, chunk, rounds=[1.0, 0.7], deg=deg)        # deferred pair
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
     assert torch.equal(gK, fK) and torch.equal(gV, fV) and torch.equal(gdeg, fdeg)
     assert int(gdeg.sum()) == int(d.sum())
 
@@ -480,12 +485,16 @@ def test_deferred_values_are_bit_identical_to_full_rounds(dtype, heads, seq, dim
     deg = None
     if use_deg:
         deg = torch.from_numpy(np.random.default_rng(2).integers(1, 7, (1, heads, seq)).astype(np.int32)).to(DEV)
-    ckv.timing_reset()
-    ckv.timing_enable(True)
-    got = ckv.compress(K, V, chunk, rounds=rounds, deg=deg, **kw)
-    torch.cuda.synchronize()
-    ckv.timing_enable(False)
-    names = ckv.timing_read()
+    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"      # small inputs would otherwise run every round in full
+    try:
+        ckv.timing_reset()
+        ckv.timing_enable(True)
+        got = ckv.compress(K, V, chunk, rounds=rounds, deg=deg, **kw)
+        torch.cuda.synchronize()
+        ckv.timing_enable(False)
+        names = ckv.timing_read()
+    finally:
+        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
     suffix = "bf16" if dtype == "bf16" else "f32"
     assert f"merge_keys_{suffix}" in names and f"merge_origin_{suffix}" in names      # the deferred path really ran
     os.environ["CKV_DISABLE_DEFERRED_VALUES"] = "1"
@@ -515,7 +524,12 @@ def test_deferred_values_with_strided_input_and_padded_output():
     oV = torch.zeros_like(oK)
     odeg = torch.zeros((B, H, out_len + 24), dtype=torch.int32, device=DEV)
     oas = torch.empty((B, H, S), dtype=torch.int32, device=DEV)
-    ckv.compress(K, V, c, retain_ratio=0.25, out=(oK, oV, odeg, oas))
+    import os
+    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"
+    try:
+        ckv.compress(K, V, c, retain_ratio=0.25, out=(oK, oV, odeg, oas))
+    finally:
+        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
     ref = ckv.compress(K.contiguous(), V.contiguous(), c, rounds=[1.0])
     ref = ckv.compress(ref[0], ref[1], c, rounds=[1.0], deg=ref[2])         # two full single-round calls
     torch.cuda.synchronize()
