@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     const float* __restrict__ score, T* __restrict__ K_out, T* __restrict__ V_out,
     int32_t* __restrict__ deg_out, TensorView out, int64_t deg_out_stride, int32_t* __restrict__ map_out,
     int64_t deg_in_stride, int64_t map_stride, int map_offset, const int2* __restrict__ sel_table,
-    int16_t* __restrict__ lists_out, ValueOrigin org) {
+    int16_t* __restrict__ lists_out, ValueOrigin org, int parts) {
   constexpr int E = Row<T>::E;
   constexpr int LPR = D / E;                 // lanes per row
   constexpr int NRG = kThreads / LPR;        // row groups per workgroup
@@ -119,7 +119,10 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   __shared__ int16_t s_src_of_out[2 * kMaxHalf];
   __shared__ int s_wave_tot[4];
 
-  const int g = blockIdx.x % n_chunks, bh = blockIdx.x / n_chunks;
+  // `parts` workgroups share a chunk when the launch would otherwise leave most of the chip idle:
+  // each repeats the (cheap) bookkeeping and emits every parts-th group of output rows.
+  const int part = blockIdx.x % parts, wg = blockIdx.x / parts;
+  const int g = wg % n_chunks, bh = wg / n_chunks;
   const int tid = threadIdx.x;
   const int g0 = g * chunk, L = min(chunk, seq - g0);
   const int half = chunk >> 1;
@@ -262,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   }
   __syncthreads();
 
-  if (MODE == kMergeKeys) {   // member lists of this chunk for the next round's value rebuild
+  if (MODE == kMergeKeys && part == 0) {   // member lists of this chunk for the next round's value rebuild
     int16_t* lst = lists_out + ((int64_t)bh * n_chunks + g) * 3 * half;
     for (int i = tid; i < half; i += kThreads) {
       lst[i] = (i < nB) ? (int16_t)s_cnt[i] : (int16_t)0;
@@ -272,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   }
 
   // ---- assignment map of this round ----------------------------------------------------------
-  if (map_out != nullptr) {
+  if (map_out != nullptr && part == 0) {
     int32_t* mp = map_out + (int64_t)bh * map_stride + g0;
     for (int u = tid; u < L; u += kThreads) {
       const int d = (u & 1) ? -1 : (int)s_dstk[u >> 1];
@@ -374,7 +377,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
   auto emit = [&](auto wide_c) {
   constexpr bool WIDE = decltype(wide_c)::value;
-  for (int ob = 0; ob < n_out; ob += NRG * U) {
+  for (int ob = part * NRG * U; ob < n_out; ob += parts * NRG * U) {
     int tok[U], nmem[U], first[U], mem0[U], du[U], dm[U];
     bool valid[U];
 #pragma unroll
@@ -546,12 +549,15 @@ hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, T
   const int64_t total = (int64_t)n_bh * n_chunks;
   if (total > (1 << 30)) return hipErrorInvalidValue;
   const ValueOrigin o = org ? *org : ValueOrigin{};
+  // small launches: split every chunk's rows over several workgroups, aiming at 4 workgroups per CU
+  int parts = 1;
+  while (parts < 8 && total * parts < 1024) parts *= 2;
 #define CKV_LAUNCH(MODE)                                                                                      \
-  hipLaunchKernelGGL((merge_kernel<T, D, MODE>), dim3((int)total), dim3(kThreads), 0, st,                    \
+  hipLaunchKernelGGL((merge_kernel<T, D, MODE>), dim3((int)(total * parts)), dim3(kThreads), 0, st,          \
                      static_cast<const T*>(K), static_cast<const T*>(V), deg_in, in, seq, chunk, n_chunks, r, \
                      dst_local, score, static_cast<T*>(K_out), static_cast<T*>(V_out), deg_out, out,          \
                      deg_out_stride, map_out, deg_in_stride, map_stride, map_offset,                          \
-                     reinterpret_cast<const int2*>(sel_table), lists_out, o)
+                     reinterpret_cast<const int2*>(sel_table), lists_out, o, parts)
   if (org) {
     ScopedTimer t(sizeof(T) == 2 ? "merge_origin_bf16" : "merge_origin_f32", st);
     CKV_LAUNCH(kMergeOrigin);
