@@ -92,6 +92,80 @@ __device__ __forceinline__ void tile_argmax(const f32x16& acc, const f32x4 (&ib)
 }
 
 
+// The same fold as straight-line code cut into 16 steps of about 8 vector instructions (two
+// tiles of the same 32 B rows at once), so that a caller can place one step behind each MFMA of
+// the NEXT tile.  Only valid when tiles arrive in INCREASING order of B index: a strict
+// comparison then keeps the lowest index among equal maxima.  jlane = first B row of the tile
+// + 4 * lane half; accumulator r is B row 8*(r/4) + r%4 past it.  The scaled scores overwrite
+// the accumulators.  Comparisons are taken one step before the selects that use them, so no
+// select has to wait for its lane mask.
+struct FoldRegs {
+  float mt[2];
+  int idx[2];
+  bool eq[4];
+};
+constexpr int kFoldSteps = 16;
+template <int STEP>
+__device__ __forceinline__ void fold_step(f32x16& c0, f32x16& c1, const f32x4 (&ib)[4], FoldRegs& f, int jlane,
+                                          float (&best)[2], int (&bestj)[2]) {
+  if constexpr (STEP < 4) {                       // scale by 1/|k_j|
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      c0[4 * STEP + q] *= ib[STEP][q];
+      c1[4 * STEP + q] *= ib[STEP][q];
+    }
+  } else if constexpr (STEP == 4) {               // maximum of the 16 scores, first half
+    f.mt[0] = __builtin_fmaxf(c0[0], c0[1]);
+    f.mt[1] = __builtin_fmaxf(c1[0], c1[1]);
+#pragma unroll
+    for (int r = 2; r < 8; r += 2) {
+      f.mt[0] = __builtin_fmaxf(__builtin_fmaxf(f.mt[0], c0[r]), c0[r + 1]);
+      f.mt[1] = __builtin_fmaxf(__builtin_fmaxf(f.mt[1], c1[r]), c1[r + 1]);
+    }
+  } else if constexpr (STEP == 5) {               // second half
+#pragma unroll
+    for (int r = 8; r < 16; r += 2) {
+      f.mt[0] = __builtin_fmaxf(__builtin_fmaxf(f.mt[0], c0[r]), c0[r + 1]);
+      f.mt[1] = __builtin_fmaxf(__builtin_fmaxf(f.mt[1], c1[r]), c1[r + 1]);
+    }
+  } else if constexpr (STEP < 15) {               // lowest accumulator that holds the maximum:
+    constexpr int KSET = STEP - 6;                // selects of pair KSET-1, comparisons of pair KSET
+    if constexpr (KSET == 0) { f.idx[0] = 27; f.idx[1] = 27; }
+    if constexpr (KSET >= 1) {
+      constexpr int R1 = 15 - 2 * (KSET - 1), R0 = R1 - 1;
+      if constexpr (R1 != 15) {
+        f.idx[0] = f.eq[0] ? (8 * (R1 >> 2) + (R1 & 3)) : f.idx[0];
+        f.idx[1] = f.eq[1] ? (8 * (R1 >> 2) + (R1 & 3)) : f.idx[1];
+      }
+      f.idx[0] = f.eq[2] ? (8 * (R0 >> 2) + (R0 & 3)) : f.idx[0];
+      f.idx[1] = f.eq[3] ? (8 * (R0 >> 2) + (R0 & 3)) : f.idx[1];
+    }
+    if constexpr (KSET <= 7) {
+      constexpr int R1 = 15 - 2 * KSET, R0 = R1 - 1;
+      f.eq[0] = c0[R1] == f.mt[0];
+      f.eq[1] = c1[R1] == f.mt[1];
+      f.eq[2] = c0[R0] == f.mt[0];
+      f.eq[3] = c1[R0] == f.mt[1];
+    }
+  } else if constexpr (STEP == 15) {              // into the running maxima
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const bool upd = f.mt[t] > best[t];
+      best[t] = upd ? f.mt[t] : best[t];
+      bestj[t] = upd ? jlane + f.idx[t] : bestj[t];
+    }
+  }
+}
+
+template <int FIRST, int LAST>   // steps FIRST .. LAST-1
+__device__ __forceinline__ void fold_steps(f32x16& c0, f32x16& c1, const f32x4 (&ib)[4], FoldRegs& f, int jlane,
+                                           float (&best)[2], int (&bestj)[2]) {
+  if constexpr (FIRST < LAST && FIRST < kFoldSteps) {
+    fold_step<FIRST>(c0, c1, ib, f, jlane, best, bestj);
+    fold_steps<FIRST + 1, LAST>(c0, c1, ib, f, jlane, best, bestj);
+  }
+}
+
 // acc[0..8)/n as 8 packed bf16, ONE nearest-even rounding (n < 2^21).
 // q = acc * (1/n) with a correctly rounded reciprocal lies within 3 ulp(fp32) of the true quotient
 // t.  For n a power of two q = t.  Otherwise the converter's rounding of q can differ from that of

@@ -14,12 +14,18 @@
 // A row: the running maximum costs one multiply (by 1/|k_j|) and half a max3 per element, and the
 // exact index is only resolved for tiles that raise some lane's maximum.
 #include <type_traits>
+#include <utility>
 
 #include "ckv_internal.h"
 #include "ckv_device.h"
 
 namespace ckv {
 namespace {
+
+template <class F, int... S>
+__device__ __forceinline__ void static_for(F&& f, std::integer_sequence<int, S...>) {
+  (f(std::integral_constant<int, S>{}), ...);
+}
 
 constexpr int kThreads = 256;
 constexpr int kRowsPerWave = 64;                 // two 32-row MFMA tiles
@@ -111,7 +117,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
   // panels are visited starting at the one that holds this block's own neighbourhood (keys are
   // most similar to their neighbours, so the running maxima settle in the first panel)
   const int n_panels = div_up(nB, kPanel);
-  const int p_first = min(a0 / kPanel, n_panels - 1);
+  // a block of full tiles takes the software-pipelined loop below, panels in increasing order
+  const bool pipelined = (NW == 8) && (a0 + ABLOCK <= nA) && (nB % kPanel == 0);
+  const int p_first = pipelined ? 0 : min(a0 / kPanel, n_panels - 1);
   {
     constexpr int APIECES = ABLOCK * OCT / THREADS;
     Piece xa[APIECES];
@@ -185,6 +193,68 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
       }
     }
   };
+  if (NW == 8 && pipelined) {
+    // A stage issues the MFMAs of one tile and, one slice of vector work behind each of them,
+    // folds the PREVIOUS tile's accumulators into the running maxima: matrix pipe and vector
+    // ALU of the wave work side by side instead of taking turns.  B fragments are read from
+    // LDS two k-steps ahead; the fences keep the compiler from regrouping the slices.
+    const int jl = 4 * half;
+    auto load_ib = [&](auto row_c, f32x4 (&ib)[4]) {
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd)
+        ib[qd] = *reinterpret_cast<const f32x4*>(ib_lane + decltype(row_c)::value + 8 * qd);
+    };
+    auto stage = [&](auto row_c, auto fold_c, f32x16& n0, f32x16& n1, f32x16& c0, f32x16& c1,
+                     const f32x4 (&ib)[4], f32x4 (&ib_next)[4], int jlane) {
+      constexpr int ROW = decltype(row_c)::value;      // first row of the B tile in the LDS panels
+      constexpr bool FOLD = decltype(fold_c)::value;
+      constexpr int SPS = (kFoldSteps + 2 * KSTEPS - 1) / (2 * KSTEPS);   // fold steps per slice
+      const unsigned char* pb = panel0 + ROW * ROWB;
+      bf16x8 bq[KSTEPS];
+      bq[0] = *reinterpret_cast<const bf16x8*>(pb + boff[0]);
+      bq[1] = *reinterpret_cast<const bf16x8*>(pb + boff[1]);
+      FoldRegs f;
+      auto kstep = [&](auto s_c) {
+        constexpr int S = decltype(s_c)::value;
+        if constexpr (S + 2 < KSTEPS) bq[S + 2] = *reinterpret_cast<const bf16x8*>(pb + boff[S + 2]);
+        n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[S], afrag[0][S], S == 0 ? f32x16{0} : n0, 0, 0, 0);
+        if constexpr (FOLD) fold_steps<2 * S * SPS, (2 * S + 1) * SPS>(c0, c1, ib, f, jlane, best, bestj);
+        __builtin_amdgcn_sched_barrier(0);
+        n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[S], afrag[1][S], S == 0 ? f32x16{0} : n1, 0, 0, 0);
+        if constexpr (FOLD) fold_steps<(2 * S + 1) * SPS, (2 * S + 2) * SPS>(c0, c1, ib, f, jlane, best, bestj);
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      static_for(kstep, std::make_integer_sequence<int, KSTEPS>{});
+      load_ib(row_c, ib_next);       // norms of the tile just multiplied, for its fold one stage on
+    };
+    f32x16 xa0, xa1, xb0, xb1;
+    f32x4 iba[4], ibb[4];
+    auto panel_body = [&](auto buf_c, int p) {
+      constexpr int BUF = decltype(buf_c)::value;
+      constexpr int R = BUF * kPanel, RN = (BUF ^ 1) * kPanel;
+      const int j0 = p * kPanel + jl;
+      stage(std::integral_constant<int, R + 32>{}, std::true_type{}, xb0, xb1, xa0, xa1, iba, ibb, j0);
+      stage(std::integral_constant<int, R + 64>{}, std::true_type{}, xa0, xa1, xb0, xb1, ibb, iba, j0 + 32);
+      stage(std::integral_constant<int, R + 96>{}, std::true_type{}, xb0, xb1, xa0, xa1, iba, ibb, j0 + 64);
+      if (p + 1 < n_panels) {
+        store_panel(BUF ^ 1, (p + 1) * kPanel);
+        if (p + 2 < n_panels) load_panel((p + 2) * kPanel);
+        __syncthreads();
+        stage(std::integral_constant<int, RN>{}, std::true_type{}, xa0, xa1, xb0, xb1, ibb, iba, j0 + 96);
+      } else {
+        FoldRegs f;
+        fold_steps<0, kFoldSteps>(xb0, xb1, ibb, f, j0 + 96, best, bestj);
+      }
+    };
+    store_panel(0, 0);
+    if (n_panels > 1) load_panel(kPanel);
+    __syncthreads();
+    stage(std::integral_constant<int, 0>{}, std::false_type{}, xa0, xa1, xb0, xb1, ibb, iba, 0);
+    for (int p = 0; p < n_panels; p += 2) {
+      panel_body(std::integral_constant<int, 0>{}, p);
+      if (p + 1 < n_panels) panel_body(std::integral_constant<int, 1>{}, p + 1);
+    }
+  } else {
   store_panel(0, p_first * kPanel);
   for (int it_p = 0; it_p < n_panels; ++it_p) {
     int p = p_first + it_p;
@@ -206,6 +276,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
     }
     if (it_p + 1 < n_panels) store_panel(buf ^ 1, p_next * kPanel);
   }
+  }
 
   // ---- merge the two lane halves of every A row and write ------------------------------------
   if (wave_active) {
@@ -222,6 +293,215 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
         score[out_base + a] = b * my_inva[rt];
       }
     }
+  }
+}
+
+// ---- persistent streaming kernel: bf16, dim 128, whole chunks of 1024 tokens -------------------
+// One workgroup per CU walks a contiguous range of (sequence, chunk) items.  While an item is
+// matched, the NEXT item's A rows arrive in a 128 KiB LDS area (one 32-row pass per stage) and the
+// B rows stream through a ring of three 32-row tiles (one tile per stage, loaded four stages
+// ahead into registers, normed on the way into LDS); the two row streams are just the even and
+// odd tokens of the same contiguous walk through memory.  At an item boundary the A operands are
+// re-read from LDS, so no global-memory latency is exposed between items.  Every stage folds
+// tile q while the MFMAs of tile q+1 run (see the pipelined loop of match_bf16_kernel).
+constexpr int kStreamChunk = 1024;
+constexpr int kStreamThreads = 512;
+constexpr int kStreamTile = 32;
+constexpr int kStreamSlots = 3;
+constexpr size_t kStreamLds = (size_t)(kStreamChunk / 2) * 256 + kStreamSlots * kStreamTile * 256 +
+                              kStreamSlots * kStreamTile * sizeof(float);
+
+__global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
+    const __bf16* __restrict__ K, TensorView kv, int seq, int n_chunks, int total_items,
+    int32_t* __restrict__ dst_local, float* __restrict__ score) {
+  constexpr int ROWB = 256, KSTEPS = 8, HALF = kStreamChunk / 2, TILES = HALF / kStreamTile;
+  constexpr int TILEB = kStreamTile * ROWB;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* abuf = smem;                                    // A rows of the next item
+  unsigned char* ring = smem + HALF * ROWB;                      // kStreamSlots B tiles
+  float* invb = reinterpret_cast<float*>(ring + kStreamSlots * TILEB);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int piece = tid & 15, r0 = tid >> 4;                     // this thread's 16 bytes of a 32-row pass
+  const int lds_piece0 = r0 * ROWB + ((piece ^ (r0 & 15)) << 4);
+  const int first = (int)((int64_t)blockIdx.x * total_items / gridDim.x);
+  const int last = (int)((int64_t)(blockIdx.x + 1) * total_items / gridDim.x);
+  if (first >= last) return;
+  const int n_src = n_sources(seq, kStreamChunk);
+  const int64_t pass_pitch = 2 * kStreamTile * kv.stride_s;      // 32 A rows (or B rows) further on
+
+  // Addresses = a workgroup-uniform pass pointer + this thread's fixed offset inside a pass (row
+  // r0, its 16-byte piece), so the walks below cost scalar instructions only.  item_ptr: A row 0 of
+  // an item (clamped to the range); the B row of a pair sits one token later.
+  const uint32_t toff = (uint32_t)(2 * r0 * kv.stride_s + piece * 8) * 2u;   // bytes
+  auto item_ptr = [&](int item) -> const __bf16* {
+    item = min(item, last - 1);
+    const int bh = item / n_chunks, g = item - bh * n_chunks;
+    return K + kv.seq_base(bh) + (int64_t)g * kStreamChunk * kv.stride_s;
+  };
+  auto ld = [&](const __bf16* pass) {
+    Piece x;
+    x.u = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(pass) + toff);
+    return x;
+  };
+  auto put_b = [&](int slot, const Piece& x) {                   // B piece + its row's norm (all 16
+    const float ss = row_sum<16>(sumsq8(x));                     // lanes of a row store the same value)
+    *reinterpret_cast<uint4*>(ring + slot * TILEB + lds_piece0) = x.u;
+    invb[slot * kStreamTile + r0] = inv_norm(ss);
+  };
+
+  // ---- prologue: A rows of the first item, B tiles 0 and 1, four passes of each stream in flight
+  Piece sb[4], sa[4];
+  const __bf16 *pB, *pA;                 // next pass each stream loads: B six tiles, A four passes ahead
+  {
+    const __bf16* p0 = item_ptr(first);
+    const __bf16* p1 = item_ptr(first + 1);
+    Piece xa[TILES];
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) xa[t] = ld(p0 + t * pass_pitch);
+    const Piece b0 = ld(p0 + kv.stride_s);
+    const Piece b1 = ld(p0 + pass_pitch + kv.stride_s);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      sb[u] = ld(p0 + (u + 2) * pass_pitch + kv.stride_s);
+      sa[u] = ld(p1 + u * pass_pitch);
+    }
+    pB = p0 + 6 * pass_pitch + kv.stride_s;
+    pA = p1 + 4 * pass_pitch;
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) *reinterpret_cast<uint4*>(abuf + t * TILEB + lds_piece0) = xa[t].u;
+    put_b(0, b0);
+    put_b(1, b1);
+  }
+  __syncthreads();
+  bf16x8 afrag[2][KSTEPS];
+  float my_inva[2];
+  auto load_afrag = [&](float (&inva)[2]) {
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      const int row = wave * kRowsPerWave + rt * 32 + col;
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s)
+        afrag[rt][s] = *reinterpret_cast<const bf16x8*>(abuf + row * ROWB + ((((2 * s + half) ^ row) & 15) << 4));
+    }
+    inva[0] = inv_norm_of_operand_row<KSTEPS>(afrag[0]);
+    inva[1] = inv_norm_of_operand_row<KSTEPS>(afrag[1]);
+  };
+  load_afrag(my_inva);
+  __syncthreads();
+
+  int boff[KSTEPS];
+#pragma unroll
+  for (int s = 0; s < KSTEPS; ++s) boff[s] = col * ROWB + ((((2 * s + half) ^ col) & 15) << 4);
+  const int jl = 4 * half;
+  const float* ib_lane = invb + jl;
+  float best[2] = {-INFINITY, -INFINITY};
+  int bestj[2] = {0, 0};
+
+  // MFMAs of the tile in `slot` into (n0, n1); with FOLD, the tile held in (c0, c1) is folded behind
+  // them.  The first two B fragments were read at the end of the stage before (the tile is complete
+  // in LDS by then), the next tile's are read here, so no LDS latency follows the barrier.
+  bf16x8 pre[2];
+  auto prefetch = [&](int slot) {
+    pre[0] = *reinterpret_cast<const bf16x8*>(ring + slot * TILEB + boff[0]);
+    pre[1] = *reinterpret_cast<const bf16x8*>(ring + slot * TILEB + boff[1]);
+  };
+  auto stage = [&](int slot, int slot_next, auto fold_c, f32x16& n0, f32x16& n1, f32x16& c0, f32x16& c1,
+                   const f32x4 (&ib)[4], f32x4 (&ib_next)[4], int jlane) {
+    constexpr bool FOLD = decltype(fold_c)::value;
+    constexpr int SPS = (kFoldSteps + 2 * KSTEPS - 1) / (2 * KSTEPS);
+    const unsigned char* pb = ring + slot * TILEB;
+    bf16x8 bq[KSTEPS];
+    bq[0] = pre[0];
+    bq[1] = pre[1];
+    FoldRegs f;
+    auto kstep = [&](auto s_c) {
+      constexpr int S = decltype(s_c)::value;
+      if constexpr (S + 2 < KSTEPS) bq[S + 2] = *reinterpret_cast<const bf16x8*>(pb + boff[S + 2]);
+      n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[S], afrag[0][S], S == 0 ? f32x16{0} : n0, 0, 0, 0);
+      if constexpr (FOLD) fold_steps<2 * S * SPS, (2 * S + 1) * SPS>(c0, c1, ib, f, jlane, best, bestj);
+      __builtin_amdgcn_sched_barrier(0);
+      n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[S], afrag[1][S], S == 0 ? f32x16{0} : n1, 0, 0, 0);
+      if constexpr (FOLD) fold_steps<(2 * S + 1) * SPS, (2 * S + 2) * SPS>(c0, c1, ib, f, jlane, best, bestj);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    static_for(kstep, std::make_integer_sequence<int, KSTEPS>{});
+    // pin the fold to this stage (its results are otherwise free to sink into a later block)
+    if constexpr (FOLD) asm volatile("" : "+v"(best[0]), "+v"(best[1]), "+v"(bestj[0]), "+v"(bestj[1]));
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd)      // norms of the tile just multiplied, for its fold one stage on
+      ib_next[qd] = *reinterpret_cast<const f32x4*>(ib_lane + slot * kStreamTile + 8 * qd);
+    prefetch(slot_next);
+  };
+
+  f32x16 xa0, xa1, xb0, xb1;
+  f32x4 iba[4], ibb[4];
+  prefetch(0);
+  stage(0, 1, std::false_type{}, xa0, xa1, xb0, xb1, ibb, iba, 0);
+  int rs = 1, ws = 2;                    // ring slots: tile q+1 is read, tile q+2 written, in stage q
+  int bh = first / n_chunks, g = first - bh * n_chunks;
+  for (int item = first; item < last; ++item) {
+    // where the two streams continue once they run off their current item (B during this item's
+    // stage 9, A during stage 11)
+    const __bf16* wrapB = item_ptr(item + 1) + kv.stride_s;
+    const __bf16* wrapA = item_ptr(item + 2);
+    float next_inva[2] = {my_inva[0], my_inva[1]};
+    for (int t0 = 0; t0 < TILES; t0 += 4) {
+      // stage t: hand over the passes loaded four stages ago, refill their registers (no branch:
+      // the four stages of this body stay one straight-line block), then compute
+      auto feed = [&](auto u_c) {
+        constexpr int U = decltype(u_c)::value;
+        const int t = t0 + U;
+        put_b(ws, sb[U]);
+        *reinterpret_cast<uint4*>(abuf + t * TILEB + lds_piece0) = sa[U].u;
+        sb[U] = ld(pB);
+        pB = (t == TILES - 7) ? wrapB : pB + pass_pitch;
+        sa[U] = ld(pA);
+        pA = (t == TILES - 5) ? wrapA : pA + pass_pitch;
+        __syncthreads();
+      };
+      auto turn = [&] {
+        rs = (rs == kStreamSlots - 1) ? 0 : rs + 1;
+        ws = (ws == kStreamSlots - 1) ? 0 : ws + 1;
+      };
+      const int j0 = t0 * kStreamTile + jl;
+      feed(std::integral_constant<int, 0>{});
+      stage(rs, ws, std::true_type{}, xb0, xb1, xa0, xa1, iba, ibb, j0);
+      turn();
+      feed(std::integral_constant<int, 1>{});
+      stage(rs, ws, std::true_type{}, xa0, xa1, xb0, xb1, ibb, iba, j0 + 32);
+      turn();
+      feed(std::integral_constant<int, 2>{});
+      stage(rs, ws, std::true_type{}, xb0, xb1, xa0, xa1, iba, ibb, j0 + 64);
+      turn();
+      feed(std::integral_constant<int, 3>{});
+      if (t0 + 4 == TILES && item + 1 < last) {   // the next tile belongs to the next item: its A
+        load_afrag(next_inva);                    // operands (this item's 1/|k_i| is still needed)
+        __syncthreads();                          // abuf may now take the rows of the item after that
+      }
+      stage(rs, ws, std::true_type{}, xa0, xa1, xb0, xb1, ibb, iba, j0 + 96);
+      turn();
+    }
+    // the item's last tile is folded: write its matches
+    const int64_t out_base = (int64_t)bh * n_src + (int64_t)g * HALF;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      const float ob = __shfl_xor(best[rt], 32);
+      const int oj = __shfl_xor(bestj[rt], 32);
+      float b = best[rt];
+      int j = bestj[rt];
+      if (ob > b || (ob == b && oj < j)) { b = ob; j = oj; }
+      const int a = wave * kRowsPerWave + rt * 32 + col;
+      if (half == 0) {
+        dst_local[out_base + a] = j;
+        score[out_base + a] = b * my_inva[rt];
+      }
+      best[rt] = -INFINITY;
+      bestj[rt] = 0;
+      my_inva[rt] = next_inva[rt];
+    }
+    if (++g == n_chunks) { g = 0; ++bh; }
   }
 }
 
@@ -335,6 +615,30 @@ hipError_t launch_match_bf16_nw(const void* K, TensorView kv, int n_bh, int seq,
   return hipGetLastError();
 }
 
+// Whole 1024-token chunks of 128-dim keys: the persistent kernel, one workgroup per CU.
+hipError_t launch_match_stream(const void* K, TensorView kv, int n_bh, int seq, int32_t* dst_local,
+                               float* score, hipStream_t st) {
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&match_stream_bf16_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLds);
+    if (e != hipSuccess) return e;
+    n_cu = v > 0 ? v : 256;
+  }
+  const int n_chunks = seq / kStreamChunk;
+  const int64_t total = (int64_t)n_bh * n_chunks;
+  if (total > (1 << 30)) return hipErrorInvalidValue;
+  const int grid = (int)(total < n_cu ? total : n_cu);
+  ScopedTimer t("match_bf16", st);
+  hipLaunchKernelGGL(match_stream_bf16_kernel, dim3(grid), dim3(kStreamThreads), kStreamLds, st,
+                     static_cast<const __bf16*>(K), kv, seq, n_chunks, (int)total, dst_local, score);
+  return hipGetLastError();
+}
+
 template <int D>
 hipError_t launch_match_bf16(const void* K, TensorView kv, int n_bh, int seq, int chunk,
                              int32_t* dst_local, float* score, hipStream_t st) {
@@ -347,6 +651,8 @@ hipError_t launch_match_bf16(const void* K, TensorView kv, int n_bh, int seq, in
 hipError_t launch_match(const void* K, int dtype, int dim, TensorView kv, int n_bh, int seq,
                         int chunk, int32_t* dst_local, float* score, hipStream_t st) {
   if (dtype == CKV_BF16) {
+    if (dim == 128 && chunk == kStreamChunk && seq % kStreamChunk == 0 && seq > 0 && kv.stride_s <= (1 << 22))
+      return launch_match_stream(K, kv, n_bh, seq, dst_local, score, st);
     if (dim == 128) return launch_match_bf16<128>(K, kv, n_bh, seq, chunk, dst_local, score, st);
     if (dim == 64) return launch_match_bf16<64>(K, kv, n_bh, seq, chunk, dst_local, score, st);
     return hipErrorInvalidValue;
