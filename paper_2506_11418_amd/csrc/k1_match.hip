@@ -421,10 +421,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
       if constexpr (S + 2 < KSTEPS) bq[S + 2] = *reinterpret_cast<const bf16x8*>(pb + boff[S + 2]);
       n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[S], afrag[0][S], S == 0 ? f32x16{0} : n0, 0, 0, 0);
       if constexpr (FOLD) fold_steps<2 * S * SPS, (2 * S + 1) * SPS>(c0, c1, ib, f, jlane, best, bestj);
-      __builtin_amdgcn_sched_barrier(0);
       n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[S], afrag[1][S], S == 0 ? f32x16{0} : n1, 0, 0, 0);
       if constexpr (FOLD) fold_steps<(2 * S + 1) * SPS, (2 * S + 2) * SPS>(c0, c1, ib, f, jlane, best, bestj);
-      __builtin_amdgcn_sched_barrier(0);
     };
     static_for(kstep, std::make_integer_sequence<int, KSTEPS>{});
     // pin the fold to this stage (its results are otherwise free to sink into a later block)
