@@ -7,9 +7,12 @@ launch per kernel per round) followed by one decode step of attention over the c
 (one ckv_decode_attn call per layer, as a model would issue them).
 
 Prints ONE JSON line.  `value` = context tokens pushed through the whole step per second.
-`roofline` describes the kernel with the largest share of GPU time (per-kernel times come from
-HIP events the library records on the launch stream during the timed steps); `kernels` lists the
-same figures for every hot kernel.  `cpu_baseline` is the numpy oracle timed on a bounded sample.
+`roofline` describes the kernel with the largest share of GPU time; its launch durations come from
+HIP events the library records on the launch stream during the timed steps.  Only that kernel is
+bracketed there: events around every launch slow the 32 short attention layers of a step by about
+a quarter.  `kernels` lists the same figures for every hot kernel; the other kernels' come from a
+few untimed profile steps (each entry says which).  `cpu_baseline` is the numpy oracle timed on a
+bounded sample.
 """
 from __future__ import annotations
 
@@ -185,8 +188,62 @@ def main():
     for i in range(args.warmup):
         step(i, False)
     torch.cuda.synchronize()
+
+    def kernel_table(ktimes, n_steps):
+        """Per-kernel time, achieved rate and roofline fraction from the library's launch events."""
+        work = algorithmic_work(cfg, plan, fused="fused2_bf16" in ktimes, deferred="merge_keys_bf16" in ktimes)
+        kernels = {}
+        for name, (tot_ms, launches) in ktimes.items():
+            per_step_ms = tot_ms / n_steps
+            ent = {"ms_per_step": round(per_step_ms, 4), "launches_per_step": launches / n_steps,
+                   "avg_launch_us": round(tot_ms * 1e3 / max(launches, 1), 2)}
+            if name == "match_bf16":
+                ach = work[name] / (per_step_ms * 1e-3) / 1e12
+                ent.update(bound="mfma", achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                           frac=round(ach / PEAK_BF16_TFLOPS, 4))
+            elif name in work and work[name] > 0:
+                ach = work[name] / (per_step_ms * 1e-3) / 1e9
+                ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                           frac=round(ach / PEAK_HBM_GBS, 4))
+                if name == "fused2_bf16":   # its similarity contractions, as a second reading
+                    tf = work["_fused2_flops"] / (per_step_ms * 1e-3) / 1e12
+                    ent.update(mfma_TFLOPs=round(tf, 1), mfma_frac=round(tf / PEAK_BF16_TFLOPS, 4))
+            kernels[name] = ent
+        if args.stage == "match" and "match_bf16" in kernels:      # ckv_match runs the first round only
+            one = algorithmic_work(cfg, type(plan)(plan.round_len[1], plan.round_len[:2], plan.round_r[:1], 0), False)
+            ach = one["match_bf16"] / (kernels["match_bf16"]["ms_per_step"] * 1e-3) / 1e12
+            kernels["match_bf16"].update(achieved=round(ach, 1), frac=round(ach / PEAK_BF16_TFLOPS, 4))
+        return kernels, work
+
+    def group_of(k):
+        # launches of one kernel function are taken together: the merge kernel's modes (full, keys-only,
+        # origin: one template, named apart in the timing only) count as one kernel
+        return "merge_kernel (all modes)" if k.startswith("merge_") else k
+
+    # ---- profile pass (untimed): every kernel bracketed by events -> the per-kernel table and the
+    # dominant kernel.  Bracketing every launch costs the 32 short attention layers about a quarter of
+    # their speed, so the timed region below brackets the dominant kernel only.
+    n_profile = 3
+    ckv.timing_select(None)
     ckv.timing_reset()
     ckv.timing_enable(True)
+    for i in range(n_profile):
+        step(i, False)
+    torch.cuda.synchronize()
+    ckv.timing_enable(False)
+    kernels, work = kernel_table(ckv.timing_read(), n_profile)
+    groups = {}
+    for k in kernels:
+        if k in work and "bound" in kernels[k]:
+            groups.setdefault(group_of(k), []).append(k)
+    dom = max(groups, key=lambda gname: sum(kernels[k]["ms_per_step"] for k in groups[gname])) if groups else None
+
+    # ---- timed region ---------------------------------------------------------------------------
+    if dom is not None:
+        ckv.timing_select("merge_" if dom.startswith("merge_kernel") else dom)
+    ckv.timing_reset()
+    ckv.timing_enable(dom is not None)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i, True)
@@ -194,47 +251,24 @@ def main():
     t1 = time.perf_counter()
     ckv.timing_enable(False)
     ktimes = ckv.timing_read()
+    ckv.timing_select(None)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     comp_ms = float(np.mean([ev[3 * i].elapsed_time(ev[3 * i + 1]) for i in range(args.steps)]))
     dec_ms = float(np.mean([ev[3 * i + 1].elapsed_time(ev[3 * i + 2]) for i in range(args.steps)]))
 
-    # ---- per-kernel roofline figures ------------------------------------------------------------
-    work = algorithmic_work(cfg, plan, fused="fused2_bf16" in ktimes, deferred="merge_keys_bf16" in ktimes)
-    kernels = {}
-    for name, (tot_ms, launches) in ktimes.items():
-        per_step_ms = tot_ms / args.steps
-        ent = {"ms_per_step": round(per_step_ms, 4), "launches_per_step": launches / args.steps,
-               "avg_launch_us": round(tot_ms * 1e3 / max(launches, 1), 2)}
-        if name == "match_bf16":
-            ach = work[name] / (per_step_ms * 1e-3) / 1e12
-            ent.update(bound="mfma", achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                       frac=round(ach / PEAK_BF16_TFLOPS, 4))
-        elif name in work and work[name] > 0:
-            ach = work[name] / (per_step_ms * 1e-3) / 1e9
-            ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                       frac=round(ach / PEAK_HBM_GBS, 4))
-            if name == "fused2_bf16":   # its similarity contractions, as a second reading
-                tf = work["_fused2_flops"] / (per_step_ms * 1e-3) / 1e12
-                ent.update(mfma_TFLOPs=round(tf, 1), mfma_frac=round(tf / PEAK_BF16_TFLOPS, 4))
-        kernels[name] = ent
-    if args.stage == "match":      # ckv_match runs the first round only
-        one = algorithmic_work(cfg, type(plan)(plan.round_len[1], plan.round_len[:2], plan.round_r[:1], 0), False)
-        ach = one["match_bf16"] / (kernels["match_bf16"]["ms_per_step"] * 1e-3) / 1e12
-        kernels["match_bf16"].update(achieved=round(ach, 1), frac=round(ach / PEAK_BF16_TFLOPS, 4))
-    # The dominant KERNEL: launches of one kernel function are taken together, so the merge kernel's modes
-    # (full, keys-only, origin: one template, named apart in the timing only) count as one kernel.
-    groups = {}
-    for k in kernels:
-        if k in work and "bound" in kernels[k]:
-            groups.setdefault("merge_kernel (all modes)" if k.startswith("merge_") else k, []).append(k)
+    # ---- roofline of the dominant kernel, from the events of the timed steps ---------------------
     roofline = None
-    if groups:
-        dom = max(groups, key=lambda gname: sum(kernels[k]["ms_per_step"] for k in groups[gname]))
-        members = groups[dom]
-        t_ms = sum(kernels[k]["ms_per_step"] for k in members)
-        n_launch = sum(kernels[k]["launches_per_step"] for k in members)
-        first = kernels[members[0]]
+    if dom is not None:
+        timed, _ = kernel_table(ktimes, args.steps)
+        members = [k for k in groups[dom] if k in timed]
+        for k in members:
+            kernels[k] = dict(timed[k], measured="timed steps")
+        for k in kernels:
+            kernels[k].setdefault("measured", f"{n_profile} untimed profile steps")
+        t_ms = sum(timed[k]["ms_per_step"] for k in members)
+        n_launch = sum(timed[k]["launches_per_step"] for k in members)
+        first = timed[members[0]]
         scale = 1e12 if first["bound"] == "mfma" else 1e9
         ach = sum(work[k] for k in members) / (t_ms * 1e-3) / scale
         traffic = [MEASURED_TRAFFIC.get((args.workload, k)) for k in members]
@@ -242,7 +276,7 @@ def main():
                     "unit": first["unit"], "frac": round(ach / first["peak"], 4),
                     "avg_launch_us": round(t_ms * 1e3 / n_launch, 2),
                     "traffic": None if any(t is None for t in traffic) else int(
-                        sum(t * kernels[k]["launches_per_step"] for t, k in zip(traffic, members)) / n_launch)}
+                        sum(t * timed[k]["launches_per_step"] for t, k in zip(traffic, members)) / n_launch)}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample ---------------------------
     cpu = None

@@ -222,7 +222,10 @@ int ckv_paged_compress(void* K_pool, void* V_pool, int32_t* deg_pool, int32_t* b
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Per-kernel timing for benchmarks.  When enabled, every kernel launch of the calling process
- * is bracketed by HIP events on its stream (a few microseconds of host overhead per launch).
+ * is bracketed by HIP events on its stream (a few microseconds per launch, on the host and on the
+ * GPU: 32 attention layers lose about a quarter of their speed to it).  ckv_timing_select narrows
+ * that to the kernels whose timing name starts with `prefix` (NULL or "" = all again), so a
+ * benchmark can time its dominant kernel inside the measured region and leave the rest alone.
  * ckv_timing_read synchronises with the recorded events, then fills up to `max` entries with the
  * accumulated time per kernel since the last reset and returns the number of kernels (or a
  * negative status).  Not thread-safe; meant for a single benchmarking thread. */
@@ -232,6 +235,7 @@ typedef struct {
   int64_t launches;
 } ckv_kernel_time;
 int ckv_timing_enable(int on);
+int ckv_timing_select(const char* prefix);
 int ckv_timing_reset(void);
 int ckv_timing_read(ckv_kernel_time* out, int max);
 

@@ -88,6 +88,7 @@ def lib() -> C.CDLL:
                                               C.POINTER(C.c_size_t)]
         L.ckv_paged_compress.argtypes = [vp, vp, vp, vp, vp, PL, i32, C.POINTER(Params), vp, vp, C.c_size_t, vp]
         L.ckv_timing_enable.argtypes = [C.c_int]
+        L.ckv_timing_select.argtypes = [C.c_char_p]
         L.ckv_timing_read.argtypes = [C.POINTER(KernelTime), C.c_int]
         _lib = L
     return _lib
@@ -373,6 +374,11 @@ def timing_enable(on: bool) -> None:
 
 def timing_reset() -> None:
     lib().ckv_timing_reset()
+
+
+def timing_select(prefix: Optional[str]) -> None:
+    """Time only kernels whose timing name starts with `prefix` (None: all)."""
+    lib().ckv_timing_select(prefix.encode() if prefix else None)
 
 
 def timing_read() -> dict:

@@ -147,6 +147,7 @@ struct TimedLaunch {
   hipEvent_t a, b;
 };
 bool g_timing = false;
+std::string g_timing_prefix;          // empty: every kernel; else only names that start with it
 std::vector<TimedLaunch> g_launches;
 std::vector<std::pair<std::string, std::pair<double, int64_t>>> g_totals;
 
@@ -168,16 +169,22 @@ void fold_launches() {
 
 }  // namespace
 
-void timing_begin(const char* name, hipStream_t st) {
-  if (!g_timing) return;
+bool timing_begin(const char* name, hipStream_t st) {
+  if (!g_timing) return false;
+  if (!g_timing_prefix.empty() && strncmp(name, g_timing_prefix.c_str(), g_timing_prefix.size()) != 0) return false;
   TimedLaunch t{name, nullptr, nullptr};
-  if (hipEventCreate(&t.a) != hipSuccess || hipEventCreate(&t.b) != hipSuccess) return;
+  if (hipEventCreate(&t.a) != hipSuccess) return false;
+  if (hipEventCreate(&t.b) != hipSuccess) {
+    (void)hipEventDestroy(t.a);
+    return false;
+  }
   (void)hipEventRecord(t.a, st);
   g_launches.push_back(t);
+  return true;
 }
 
 void timing_end(hipStream_t st) {
-  if (!g_timing || g_launches.empty()) return;
+  if (g_launches.empty()) return;
   (void)hipEventRecord(g_launches.back().b, st);
 }
 
@@ -621,6 +628,11 @@ int ckv_paged_compress(void* K_pool, void* V_pool, int32_t* deg_pool, int32_t* b
 int ckv_timing_enable(int on) {
   if (!on) fold_launches();
   g_timing = on != 0;
+  return CKV_OK;
+}
+
+int ckv_timing_select(const char* prefix) {
+  g_timing_prefix = prefix ? prefix : "";
   return CKV_OK;
 }
 

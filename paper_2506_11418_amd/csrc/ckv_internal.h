@@ -140,12 +140,13 @@ hipError_t launch_paged_scatter(const void* K, const void* V, const int32_t* deg
                                 int keep_blocks, int old_blocks, int32_t* freed, int32_t* lens, hipStream_t st);
 
 // ---- timing hooks ----------------------------------------------------------------------------
-void timing_begin(const char* name, hipStream_t st);
+bool timing_begin(const char* name, hipStream_t st);   // false: this launch is not being timed
 void timing_end(hipStream_t st);
 struct ScopedTimer {
   hipStream_t st;
-  ScopedTimer(const char* name, hipStream_t s) : st(s) { timing_begin(name, s); }
-  ~ScopedTimer() { timing_end(st); }
+  bool on;
+  ScopedTimer(const char* name, hipStream_t s) : st(s), on(timing_begin(name, s)) {}
+  ~ScopedTimer() { if (on) timing_end(st); }
 };
 
 }  // namespace ckv
