@@ -92,69 +92,62 @@ __device__ __forceinline__ void tile_argmax(const f32x16& acc, const f32x4 (&ib)
 }
 
 
-// The same fold as straight-line code cut into 16 steps of about 8 vector instructions (two
+// The same fold as straight-line code cut into 16 steps of at most 8 vector instructions (two
 // tiles of the same 32 B rows at once), so that a caller can place one step behind each MFMA of
 // the NEXT tile.  Only valid when tiles arrive in INCREASING order of B index: a strict
 // comparison then keeps the lowest index among equal maxima.  jlane = first B row of the tile
 // + 4 * lane half; accumulator r is B row 8*(r/4) + r%4 past it.  The scaled scores overwrite
-// the accumulators.  Comparisons are taken one step before the selects that use them, so no
-// select has to wait for its lane mask.
+// the accumulators' registers.
+// The maximum is taken as a running maximum over the four quads of accumulators, q[k] = max of
+// accumulators 0 .. 4k+3.  The lowest quad with q[k] == q[3] holds the first maximum: its four
+// scores are picked with nested selects and searched, 25 instructions instead of the 31 of a
+// compare + select per accumulator.  Steps 11..15 are empty.
 struct FoldRegs {
-  float mt[2];
-  int idx[2];
-  bool eq[4];
+  float s[2][16];      // scaled scores (held apart from the accumulator vectors: a select between two
+                       // elements of ONE vector would be turned into a run-time element index)
+  float q[2][4];       // running quad maxima; q[.][3] is the tile's maximum
+  float x[2][4];       // the scores of the lowest quad that holds it
+  int base[2];         // that quad's first B row, then the B row of the maximum
 };
 constexpr int kFoldSteps = 16;
+template <int STEP, int T>   // the part of step STEP that belongs to tile T (accumulators v)
+__device__ __forceinline__ void fold_step_tile(const f32x16& v, const f32x4 (&ib)[4], FoldRegs& f, int jlane,
+                                               float& best, int& bestj) {
+  float(&s)[16] = f.s[T];
+  float(&q)[4] = f.q[T];
+  float(&x)[4] = f.x[T];
+  if constexpr (STEP < 4) {                       // scale by 1/|k_j|
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s[4 * STEP + i] = v[4 * STEP + i] * ib[STEP][i];
+  } else if constexpr (STEP == 4) {               // running quad maxima
+    q[0] = __builtin_fmaxf(__builtin_fmaxf(__builtin_fmaxf(s[0], s[1]), s[2]), s[3]);
+    q[1] = __builtin_fmaxf(__builtin_fmaxf(__builtin_fmaxf(q[0], s[4]), s[5]), __builtin_fmaxf(s[6], s[7]));
+  } else if constexpr (STEP == 5) {
+    q[2] = __builtin_fmaxf(__builtin_fmaxf(__builtin_fmaxf(q[1], s[8]), s[9]), __builtin_fmaxf(s[10], s[11]));
+    q[3] = __builtin_fmaxf(__builtin_fmaxf(__builtin_fmaxf(q[2], s[12]), s[13]), __builtin_fmaxf(s[14], s[15]));
+  } else if constexpr (STEP >= 6 && STEP <= 8) {  // the scores and first row of the lowest quad that
+    constexpr int K = 8 - STEP;                   // has reached the maximum: quad 2 against 3, then 1, 0
+    const bool in = q[K] == q[3];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = in ? s[4 * K + i] : (K == 2 ? s[12 + i] : x[i]);
+    f.base[T] = in ? 8 * K : (K == 2 ? 24 : f.base[T]);
+  } else if constexpr (STEP == 9) {               // the first of its scores that is the maximum
+    int i = (x[2] == q[3]) ? 2 : 3;
+    i = (x[1] == q[3]) ? 1 : i;
+    i = (x[0] == q[3]) ? 0 : i;
+    f.base[T] += i;
+  } else if constexpr (STEP == 10) {              // into the running maxima
+    const bool upd = q[3] > best;
+    best = upd ? q[3] : best;
+    bestj = upd ? jlane + f.base[T] : bestj;
+  }
+}
+
 template <int STEP>
 __device__ __forceinline__ void fold_step(f32x16& c0, f32x16& c1, const f32x4 (&ib)[4], FoldRegs& f, int jlane,
                                           float (&best)[2], int (&bestj)[2]) {
-  if constexpr (STEP < 4) {                       // scale by 1/|k_j|
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      c0[4 * STEP + q] *= ib[STEP][q];
-      c1[4 * STEP + q] *= ib[STEP][q];
-    }
-  } else if constexpr (STEP == 4) {               // maximum of the 16 scores, first half
-    f.mt[0] = __builtin_fmaxf(c0[0], c0[1]);
-    f.mt[1] = __builtin_fmaxf(c1[0], c1[1]);
-#pragma unroll
-    for (int r = 2; r < 8; r += 2) {
-      f.mt[0] = __builtin_fmaxf(__builtin_fmaxf(f.mt[0], c0[r]), c0[r + 1]);
-      f.mt[1] = __builtin_fmaxf(__builtin_fmaxf(f.mt[1], c1[r]), c1[r + 1]);
-    }
-  } else if constexpr (STEP == 5) {               // second half
-#pragma unroll
-    for (int r = 8; r < 16; r += 2) {
-      f.mt[0] = __builtin_fmaxf(__builtin_fmaxf(f.mt[0], c0[r]), c0[r + 1]);
-      f.mt[1] = __builtin_fmaxf(__builtin_fmaxf(f.mt[1], c1[r]), c1[r + 1]);
-    }
-  } else if constexpr (STEP < 15) {               // lowest accumulator that holds the maximum:
-    constexpr int KSET = STEP - 6;                // selects of pair KSET-1, comparisons of pair KSET
-    if constexpr (KSET == 0) { f.idx[0] = 27; f.idx[1] = 27; }
-    if constexpr (KSET >= 1) {
-      constexpr int R1 = 15 - 2 * (KSET - 1), R0 = R1 - 1;
-      if constexpr (R1 != 15) {
-        f.idx[0] = f.eq[0] ? (8 * (R1 >> 2) + (R1 & 3)) : f.idx[0];
-        f.idx[1] = f.eq[1] ? (8 * (R1 >> 2) + (R1 & 3)) : f.idx[1];
-      }
-      f.idx[0] = f.eq[2] ? (8 * (R0 >> 2) + (R0 & 3)) : f.idx[0];
-      f.idx[1] = f.eq[3] ? (8 * (R0 >> 2) + (R0 & 3)) : f.idx[1];
-    }
-    if constexpr (KSET <= 7) {
-      constexpr int R1 = 15 - 2 * KSET, R0 = R1 - 1;
-      f.eq[0] = c0[R1] == f.mt[0];
-      f.eq[1] = c1[R1] == f.mt[1];
-      f.eq[2] = c0[R0] == f.mt[0];
-      f.eq[3] = c1[R0] == f.mt[1];
-    }
-  } else if constexpr (STEP == 15) {              // into the running maxima
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const bool upd = f.mt[t] > best[t];
-      best[t] = upd ? f.mt[t] : best[t];
-      bestj[t] = upd ? jlane + f.idx[t] : bestj[t];
-    }
-  }
+  fold_step_tile<STEP, 0>(c0, ib, f, jlane, best[0], bestj[0]);
+  fold_step_tile<STEP, 1>(c1, ib, f, jlane, best[1], bestj[1]);
 }
 
 template <int FIRST, int LAST>   // steps FIRST .. LAST-1

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
     // A stage issues the MFMAs of one tile and, one slice of vector work behind each of them,
     // folds the PREVIOUS tile's accumulators into the running maxima: matrix pipe and vector
     // ALU of the wave work side by side instead of taking turns.  B fragments are read from
-    // LDS two k-steps ahead; the fences keep the compiler from regrouping the slices.
+    // LDS two k-steps ahead.
     const int jl = 4 * half;
     auto load_ib = [&](auto row_c, f32x4 (&ib)[4]) {
 #pragma unroll
@@ -219,12 +219,12 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
         if constexpr (S + 2 < KSTEPS) bq[S + 2] = *reinterpret_cast<const bf16x8*>(pb + boff[S + 2]);
         n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[S], afrag[0][S], S == 0 ? f32x16{0} : n0, 0, 0, 0);
         if constexpr (FOLD) fold_steps<2 * S * SPS, (2 * S + 1) * SPS>(c0, c1, ib, f, jlane, best, bestj);
-        __builtin_amdgcn_sched_barrier(0);
         n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[S], afrag[1][S], S == 0 ? f32x16{0} : n1, 0, 0, 0);
         if constexpr (FOLD) fold_steps<(2 * S + 1) * SPS, (2 * S + 2) * SPS>(c0, c1, ib, f, jlane, best, bestj);
-        __builtin_amdgcn_sched_barrier(0);
       };
       static_for(kstep, std::make_integer_sequence<int, KSTEPS>{});
+      // pin the fold to this stage (its results are otherwise free to sink into a later block)
+      if constexpr (FOLD) asm volatile("" : "+v"(best[0]), "+v"(best[1]), "+v"(bestj[0]), "+v"(bestj[1]));
       load_ib(row_c, ib_next);       // norms of the tile just multiplied, for its fold one stage on
     };
     f32x16 xa0, xa1, xb0, xb1;
