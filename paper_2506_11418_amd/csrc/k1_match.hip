@@ -296,26 +296,33 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
   }
 }
 
-// ---- persistent streaming kernel: bf16, dim 128, whole chunks of 1024 tokens -------------------
-// One workgroup per CU walks a contiguous range of (sequence, chunk) items.  While an item is
+// ---- persistent streaming kernel: bf16, dim 128, whole chunks of 1024 or 2048 tokens -----------
+// One workgroup per CU walks a contiguous range of items: (sequence, chunk, block of 512 A rows),
+// one block per 1024-token chunk, two per 2048-token chunk (each against all of the chunk's B
+// rows: TILES = 16 or 32 B tiles per item).  While an item is
 // matched, the NEXT item's A rows arrive in a 128 KiB LDS area (one 32-row pass per stage) and the
 // B rows stream through a ring of three 32-row tiles (one tile per stage, loaded four stages
-// ahead into registers, normed on the way into LDS); the two row streams are just the even and
-// odd tokens of the same contiguous walk through memory.  At an item boundary the A operands are
+// ahead into registers, normed on the way into LDS); at 1024 tokens the two row streams are just
+// the even and odd tokens of one contiguous walk through memory.  At an item boundary the A operands are
 // re-read from LDS, so no global-memory latency is exposed between items.  Every stage folds
 // tile q while the MFMAs of tile q+1 run (see the pipelined loop of match_bf16_kernel).
-constexpr int kStreamChunk = 1024;
+constexpr int kStreamBlock = 512;       // A rows per item
 constexpr int kStreamThreads = 512;
 constexpr int kStreamTile = 32;
 constexpr int kStreamSlots = 3;
-constexpr size_t kStreamLds = (size_t)(kStreamChunk / 2) * 256 + kStreamSlots * kStreamTile * 256 +
+constexpr size_t kStreamLds = (size_t)kStreamBlock * 256 + kStreamSlots * kStreamTile * 256 +
                               kStreamSlots * kStreamTile * sizeof(float);
 
+template <int TILES>
 __global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
     const __bf16* __restrict__ K, TensorView kv, int seq, int n_chunks, int total_items,
     int32_t* __restrict__ dst_local, float* __restrict__ score) {
-  constexpr int ROWB = 256, KSTEPS = 8, HALF = kStreamChunk / 2, TILES = HALF / kStreamTile;
+  constexpr int ROWB = 256, KSTEPS = 8, HALF = kStreamBlock, APASSES = HALF / kStreamTile;
+  constexpr int CHUNK = 2 * TILES * kStreamTile;   // tokens per chunk
+  constexpr int AB = TILES / APASSES;              // A blocks (items) per chunk
+  constexpr int NA = 4 / AB;                       // A passes in flight (one is handed over every AB stages)
   constexpr int TILEB = kStreamTile * ROWB;
+  static_assert(TILES == 16 || TILES == 32, "chunks of 1024 or 2048 tokens");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* abuf = smem;                                    // A rows of the next item
   unsigned char* ring = smem + HALF * ROWB;                      // kStreamSlots B tiles
@@ -328,17 +335,28 @@ __global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
   const int first = (int)((int64_t)blockIdx.x * total_items / gridDim.x);
   const int last = (int)((int64_t)(blockIdx.x + 1) * total_items / gridDim.x);
   if (first >= last) return;
-  const int n_src = n_sources(seq, kStreamChunk);
+  const int n_src = n_sources(seq, CHUNK);
   const int64_t pass_pitch = 2 * kStreamTile * kv.stride_s;      // 32 A rows (or B rows) further on
 
   // Addresses = a workgroup-uniform pass pointer + this thread's fixed offset inside a pass (row
-  // r0, its 16-byte piece), so the walks below cost scalar instructions only.  item_ptr: A row 0 of
-  // an item (clamped to the range); the B row of a pair sits one token later.
+  // r0, its 16-byte piece), so the walks below cost scalar instructions only.  a_ptr / b_ptr: A row
+  // 0 of an item's block / B row 0 of its chunk (item clamped to the range).
   const uint32_t toff = (uint32_t)(2 * r0 * kv.stride_s + piece * 8) * 2u;   // bytes
-  auto item_ptr = [&](int item) -> const __bf16* {
+  auto chunk_ptr = [&](int item, int& ab) -> const __bf16* {
     item = min(item, last - 1);
-    const int bh = item / n_chunks, g = item - bh * n_chunks;
-    return K + kv.seq_base(bh) + (int64_t)g * kStreamChunk * kv.stride_s;
+    const int cg = item / AB;
+    ab = item - cg * AB;
+    const int bh = cg / n_chunks, g = cg - bh * n_chunks;
+    return K + kv.seq_base(bh) + (int64_t)g * CHUNK * kv.stride_s;
+  };
+  auto a_ptr = [&](int item) -> const __bf16* {
+    int ab;
+    const __bf16* c = chunk_ptr(item, ab);
+    return c + (int64_t)ab * 2 * HALF * kv.stride_s;
+  };
+  auto b_ptr = [&](int item) -> const __bf16* {
+    int ab;
+    return chunk_ptr(item, ab) + kv.stride_s;
   };
   auto ld = [&](const __bf16* pass) {
     Piece x;
@@ -351,26 +369,26 @@ __global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
     invb[slot * kStreamTile + r0] = inv_norm(ss);
   };
 
-  // ---- prologue: A rows of the first item, B tiles 0 and 1, four passes of each stream in flight
-  Piece sb[4], sa[4];
-  const __bf16 *pB, *pA;                 // next pass each stream loads: B six tiles, A four passes ahead
+  // ---- prologue: A rows of the first item, B tiles 0 and 1, four stages of each stream in flight
+  Piece sb[4], sa[NA];
+  const __bf16 *pB, *pA;                 // next pass each stream loads: B six tiles, A four stages ahead
   {
-    const __bf16* p0 = item_ptr(first);
-    const __bf16* p1 = item_ptr(first + 1);
-    Piece xa[TILES];
+    const __bf16* a0 = a_ptr(first);
+    const __bf16* b0p = b_ptr(first);
+    const __bf16* a1 = a_ptr(first + 1);
+    Piece xa[APASSES];
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) xa[t] = ld(p0 + t * pass_pitch);
-    const Piece b0 = ld(p0 + kv.stride_s);
-    const Piece b1 = ld(p0 + pass_pitch + kv.stride_s);
+    for (int t = 0; t < APASSES; ++t) xa[t] = ld(a0 + t * pass_pitch);
+    const Piece b0 = ld(b0p);
+    const Piece b1 = ld(b0p + pass_pitch);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      sb[u] = ld(p0 + (u + 2) * pass_pitch + kv.stride_s);
-      sa[u] = ld(p1 + u * pass_pitch);
-    }
-    pB = p0 + 6 * pass_pitch + kv.stride_s;
-    pA = p1 + 4 * pass_pitch;
+    for (int u = 0; u < 4; ++u) sb[u] = ld(b0p + (u + 2) * pass_pitch);
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) *reinterpret_cast<uint4*>(abuf + t * TILEB + lds_piece0) = xa[t].u;
+    for (int u = 0; u < NA; ++u) sa[u] = ld(a1 + u * pass_pitch);
+    pB = b0p + 6 * pass_pitch;
+    pA = a1 + NA * pass_pitch;
+#pragma unroll
+    for (int t = 0; t < APASSES; ++t) *reinterpret_cast<uint4*>(abuf + t * TILEB + lds_piece0) = xa[t].u;
     put_b(0, b0);
     put_b(1, b1);
   }
@@ -438,12 +456,11 @@ __global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
   prefetch(0);
   stage(0, 1, std::false_type{}, xa0, xa1, xb0, xb1, ibb, iba, 0);
   int rs = 1, ws = 2;                    // ring slots: tile q+1 is read, tile q+2 written, in stage q
-  int bh = first / n_chunks, g = first - bh * n_chunks;
   for (int item = first; item < last; ++item) {
-    // where the two streams continue once they run off their current item (B during this item's
-    // stage 9, A during stage 11)
-    const __bf16* wrapB = item_ptr(item + 1) + kv.stride_s;
-    const __bf16* wrapA = item_ptr(item + 2);
+    // where the two streams continue once they run off their current item: B after the item's last
+    // tile (loaded six stages ahead), A after the next item's last pass (loaded four stages ahead)
+    const __bf16* wrapB = b_ptr(item + 1);
+    const __bf16* wrapA = a_ptr(item + 2);
     float next_inva[2] = {my_inva[0], my_inva[1]};
     for (int t0 = 0; t0 < TILES; t0 += 4) {
       // stage t: hand over the passes loaded four stages ago, refill their registers (no branch:
@@ -452,11 +469,13 @@ __global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
         constexpr int U = decltype(u_c)::value;
         const int t = t0 + U;
         put_b(ws, sb[U]);
-        *reinterpret_cast<uint4*>(abuf + t * TILEB + lds_piece0) = sa[U].u;
         sb[U] = ld(pB);
         pB = (t == TILES - 7) ? wrapB : pB + pass_pitch;
-        sa[U] = ld(pA);
-        pA = (t == TILES - 5) ? wrapA : pA + pass_pitch;
+        if constexpr (U % AB == 0) {     // an A pass of the next item every AB stages
+          *reinterpret_cast<uint4*>(abuf + (t / AB) * TILEB + lds_piece0) = sa[U / AB].u;
+          sa[U / AB] = ld(pA);
+          pA = (t == (APASSES - 1 - NA) * AB) ? wrapA : pA + pass_pitch;
+        }
         __syncthreads();
       };
       auto turn = [&] {
@@ -482,7 +501,9 @@ __global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
       turn();
     }
     // the item's last tile is folded: write its matches
-    const int64_t out_base = (int64_t)bh * n_src + (int64_t)g * HALF;
+    const int cg = item / AB, ab = item - cg * AB;
+    const int bh = cg / n_chunks, g = cg - bh * n_chunks;
+    const int64_t out_base = (int64_t)bh * n_src + (int64_t)g * (CHUNK / 2) + ab * HALF;
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
       const float ob = __shfl_xor(best[rt], 32);
@@ -499,7 +520,6 @@ __global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
       bestj[rt] = 0;
       my_inva[rt] = next_inva[rt];
     }
-    if (++g == n_chunks) { g = 0; ++bh; }
   }
 }
 
@@ -613,7 +633,8 @@ hipError_t launch_match_bf16_nw(const void* K, TensorView kv, int n_bh, int seq,
   return hipGetLastError();
 }
 
-// Whole 1024-token chunks of 128-dim keys: the persistent kernel, one workgroup per CU.
+// Whole 1024- or 2048-token chunks of 128-dim keys: the persistent kernel, one workgroup per CU.
+template <int TILES>
 hipError_t launch_match_stream(const void* K, TensorView kv, int n_bh, int seq, int32_t* dst_local,
                                float* score, hipStream_t st) {
   static int n_cu = 0;
@@ -622,17 +643,18 @@ hipError_t launch_match_stream(const void* K, TensorView kv, int n_bh, int seq, 
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&match_stream_bf16_kernel),
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&match_stream_bf16_kernel<TILES>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLds);
     if (e != hipSuccess) return e;
     n_cu = v > 0 ? v : 256;
   }
-  const int n_chunks = seq / kStreamChunk;
-  const int64_t total = (int64_t)n_bh * n_chunks;
+  constexpr int CHUNK = 2 * TILES * kStreamTile;
+  const int n_chunks = seq / CHUNK;
+  const int64_t total = (int64_t)n_bh * n_chunks * (TILES / 16);
   if (total > (1 << 30)) return hipErrorInvalidValue;
   const int grid = (int)(total < n_cu ? total : n_cu);
   ScopedTimer t("match_bf16", st);
-  hipLaunchKernelGGL(match_stream_bf16_kernel, dim3(grid), dim3(kStreamThreads), kStreamLds, st,
+  hipLaunchKernelGGL(match_stream_bf16_kernel<TILES>, dim3(grid), dim3(kStreamThreads), kStreamLds, st,
                      static_cast<const __bf16*>(K), kv, seq, n_chunks, (int)total, dst_local, score);
   return hipGetLastError();
 }
@@ -649,8 +671,9 @@ hipError_t launch_match_bf16(const void* K, TensorView kv, int n_bh, int seq, in
 hipError_t launch_match(const void* K, int dtype, int dim, TensorView kv, int n_bh, int seq,
                         int chunk, int32_t* dst_local, float* score, hipStream_t st) {
   if (dtype == CKV_BF16) {
-    if (dim == 128 && chunk == kStreamChunk && seq % kStreamChunk == 0 && seq > 0 && kv.stride_s <= (1 << 22))
-      return launch_match_stream(K, kv, n_bh, seq, dst_local, score, st);
+    if (dim == 128 && (chunk == 1024 || chunk == 2048) && seq % chunk == 0 && seq > 0 && kv.stride_s <= (1 << 22))
+      return chunk == 1024 ? launch_match_stream<16>(K, kv, n_bh, seq, dst_local, score, st)
+                           : launch_match_stream<32>(K, kv, n_bh, seq, dst_local, score, st);
     if (dim == 128) return launch_match_bf16<128>(K, kv, n_bh, seq, chunk, dst_local, score, st);
     if (dim == 64) return launch_match_bf16<64>(K, kv, n_bh, seq, chunk, dst_local, score, st);
     return hipErrorInvalidValue;

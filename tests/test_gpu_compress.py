@@ -92,15 +92,18 @@ def test_match_bf16_shapes(heads, seq, dim, chunk):
         check_match(f64(K[0, h]), chunk, i64(dst[0, h]), f64(score[0, h]), f"h{h}")
 
 
-# ---- the persistent kernel for whole 1024-token chunks of 128-dim bf16 keys -----------------------
-@pytest.mark.parametrize("batch,heads,seq,layout", [
-    (1, 5, 1024, "bhsd"),        # one chunk per sequence: every item starts a new sequence
-    (1, 3, 7168, "bhsd"),        # 21 items, one per workgroup
-    (2, 3, 5120, "bshd"),        # token-major storage: row stride heads*dim, separate batch stride
-    (2, 5, 33792, "bhsd"),       # 330 items on 256 workgroups: ranges of one and of two items
+# ---- the persistent kernel for whole 1024- or 2048-token chunks of 128-dim bf16 keys --------------
+@pytest.mark.parametrize("batch,heads,seq,layout,chunk", [
+    (1, 5, 1024, "bhsd", 1024),        # one chunk per sequence: every item starts a new sequence
+    (1, 3, 7168, "bhsd", 1024),        # 21 items, one per workgroup
+    (2, 3, 5120, "bshd", 1024),        # token-major storage: row stride heads*dim, separate batch stride
+    (2, 5, 33792, "bhsd", 1024),       # 330 items on 256 workgroups: ranges of one and of two items
+    (1, 3, 2048, "bhsd", 2048),        # two A blocks per chunk, one chunk per sequence
+    (2, 2, 10240, "bshd", 2048),       # 40 items; token-major storage
+    (1, 7, 40960, "bhsd", 2048),       # 280 items on 256 workgroups: a chunk's two blocks on different workgroups
 ])
-def test_match_streaming_kernel_bf16(batch, heads, seq, layout):
-    _say(f"match streaming B={batch} H={heads} S={seq} {layout}")
+def test_match_streaming_kernel_bf16(batch, heads, seq, layout, chunk):
+    _say(f"match streaming B={batch} H={heads} S={seq} {layout} c={chunk}")
     Ks = [kv_host(31 + b, heads, seq, 128, "bf16", alpha=0.9, n_outlier=4)[0] for b in range(batch)]
     K = torch.cat(Ks, dim=0)                                   # [B, H, S, D]
     if seq == 1024:
@@ -111,32 +114,34 @@ def test_match_streaming_kernel_bf16(batch, heads, seq, layout):
         assert not K.is_contiguous()
     else:
         K = K.to(DEV)
-    dst, score = ckv.match(K, 1024)
+    dst, score = ckv.match(K, chunk)
     torch.cuda.synchronize()
     for b in range(batch):
         for h in range(heads):
-            check_match(f64(K[b, h]), 1024, i64(dst[b, h]), f64(score[b, h]), f"b{b}h{h}")
+            check_match(f64(K[b, h]), chunk, i64(dst[b, h]), f64(score[b, h]), f"b{b}h{h}")
 
 
-def test_match_streaming_kernel_takes_the_lowest_index_among_equal_maxima():
+@pytest.mark.parametrize("chunk", [1024, 2048])
+def test_match_streaming_kernel_takes_the_lowest_index_among_equal_maxima(chunk):
     """Exactly equal scores in different tiles, lane halves and accumulators: lowest B index wins."""
-    _say("match streaming ties")
+    _say(f"match streaming ties c={chunk}")
     rng = np.random.default_rng(77)
-    K = torch.from_numpy(rng.standard_normal((1, 2, 3072, 128)).astype(np.float32)).to(torch.bfloat16)
-    K[0, 1, 1024:2048] = K[0, 1, 1024]                         # a chunk of identical keys
+    K = torch.from_numpy(rng.standard_normal((1, 2, 4096, 128)).astype(np.float32)).to(torch.bfloat16)
+    K[0, 1, 2048:4096] = K[0, 1, 2048]                         # identical keys: every source takes B row 0
     picks = [(0, 10, (37, 411)), (0, 300, (5, 4)), (0, 511, (480, 31)), (2048, 64, (96, 100)), (2048, 7, (3, 259))]
     for g0, a, (j1, j2) in picks:                               # two copies of an A key among the B keys
         K[0, 0, g0 + 2 * j1 + 1] = K[0, 0, g0 + 2 * a]
         K[0, 0, g0 + 2 * j2 + 1] = K[0, 0, g0 + 2 * a]
     K = K.to(DEV)
-    dst, score = ckv.match(K, 1024)
+    dst, score = ckv.match(K, chunk)
     torch.cuda.synchronize()
     d0, d1 = i64(dst[0, 0]), i64(dst[0, 1])
     for g0, a, (j1, j2) in picks:
         assert d0[g0 // 2 + a] == g0 + 2 * min(j1, j2) + 1, (g0, a, j1, j2, d0[g0 // 2 + a])
-    assert np.all(d1[512:1024] == 1024 + 1)
+    for g0 in range(2048, 4096, chunk):
+        assert np.all(d1[g0 // 2:(g0 + chunk) // 2] == g0 + 1)
     for h in range(2):
-        check_match(f64(K[0, h]), 1024, i64(dst[0, h]), f64(score[0, h]), f"ties h{h}")
+        check_match(f64(K[0, h]), chunk, i64(dst[0, h]), f64(score[0, h]), f"ties h{h}")
 
 
 @pytest.mark.parametrize("heads,seq,dim,chunk,rounds", [
