@@ -160,7 +160,7 @@ __device__ __forceinline__ void fold_steps(f32x16& c0, f32x16& c1, const f32x4 (
 }
 
 // acc[0..8)/n as 8 packed bf16, ONE nearest-even rounding (n < 2^21).
-// q = acc * (1/n) with a correctly rounded reciprocal lies within 3 ulp(fp32) of the true quotient
+// q = acc * (1/n) with a reciprocal good to an ulp lies within 3 ulp(fp32) of the true quotient
 // t.  For n a power of two q = t.  Otherwise the converter's rounding of q can differ from that of
 // t only if q sits within those 3 ulp of a bf16 midpoint M (low 16 bits in 0x7ffd..0x8003), and not
 // even then if q*n == acc exactly (sums of bf16 values divide evenly quite often; q = t then).
@@ -181,16 +181,20 @@ __device__ __forceinline__ uint32_t round_bf16_near_midpoint(float S, float fn, 
 
 __device__ __forceinline__ uint4 round_div_pack_bf16(const float* acc, int n) {
   const float fn = (float)n;
-  const float rcp = 1.0f / fn;   // correctly rounded: quotients that divide evenly then come out exact
+  // 1/n: hardware reciprocal (1 ulp) + one Newton step.  Exact for powers of two; otherwise within
+  // an ulp of 1/n, which keeps q within the 3 ulp the window below allows for (checked on the CPU
+  // against exact rational arithmetic with the reciprocal forced one ulp off either way).
+  float rcp = __builtin_amdgcn_rcpf(fn);
+  rcp = fmaf(fmaf(-fn, rcp, 1.0f), rcp, rcp);
   const bool pow2 = (n & (n - 1)) == 0;          // then acc*rcp IS the quotient: no second rounding
   float qv[8];
-  bool window = false;
+  uint32_t nearest = 0xffffffffu;                // min over the elements of (low 16 bits - 0x7ffd) mod 2^16
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     qv[i] = acc[i] * rcp;
-    window |= ((__float_as_uint(qv[i]) & 0xffffu) - 0x7ffdu) <= 6u;
+    nearest = min(nearest, (uint32_t)(uint16_t)(__float_as_uint(qv[i]) - 0x7ffdu));
   }
-  window &= !pow2;
+  const bool window = (nearest <= 6u) & !pow2;
   uint32_t w[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
