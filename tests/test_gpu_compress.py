@@ -587,3 +587,31 @@ def test_deferred_values_with_strided_input_and_padded_output():
     torch.cuda.synchronize()
     assert torch.equal(oK[:, :, :out_len], ref[0]) and torch.equal(oV[:, :, :out_len], ref[1])
     assert torch.equal(odeg[:, :, :out_len], ref[2]) and not bool(oV[:, :, out_len:].any())
+
+
+def test_timing_hooks_can_be_narrowed_to_one_kernel():
+    """ckv_timing_select: only launches whose timing name starts with the prefix are bracketed."""
+    _say("timing select")
+    K, V, _ = kv_host(5, 2, 4096, 128, "bf16", alpha=0.9, n_outlier=4)
+    K, V = K.to(DEV), V.to(DEV)
+    try:
+        ckv.timing_select("merge")
+        ckv.timing_reset()
+        ckv.timing_enable(True)
+        ckv.compress(K, V, 1024, retain_ratio=0.25)
+        torch.cuda.synchronize()
+        ckv.timing_enable(False)
+        names = ckv.timing_read()
+        assert names and all(n.startswith("merge") for n in names), names
+        ckv.timing_select(None)
+        ckv.timing_reset()
+        ckv.timing_enable(True)
+        ckv.compress(K, V, 1024, retain_ratio=0.25)
+        torch.cuda.synchronize()
+        ckv.timing_enable(False)
+        names = ckv.timing_read()
+        assert "match_bf16" in names and any(n.startswith("merge") for n in names), names
+    finally:
+        ckv.timing_select(None)
+        ckv.timing_enable(False)
+        ckv.timing_reset()
