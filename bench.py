@@ -422,6 +422,27 @@ def main():
         serving["paged_compress_16x8x32768_ms"] = round(times["paged"], 3)
         serving["strided_compress_16x8x32768_ms"] = round(times["strided"], 3)
         del K_pool, V_pool, deg_pool, sK, sV, s_out, pws, sws
+        # What this part's memory system gives a plain read + write stream: the library's row-copy kernel
+        # (ckv_compress with no round to run) over the whole input cache, timed the same way.  The merge
+        # kernels move the same kind of traffic and are to be read against this, not only against 8 TB/s.
+        if Ly * H * S * D * 2 >= (1 << 32):
+            Kc, Vc = torch.empty_like(sets[0][0]), torch.empty_like(sets[0][1])
+            degc = torch.empty((Ly, H, S), dtype=torch.int32, device=dev)
+            for _ in range(2):
+                ckv.compress(sets[0][0], sets[0][1], cfg["chunk"], retain_ratio=1.0, out=(Kc, Vc, degc, assign), workspace=ws)
+            torch.cuda.synchronize()
+            ckv.timing_reset()
+            ckv.timing_enable(True)
+            for _ in range(5):
+                ckv.compress(sets[0][0], sets[0][1], cfg["chunk"], retain_ratio=1.0, out=(Kc, Vc, degc, assign), workspace=ws)
+            torch.cuda.synchronize()
+            ckv.timing_enable(False)
+            tc = ckv.timing_read()
+            cp_us = tc["copy_rows"][0] / tc["copy_rows"][1] * 1e3
+            cp_bytes = 2 * Ly * H * S * D * 2          # one launch copies K (or V): read + written
+            serving["plain_copy_kernel"] = {"GBps": round(cp_bytes / cp_us / 1e3, 1), "us": round(cp_us, 1),
+                                            "what": "the library's row-copy kernel, one launch = 8 GiB read + 8 GiB written"}
+            del Kc, Vc, degc
 
     dec_bytes = work["attn_partial_bf16"]
     out = {

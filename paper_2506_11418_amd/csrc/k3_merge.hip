@@ -18,7 +18,7 @@ namespace ckv {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxHalf = 1024;  // max |A| = |B| (chunk <= 2048)
+constexpr int kMaxHalf = 1024;  // max |A| = |B| (chunk <= 2048); chunks up to 1024 tokens take half the LDS
 
 __device__ inline int block_exclusive_scan(int v, int* s_wave_tot, int* total) {
   // 256 threads = 4 waves
@@ -93,7 +93,7 @@ constexpr int kRowsInFlightOrigin = 2;   // ... when every value row is itself r
 //                 rounding the first round would have used, so the results are bit-identical.
 enum { kMergeFull = 0, kMergeKeys = 1, kMergeOrigin = 2 };
 
-template <typename T, int D, int MODE>
+template <typename T, int D, int MODE, int MH>   // MH: capacity of the per-chunk LDS arrays (|A| = |B| <= MH)
 __global__ __launch_bounds__(kThreads) void merge_kernel(
     const T* __restrict__ K, const T* __restrict__ V, const int32_t* __restrict__ deg_in, TensorView in,
     int seq, int chunk, int n_chunks, float r, const int32_t* __restrict__ dst_local,
@@ -109,14 +109,14 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   typedef typename Row<T>::Raw Raw;
 
   // s_dstk[i]: destination (B index) of source i if its edge is kept, -1 otherwise
-  __shared__ __attribute__((aligned(16))) int16_t s_dstk[kMaxHalf];
-  __shared__ __attribute__((aligned(16))) float s_score[kMaxHalf];
-  __shared__ int32_t s_cnt[kMaxHalf];
-  __shared__ int32_t s_fill[kMaxHalf];
-  __shared__ int16_t s_start[kMaxHalf];
-  __shared__ int16_t s_members[kMaxHalf];
-  __shared__ int16_t s_local_out[2 * kMaxHalf];
-  __shared__ int16_t s_src_of_out[2 * kMaxHalf];
+  __shared__ __attribute__((aligned(16))) int16_t s_dstk[MH];
+  __shared__ __attribute__((aligned(16))) float s_score[MH];
+  __shared__ int32_t s_cnt[MH];
+  __shared__ int32_t s_fill[MH];
+  __shared__ int16_t s_start[MH];
+  __shared__ int16_t s_members[MH];
+  __shared__ int16_t s_local_out[2 * MH];
+  __shared__ int16_t s_src_of_out[2 * MH];
   __shared__ int s_wave_tot[4];
 
   // `parts` workgroups share a chunk when the launch would otherwise leave most of the chip idle:
@@ -152,9 +152,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
   // ---- top-r: rank by counting (score descending, index ascending) ----------------------------
   if (m > 0 && m < nA) {
-    bool drop[kMaxHalf / kThreads];
+    bool drop[MH / kThreads];
 #pragma unroll
-    for (int it = 0; it < kMaxHalf / kThreads; ++it) {
+    for (int it = 0; it < MH / kThreads; ++it) {
       const int i = tid + it * kThreads;
       drop[it] = false;
       if (i < nA) {
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     }
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < kMaxHalf / kThreads; ++it)
+    for (int it = 0; it < MH / kThreads; ++it)
       if (drop[it]) s_dstk[tid + it * kThreads] = -1;
     __syncthreads();
   }
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   // are placed by rank counting instead.
   constexpr int kSortMax = 8;
 #pragma unroll
-  for (int it = 0; it < kMaxHalf / kThreads; ++it) {
+  for (int it = 0; it < MH / kThreads; ++it) {
     const int i = tid + it * kThreads;
     const int d = (i < nA) ? (int)s_dstk[i] : -1;
     if (d >= 0) atomicAdd(&s_cnt[d], 1);
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   }
   const bool any_long = __syncthreads_or(longest > kSortMax);
 #pragma unroll
-  for (int it = 0; it < kMaxHalf / kThreads; ++it) {
+  for (int it = 0; it < MH / kThreads; ++it) {
     const int i = tid + it * kThreads;
     const int d = (i < nA) ? (int)s_dstk[i] : -1;
     if (d >= 0) {
@@ -286,9 +286,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
   // kMergeOrigin: the member lists of the two previous-round chunks that feed this chunk, staged in
   // LDS arrays the bookkeeping above no longer needs (scores, fill counters, local output slots)
-  int16_t (*s0_cnt)[kMaxHalf] = reinterpret_cast<int16_t (*)[kMaxHalf]>(s_score);
-  int16_t (*s0_start)[kMaxHalf] = reinterpret_cast<int16_t (*)[kMaxHalf]>(s_fill);
-  int16_t (*s0_mem)[kMaxHalf] = reinterpret_cast<int16_t (*)[kMaxHalf]>(s_local_out);
+  int16_t (*s0_cnt)[MH] = reinterpret_cast<int16_t (*)[MH]>(s_score);
+  int16_t (*s0_start)[MH] = reinterpret_cast<int16_t (*)[MH]>(s_fill);
+  int16_t (*s0_mem)[MH] = reinterpret_cast<int16_t (*)[MH]>(s_local_out);
   if (MODE == kMergeOrigin) {
     __syncthreads();
 #pragma unroll
@@ -552,12 +552,18 @@ hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, T
   // small launches: split every chunk's rows over several workgroups, aiming at 4 workgroups per CU
   int parts = 1;
   while (parts < 8 && total * parts < 1024) parts *= 2;
-#define CKV_LAUNCH(MODE)                                                                                      \
-  hipLaunchKernelGGL((merge_kernel<T, D, MODE>), dim3((int)(total * parts)), dim3(kThreads), 0, st,          \
+#define CKV_LAUNCH_MH(MODE, MH)                                                                               \
+  hipLaunchKernelGGL((merge_kernel<T, D, MODE, MH>), dim3((int)(total * parts)), dim3(kThreads), 0, st,      \
                      static_cast<const T*>(K), static_cast<const T*>(V), deg_in, in, seq, chunk, n_chunks, r, \
                      dst_local, score, static_cast<T*>(K_out), static_cast<T*>(V_out), deg_out, out,          \
                      deg_out_stride, map_out, deg_in_stride, map_stride, map_offset,                          \
                      reinterpret_cast<const int2*>(sel_table), lists_out, o, parts)
+  // smaller LDS arrays for chunks of up to 1024 tokens: more workgroups per CU
+#define CKV_LAUNCH(MODE)                                       \
+  do {                                                         \
+    if (chunk <= kMaxHalf) CKV_LAUNCH_MH(MODE, kMaxHalf / 2);  \
+    else CKV_LAUNCH_MH(MODE, kMaxHalf);                        \
+  } while (0)
   if (org) {
     ScopedTimer t(sizeof(T) == 2 ? "merge_origin_bf16" : "merge_origin_f32", st);
     CKV_LAUNCH(kMergeOrigin);
