@@ -78,7 +78,7 @@ struct Row<float> {
   __device__ static void store_div(float* p, const Acc* acc, int n) { *reinterpret_cast<float4*>(p) = div_raw(acc, n); }
 };
 
-constexpr int kRowsInFlight = 2;   // output rows a row group works on at once
+constexpr int kRowsInFlight = 1;   // output rows of a row group per batch (two batches are in flight)
 constexpr int kRowsInFlightOrigin = 2;   // ... when every value row is itself rebuilt from several rows
 
 // MODE (two consecutive rounds whose first merges every edge, r = 1, can skip the intermediate
@@ -327,6 +327,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     int db, dm[kEager], n, base;
     const int16_t* mem;
   };
+  struct NoVLoad {};   // keys-only mode carries no value rows
   auto v_issue = [&](int p) -> VLoad {
     VLoad x;
     if (MODE == kMergeFull) {
@@ -375,67 +376,98 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     return Row<T>::div_raw(a, nd);
   };
 
-  auto emit = [&](auto wide_c) {
-  constexpr bool WIDE = decltype(wide_c)::value;
-  for (int ob = part * NRG * U; ob < n_out; ob += parts * NRG * U) {
-    int tok[U], nmem[U], first[U], mem0[U], du[U], dm[U];
+  // One batch = U output rows per row group: where they come from (LDS lookups) and the loads of
+  // their own rows and first merged sources, all issued before anything is consumed.
+  struct Batch {
+    int ob;
+    int tok[U], nmem[U], first[U], du[U], dm[U];
     bool valid[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = ob + u * NRG + rg;
-      valid[u] = o < n_out;
-      tok[u] = s_src_of_out[valid[u] ? o : n_out - 1];
-      const bool isB = tok[u] & 1;
-      nmem[u] = isB ? s_cnt[tok[u] >> 1] : 0;
-      first[u] = isB ? (int)s_start[tok[u] >> 1] : 0;
-      mem0[u] = (nmem[u] > 0) ? 2 * (int)s_members[first[u]] : tok[u];   // no source: re-read own row
-    }
     Raw kb[U], km[U];
-    VLoad vb[U], vm[U];
+    typename std::conditional<MODE == kMergeKeys, NoVLoad, VLoad>::type vb[U], vm[U];
+  };
+  auto fetch = [&](int ob) -> Batch {
+    Batch x;
+    x.ob = ob;
+    int mem0[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      kb[u] = Row<T>::load_raw(Kin + (int64_t)tok[u] * in.stride_s);
-      km[u] = Row<T>::load_raw(Kin + (int64_t)mem0[u] * in.stride_s);
-      if (MODE != kMergeKeys) {
-        vb[u] = v_issue(tok[u]);
-        vm[u] = v_issue(mem0[u]);
-      }
-      du[u] = dseq ? dseq[tok[u]] : 1;
-      dm[u] = dseq ? dseq[mem0[u]] : 1;
+      const int o = ob + u * NRG + rg;
+      x.valid[u] = o < n_out;
+      x.tok[u] = s_src_of_out[x.valid[u] ? o : n_out - 1];
+      const bool isB = x.tok[u] & 1;
+      x.nmem[u] = isB ? s_cnt[x.tok[u] >> 1] : 0;
+      x.first[u] = isB ? (int)s_start[x.tok[u] >> 1] : 0;
+      mem0[u] = (x.nmem[u] > 0) ? 2 * (int)s_members[x.first[u]] : x.tok[u];   // no source: re-read own row
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (!valid[u]) continue;
-      const int o = ob + u * NRG + rg;
-      if (nmem[u] == 0) {  // untouched token: bit copy
-        Row<T>::store_raw(Ko + (int64_t)o * out.stride_s, kb[u]);
-        if (MODE != kMergeKeys) Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, v_finish(wide_c, vb[u]));
-        if (piece == 0) dout[o] = du[u];
+      x.kb[u] = Row<T>::load_raw(Kin + (int64_t)x.tok[u] * in.stride_s);
+      x.km[u] = Row<T>::load_raw(Kin + (int64_t)mem0[u] * in.stride_s);
+      if constexpr (MODE != kMergeKeys) {
+        x.vb[u] = v_issue(x.tok[u]);
+        x.vm[u] = v_issue(mem0[u]);
+      }
+      x.du[u] = dseq ? dseq[x.tok[u]] : 1;
+      x.dm[u] = dseq ? dseq[mem0[u]] : 1;
+    }
+    return x;
+  };
+  auto finish = [&](auto wide_c, const Batch& x) {
+    constexpr bool WIDE = decltype(wide_c)::value;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!x.valid[u]) continue;
+      const int o = x.ob + u * NRG + rg;
+      if (x.nmem[u] == 0) {  // untouched token: bit copy
+        Row<T>::store_raw(Ko + (int64_t)o * out.stride_s, x.kb[u]);
+        if constexpr (MODE != kMergeKeys) Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, v_finish(wide_c, x.vb[u]));
+        if (piece == 0) dout[o] = x.du[u];
         continue;
       }
       Acc ak[E], av[E];
 #pragma unroll
       for (int e = 0; e < E; ++e) { ak[e] = 0; av[e] = 0; }
-      Row<T>::template fma_into<WIDE>(ak, kb[u], du[u]);
-      Row<T>::template fma_into<WIDE>(ak, km[u], dm[u]);
-      if (MODE != kMergeKeys) {
-        Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, vb[u]), du[u]);
-        Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, vm[u]), dm[u]);
+      Row<T>::template fma_into<WIDE>(ak, x.kb[u], x.du[u]);
+      Row<T>::template fma_into<WIDE>(ak, x.km[u], x.dm[u]);
+      if constexpr (MODE != kMergeKeys) {
+        Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, x.vb[u]), x.du[u]);
+        Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, x.vm[u]), x.dm[u]);
       }
-      int ndeg = du[u] + dm[u];
-      for (int q = 1; q < nmem[u]; ++q) {
-        const int ua = 2 * (int)s_members[first[u] + q];
+      int ndeg = x.du[u] + x.dm[u];
+      for (int q = 1; q < x.nmem[u]; ++q) {
+        const int ua = 2 * (int)s_members[x.first[u] + q];
         const int da = dseq ? dseq[ua] : 1;
         const Raw kx = Row<T>::load_raw(Kin + (int64_t)ua * in.stride_s);
         Row<T>::template fma_into<WIDE>(ak, kx, da);
-        if (MODE != kMergeKeys) Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, v_issue(ua)), da);
+        if constexpr (MODE != kMergeKeys) Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, v_issue(ua)), da);
         ndeg += da;
       }
       Row<T>::store_div(Ko + (int64_t)o * out.stride_s, ak, ndeg);
-      if (MODE != kMergeKeys) Row<T>::store_div(Vo + (int64_t)o * out.stride_s, av, ndeg);
+      if constexpr (MODE != kMergeKeys) Row<T>::store_div(Vo + (int64_t)o * out.stride_s, av, ndeg);
       if (piece == 0) dout[o] = ndeg;
     }
-  }
+  };
+  // The loop over batches is software-pipelined (the next batch's loads are in flight while this
+  // one is merged and stored) except in origin mode, whose batches are too large to hold twice.
+  auto emit = [&](auto wide_c) {
+    const int step = parts * NRG * U;
+    int ob = part * NRG * U;
+    if (ob >= n_out) return;
+    if (MODE == kMergeOrigin) {
+      for (; ob < n_out; ob += step) finish(wide_c, fetch(ob));
+      return;
+    }
+    Batch a = fetch(ob);
+    for (;;) {
+      ob += step;
+      if (ob >= n_out) { finish(wide_c, a); break; }
+      Batch b2 = fetch(ob);
+      finish(wide_c, a);
+      ob += step;
+      if (ob >= n_out) { finish(wide_c, b2); break; }
+      a = fetch(ob);
+      finish(wide_c, b2);
+    }
   };
   // Two versions of the emit loop: weights up to 256 ride in a packed bf16 operand (one v_dot2 per
   // element); a chunk that holds a larger degree takes the general route.  Same bits either way.
