@@ -140,6 +140,32 @@ hipError_t launch_paged_scatter(const void* K, const void* V, const int32_t* deg
                                 int keep_blocks, int old_blocks, int32_t* freed, int32_t* lens, hipStream_t st);
 
 // ---- timing hooks ----------------------------------------------------------------------------
+// One-time set-up of a kernel that needs more than the default dynamic LDS, per device (each device
+// holds its own copy of the code object, so the limit is raised on each one that launches it).
+// `state` is the call site's own table; a concurrent first call sets the same values twice.
+constexpr int kMaxDevices = 64;
+struct KernelSetup {
+  bool done[kMaxDevices] = {};
+  int n_cu[kMaxDevices] = {};
+};
+inline hipError_t kernel_setup(const void* kernel, size_t dynamic_lds, KernelSetup& state, int* n_cu = nullptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!state.done[dev]) {
+    int v = 0;
+    e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dynamic_lds);
+    if (e != hipSuccess) return e;
+    state.n_cu[dev] = v > 0 ? v : 256;
+    state.done[dev] = true;
+  }
+  if (n_cu) *n_cu = state.n_cu[dev];
+  return hipSuccess;
+}
+
 bool timing_begin(const char* name, hipStream_t st);   // false: this launch is not being timed
 void timing_end(hipStream_t st);
 struct ScopedTimer {

@@ -614,13 +614,9 @@ hipError_t launch_match_bf16_nw(const void* K, TensorView kv, int n_bh, int seq,
                                 int32_t* dst_local, float* score, hipStream_t st) {
   constexpr int ABLOCK = NW * kRowsPerWave;
   constexpr size_t lds = (size_t)(ABLOCK > 2 * kPanel ? ABLOCK : 2 * kPanel) * D * 2 + 2 * kPanel * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&match_bf16_kernel<D, NW>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static KernelSetup setup;
+  if (hipError_t e = kernel_setup(reinterpret_cast<const void*>(&match_bf16_kernel<D, NW>), lds, setup); e != hipSuccess)
+    return e;
   const int n_chunks = div_up(seq, chunk);
   const int a_blocks = div_up(chunk / 2, ABLOCK);
   const int64_t total = (int64_t)n_bh * n_chunks * a_blocks;
@@ -637,17 +633,11 @@ hipError_t launch_match_bf16_nw(const void* K, TensorView kv, int n_bh, int seq,
 template <int TILES>
 hipError_t launch_match_stream(const void* K, TensorView kv, int n_bh, int seq, int32_t* dst_local,
                                float* score, hipStream_t st) {
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0, v = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&match_stream_bf16_kernel<TILES>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLds);
-    if (e != hipSuccess) return e;
-    n_cu = v > 0 ? v : 256;
-  }
+  static KernelSetup setup;
+  int n_cu = 0;
+  if (hipError_t e = kernel_setup(reinterpret_cast<const void*>(&match_stream_bf16_kernel<TILES>), kStreamLds, setup, &n_cu);
+      e != hipSuccess)
+    return e;
   constexpr int CHUNK = 2 * TILES * kStreamTile;
   const int n_chunks = seq / CHUNK;
   const int64_t total = (int64_t)n_bh * n_chunks * (TILES / 16);

@@ -510,13 +510,8 @@ bool fused2_supported(int dtype, int dim, int chunk, int seq, float r0) {
 hipError_t launch_fused2(const void* K, const void* V, const int32_t* deg_in, TensorView in, int n_bh, int seq,
                          float r1, void* K_out, void* V_out, int32_t* deg_out, TensorView out,
                          int64_t deg_out_stride, int32_t* map_out, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused2_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static KernelSetup setup;
+  if (hipError_t e = kernel_setup(reinterpret_cast<const void*>(&fused2_kernel), kLdsBytes, setup); e != hipSuccess) return e;
   const int n_super = seq / (2 * kC);
   const int64_t total = (int64_t)n_bh * n_super;
   // rows of a super-chunk are addressed with 32-bit byte offsets
