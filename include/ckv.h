@@ -15,7 +15,10 @@
  *   - buffers passed through const pointers are never written; outputs and workspace must not
  *     overlap inputs (CKV_EINVAL where the host can tell); ckv_append and the ckv_paged_* calls
  *     update the cache they are given in place, as stated with each of them;
- *   - base pointers and row strides (in bytes) of K/V tensors are multiples of 16 (CKV_EALIGN).
+ *   - base pointers and row strides (in bytes) of K/V tensors are multiples of 16 (CKV_EALIGN);
+ *   - the library keeps no state between calls apart from the timing hooks at the end of this file
+ *     (a single benchmarking thread) and a per-device note of which kernels have been set up:
+ *     calls from several threads, each on its own stream and buffers, do not disturb one another.
  *
  * Tensor layout ("layout"): element (b, h, t, :) of a [batch, heads, seq, dim] tensor lives at
  * base + b*stride_b + h*stride_h + t*stride_s (strides in ELEMENTS); dim is contiguous.  This
