@@ -4,15 +4,18 @@
 // For every A token i:  j*(i) = argmax_j  k_i.k_j / (|k_i||k_j|)  (lowest j on ties) and that
 // maximum.  The |A| x |B| similarity matrix lives only in MFMA accumulators.
 //
-// bf16 kernel: one workgroup = (sequence, chunk, block of A rows), 64 A rows per wave; 8 waves
-// (512 A rows: a whole 1024-token chunk) for chunks above 512 tokens, 4 waves otherwise.  The
-// A rows are staged once through LDS into registers in MFMA operand order; the chunk's B rows
-// stream through two LDS panels of 128 rows (global -> registers -> LDS, one barrier per panel).
-// Inverse norms come from the same bytes (v_dot2 on the packed pairs): the B rows' while they
-// are staged, the A rows' from the operand registers.  The MFMA computes
-// S^T (B index on the M side) so that a lane's 16 accumulators of a 32x32 tile all belong to ONE
-// A row: the running maximum costs one multiply (by 1/|k_j|) and half a max3 per element, and the
-// exact index is only resolved for tiles that raise some lane's maximum.
+// Two bf16 kernels.  Common to both: 64 A rows per wave held as MFMA operands in registers; the
+// MFMA computes S^T (B index on the M side) so that a lane's 16 accumulators of a 32x32 tile all
+// belong to ONE A row (no cross-lane step until the very end); inverse norms come from the same
+// bytes (v_dot2 on the packed pairs): the B rows' while they are staged into LDS, the A rows'
+// from the operand registers.
+//   match_bf16_kernel: one workgroup = (sequence, chunk, block of A rows); 8 waves (512 A rows) for
+// chunks above 512 tokens, 4 waves otherwise.  The A rows are staged once through LDS; the chunk's
+// B rows stream through two LDS panels of 128 rows (global -> registers -> LDS, one barrier per
+// panel).  Blocks made of full tiles fold tile q into the running maxima while the MFMAs of tile
+// q+1 run; ragged blocks take the maximum first and resolve the index only for tiles that raise
+// some lane's maximum.
+//   match_stream_bf16_kernel (dim 128, whole chunks of 1024 or 2048 tokens): persistent, see below.
 #include <type_traits>
 #include <utility>
 
@@ -303,8 +306,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
 // matched, the NEXT item's A rows arrive in a 128 KiB LDS area (one 32-row pass per stage) and the
 // B rows stream through a ring of three 32-row tiles (one tile per stage, loaded four stages
 // ahead into registers, normed on the way into LDS); at 1024 tokens the two row streams are just
-// the even and odd tokens of one contiguous walk through memory.  At an item boundary the A operands are
-// re-read from LDS, so no global-memory latency is exposed between items.  Every stage folds
+// the even and odd tokens of one contiguous walk through memory.  At an item boundary the A
+// operands are re-read from LDS, so no global-memory latency is exposed between items.  Every stage folds
 // tile q while the MFMAs of tile q+1 run (see the pipelined loop of match_bf16_kernel).
 constexpr int kStreamBlock = 512;       // A rows per item
 constexpr int kStreamThreads = 512;
