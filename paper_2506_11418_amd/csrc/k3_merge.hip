@@ -118,6 +118,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   __shared__ int16_t s_local_out[2 * MH];
   __shared__ int16_t s_src_of_out[2 * MH];
   __shared__ int s_wave_tot[4];
+  // kMergeOrigin, chunks up to 1024 tokens: per output row, everything the emit loop would look up
+  // through the lists, resolved once (three 8-byte words: the row's own sources, then where the
+  // value rows of its own token and of its first merged source come from)
+  constexpr bool DESC = (MODE == kMergeOrigin) && (MH <= 512);
+  __shared__ uint2 s_desc[DESC ? 3 * 2 * MH : 1];
 
   // `parts` workgroups share a chunk when the launch would otherwise leave most of the chip idle:
   // each repeats the (cheap) bookkeeping and emits every parts-th group of output rows.
@@ -304,6 +309,29 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       }
     }
     __syncthreads();
+    if constexpr (DESC) {
+      // token indices are kept relative to the first token of previous-round chunk 2g
+      auto value_words = [&](int p) -> uint2 {
+        const int h = (p >= half) ? 1 : 0, jj = p - h * half;
+        const bool single = (org.seq0 - (2 * g + h) * chunk) == 1;
+        const int tb = h * chunk + (single ? 0 : 2 * jj + 1);
+        const int n = single ? 0 : (int)s0_cnt[h][jj];
+        const int off = h * MH + (int)s0_start[h][jj];
+        const int ta = (n > 0) ? h * chunk + 2 * (int)(&s0_mem[0][0])[off] : tb;
+        return make_uint2((uint32_t)tb | ((uint32_t)ta << 16), (uint32_t)n | ((uint32_t)off << 16));
+      };
+      for (int o = tid; o < n_out; o += kThreads) {
+        const int tok = s_src_of_out[o];
+        const bool isB = tok & 1;
+        const int nmem = isB ? s_cnt[tok >> 1] : 0;
+        const int first = isB ? (int)s_start[tok >> 1] : 0;
+        const int mem0 = (nmem > 0) ? 2 * (int)s_members[first] : tok;
+        s_desc[3 * o] = make_uint2((uint32_t)tok | ((uint32_t)mem0 << 16), (uint32_t)nmem | ((uint32_t)first << 16));
+        s_desc[3 * o + 1] = value_words(tok);
+        s_desc[3 * o + 2] = value_words(mem0);
+      }
+      __syncthreads();
+    }
   }
 
   // ---- emit rows: every row group works on U output rows at once; the loads of their own rows
@@ -353,6 +381,25 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     }
     return x;
   };
+  auto v_issue_resolved = [&](uint2 w) -> VLoad {
+    VLoad x;
+    if constexpr (MODE == kMergeOrigin) {
+      const int t0 = 2 * g * chunk;
+      const int tb_rel = (int)(w.x & 0xffffu);
+      const int tb = t0 + tb_rel, ta = t0 + (int)(w.x >> 16);
+      x.base = t0 + ((tb_rel >= chunk) ? chunk : 0);
+      x.n = (int)(w.y & 0xffffu);
+      x.mem = &s0_mem[0][0] + (w.y >> 16);
+      x.b = Row<T>::load_raw(V0p + (int64_t)tb * org.view0.stride_s);
+      x.db = d0p ? d0p[tb] : 1;
+      static_assert(kEager == 1, "one resolved member per cluster");
+      if (x.n > 0) {
+        x.m[0] = Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s);
+        x.dm[0] = d0p ? d0p[ta] : 1;
+      }
+    }
+    return x;
+  };
   auto v_finish = [&](auto wide_c, const VLoad& x) -> Raw {
     constexpr bool WIDE = decltype(wide_c)::value;
     if (MODE != kMergeOrigin || x.n == 0) return x.b;
@@ -385,33 +432,62 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     Raw kb[U], km[U];
     typename std::conditional<MODE == kMergeKeys, NoVLoad, VLoad>::type vb[U], vm[U];
   };
-  auto fetch = [&](int ob) -> Batch {
-    Batch x;
-    x.ob = ob;
-    int mem0[U];
+  struct Where {
+    int ob;
+    int tok[U], mem0[U], nmem[U], first[U];
+    bool valid[U];
+    uint2 wb[U], wm[U];
+  };
+  auto lookup = [&](int ob) -> Where {
+    Where w;
+    w.ob = ob;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int o = ob + u * NRG + rg;
-      x.valid[u] = o < n_out;
-      x.tok[u] = s_src_of_out[x.valid[u] ? o : n_out - 1];
-      const bool isB = x.tok[u] & 1;
-      x.nmem[u] = isB ? s_cnt[x.tok[u] >> 1] : 0;
-      x.first[u] = isB ? (int)s_start[x.tok[u] >> 1] : 0;
-      mem0[u] = (x.nmem[u] > 0) ? 2 * (int)s_members[x.first[u]] : x.tok[u];   // no source: re-read own row
+      w.valid[u] = o < n_out;
+      const int oo = w.valid[u] ? o : n_out - 1;
+      if constexpr (DESC) {
+        const uint2 k = s_desc[3 * oo];
+        w.wb[u] = s_desc[3 * oo + 1];
+        w.wm[u] = s_desc[3 * oo + 2];
+        w.tok[u] = (int)(k.x & 0xffffu);
+        w.mem0[u] = (int)(k.x >> 16);
+        w.nmem[u] = (int)(k.y & 0xffffu);
+        w.first[u] = (int)(k.y >> 16);
+      } else {
+        w.tok[u] = s_src_of_out[oo];
+        const bool isB = w.tok[u] & 1;
+        w.nmem[u] = isB ? s_cnt[w.tok[u] >> 1] : 0;
+        w.first[u] = isB ? (int)s_start[w.tok[u] >> 1] : 0;
+        w.mem0[u] = (w.nmem[u] > 0) ? 2 * (int)s_members[w.first[u]] : w.tok[u];   // no source: re-read own row
+      }
     }
+    return w;
+  };
+  auto issue = [&](const Where& w) -> Batch {
+    Batch x;
+    x.ob = w.ob;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      x.kb[u] = Row<T>::load_raw(Kin + (int64_t)x.tok[u] * in.stride_s);
-      x.km[u] = Row<T>::load_raw(Kin + (int64_t)mem0[u] * in.stride_s);
-      if constexpr (MODE != kMergeKeys) {
-        x.vb[u] = v_issue(x.tok[u]);
-        x.vm[u] = v_issue(mem0[u]);
+      x.valid[u] = w.valid[u];
+      x.tok[u] = w.tok[u];
+      x.nmem[u] = w.nmem[u];
+      x.first[u] = w.first[u];
+      x.kb[u] = Row<T>::load_raw(Kin + (int64_t)w.tok[u] * in.stride_s);
+      x.km[u] = Row<T>::load_raw(Kin + (int64_t)w.mem0[u] * in.stride_s);
+      if constexpr (DESC) {
+        x.vb[u] = v_issue_resolved(w.wb[u]);
+        x.vm[u] = v_issue_resolved(w.wm[u]);
+      } else if constexpr (MODE != kMergeKeys) {
+        x.vb[u] = v_issue(w.tok[u]);
+        x.vm[u] = v_issue(w.mem0[u]);
       }
-      x.du[u] = dseq ? dseq[x.tok[u]] : 1;
-      x.dm[u] = dseq ? dseq[mem0[u]] : 1;
+      x.du[u] = dseq ? dseq[w.tok[u]] : 1;
+      x.dm[u] = dseq ? dseq[w.mem0[u]] : 1;
     }
     return x;
   };
+  auto fetch = [&](int ob) -> Batch { return issue(lookup(ob)); };
   auto finish = [&](auto wide_c, const Batch& x) {
     constexpr bool WIDE = decltype(wide_c)::value;
 #pragma unroll
@@ -447,6 +523,95 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       if (piece == 0) dout[o] = ndeg;
     }
   };
+  // kMergeOrigin: the same sums in the same order as v_finish, for several clusters in lock step.
+  // A row group that walks one cluster after the other waits a full memory latency per extra member
+  // while the rest of its wave idles; here the q-th extra member of every cluster handed in is
+  // requested at once, so the wave waits as often as the longest of them has members, not the sum.
+  // Called per output row with its two clusters (own token, first merged source): handing in all
+  // four of a batch measured the same and needs 15 more registers.
+  auto v_finish_all = [&](auto wide_c, auto count_c, const VLoad* cl, const bool* on, Raw* res) {
+    constexpr bool WIDE = decltype(wide_c)::value;
+    constexpr int C = decltype(count_c)::value;
+    Acc a[C][E];
+    int nd[C], n[C], longest = 0;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+      n[c] = on[c] ? cl[c].n : 0;
+      nd[c] = 0;
+#pragma unroll
+      for (int e = 0; e < E; ++e) a[c][e] = 0;
+      if (n[c] > 0) {
+        Row<T>::template fma_into<WIDE>(a[c], cl[c].b, cl[c].db);
+        Row<T>::template fma_into<WIDE>(a[c], cl[c].m[0], cl[c].dm[0]);
+        nd[c] = cl[c].db + cl[c].dm[0];
+      }
+      longest = max(longest, n[c]);
+    }
+    for (int q = kEager; q < longest; ++q) {
+      Raw r[C];
+      int d[C];
+#pragma unroll
+      for (int c = 0; c < C; ++c)
+        if (q < n[c]) {
+          const int ta = cl[c].base + 2 * (int)cl[c].mem[q];
+          r[c] = Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s);
+          d[c] = d0p ? d0p[ta] : 1;
+        }
+#pragma unroll
+      for (int c = 0; c < C; ++c)
+        if (q < n[c]) {
+          Row<T>::template fma_into<WIDE>(a[c], r[c], d[c]);
+          nd[c] += d[c];
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+      if (on[c]) res[c] = (n[c] == 0) ? cl[c].b : Row<T>::div_raw(a[c], nd[c]);
+  };
+  auto finish_origin = [&](auto wide_c, const Batch& x) {
+    constexpr bool WIDE = decltype(wide_c)::value;
+    if constexpr (MODE == kMergeOrigin) {
+      bool on[2 * U];
+      Raw vr[2 * U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const VLoad cl[2] = {x.vb[u], x.vm[u]};
+        on[2 * u] = x.valid[u];
+        on[2 * u + 1] = x.valid[u] && x.nmem[u] > 0;
+        v_finish_all(wide_c, std::integral_constant<int, 2>{}, cl, on + 2 * u, vr + 2 * u);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (!x.valid[u]) continue;
+        const int o = x.ob + u * NRG + rg;
+        if (x.nmem[u] == 0) {  // untouched token: bit copy of the key; its value row is one cluster
+          Row<T>::store_raw(Ko + (int64_t)o * out.stride_s, x.kb[u]);
+          Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, vr[2 * u]);
+          if (piece == 0) dout[o] = x.du[u];
+          continue;
+        }
+        Acc ak[E], av[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) { ak[e] = 0; av[e] = 0; }
+        Row<T>::template fma_into<WIDE>(ak, x.kb[u], x.du[u]);
+        Row<T>::template fma_into<WIDE>(ak, x.km[u], x.dm[u]);
+        Row<T>::template fma_into<WIDE>(av, vr[2 * u], x.du[u]);
+        Row<T>::template fma_into<WIDE>(av, vr[2 * u + 1], x.dm[u]);
+        int ndeg = x.du[u] + x.dm[u];
+        for (int q = 1; q < x.nmem[u]; ++q) {
+          const int ua = 2 * (int)s_members[x.first[u] + q];
+          const int da = dseq ? dseq[ua] : 1;
+          const Raw kx = Row<T>::load_raw(Kin + (int64_t)ua * in.stride_s);
+          Row<T>::template fma_into<WIDE>(ak, kx, da);
+          Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, v_issue(ua)), da);
+          ndeg += da;
+        }
+        Row<T>::store_div(Ko + (int64_t)o * out.stride_s, ak, ndeg);
+        Row<T>::store_div(Vo + (int64_t)o * out.stride_s, av, ndeg);
+        if (piece == 0) dout[o] = ndeg;
+      }
+    }
+  };
   // The loop over batches is software-pipelined (the next batch's loads are in flight while this
   // one is merged and stored) except in origin mode, whose batches are too large to hold twice.
   auto emit = [&](auto wide_c) {
@@ -454,7 +619,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     int ob = part * NRG * U;
     if (ob >= n_out) return;
     if (MODE == kMergeOrigin) {
-      for (; ob < n_out; ob += step) finish(wide_c, fetch(ob));
+      for (; ob < n_out; ob += step) finish_origin(wide_c, fetch(ob));
       return;
     }
     Batch a = fetch(ob);
