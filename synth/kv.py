@@ -69,6 +69,22 @@ def kv_host(seed: int, heads: int, s: int, d: int, dtype: str, alpha: float = 0.
     return to_storage(K, dtype), to_storage(V, dtype), rng
 
 
+def prototype_kv_host(seed: int, heads: int, s: int, d: int, dtype: str, n_proto: int, noise: float = 0.02):
+    """K, V as torch CPU tensors [1, heads, s, d]: every key is one of n_proto random directions
+    (drawn per head) plus a little noise, so that many tokens pick the same partner and clusters
+    grow long.  Draw order per head: the directions (n_proto, d), the choice per token (s), the
+    key noise (s, d), the values (s, d)."""
+    K = np.empty((1, heads, s, d))
+    V = np.empty((1, heads, s, d))
+    for h in range(heads):
+        g = np.random.Generator(np.random.PCG64(head_seed(seed, 0, h)))
+        proto = g.standard_normal((n_proto, d))
+        pick = g.integers(0, n_proto, s)
+        K[0, h] = proto[pick] + noise * g.standard_normal((s, d))
+        V[0, h] = g.standard_normal((s, d))
+    return to_storage(K, dtype), to_storage(V, dtype)
+
+
 def query_host(rng_or_seed, batch: int, q_heads: int, d: int, dtype: str) -> torch.Tensor:
     """[batch, q_heads, d] i.i.d. N(0,1) queries in the storage dtype."""
     g = rng_or_seed if isinstance(rng_or_seed, np.random.Generator) else \

@@ -589,6 +589,46 @@ def test_deferred_values_with_strided_input_and_padded_output():
     assert torch.equal(odeg[:, :, :out_len], ref[2]) and not bool(oV[:, :, out_len:].any())
 
 
+@pytest.mark.parametrize("dtype,seq,dim,chunk,n_proto,rounds", [
+    ("bf16", 4096, 128, 1024, 6, [1.0, 1.0]),
+    ("bf16", 4096 + 300, 128, 1024, 40, [1.0, 0.8]),
+    ("bf16", 8192, 64, 2048, 12, [1.0, 1.0]),       # chunk 2048: the origin-mode route without resolved lookups
+    ("f32", 2048, 64, 256, 5, [1.0, 1.0, 1.0, 1.0]),
+])
+def test_deferred_values_with_long_clusters(dtype, seq, dim, chunk, n_proto, rounds):
+    """Keys from a handful of directions: tens of tokens join one centroid in the first round and
+    several such centroids merge in the second, so the origin-mode rebuild walks long member lists
+    at both levels.  Same bits as the full rounds, which are also checked against the oracle."""
+    import os
+    from synth.kv import prototype_kv_host
+    _say(f"deferred values, long clusters {dtype} S={seq} D={dim} c={chunk} directions={n_proto} rounds={rounds}")
+    K, V = prototype_kv_host(61, 2, seq, dim, dtype, n_proto)
+    K, V = K.to(DEV), V.to(DEV)
+    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"
+    try:
+        got = ckv.compress(K, V, chunk, rounds=rounds)
+    finally:
+        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
+    os.environ["CKV_DISABLE_DEFERRED_VALUES"] = "1"
+    try:
+        ref = ckv.compress(K, V, chunk, rounds=rounds)
+    finally:
+        del os.environ["CKV_DISABLE_DEFERRED_VALUES"]
+    torch.cuda.synchronize()
+    for n, a, b in zip(["K'", "V'", "deg'", "assign"], got, ref):
+        assert torch.equal(a, b), f"{n} differs between deferred and full rounds"
+    assert int(got[2].max()) >= 24                      # the long lists really occurred
+    # the degrees are consistent with the assignment map, and the centroid values are the plain
+    # degree-weighted means of the ORIGINAL values (one rounding per round: loose tolerance)
+    gas, gdeg = i64(got[3][0, 0]), i64(got[2][0, 0])
+    assert np.array_equal(np.bincount(gas, minlength=gdeg.size), gdeg)
+    mean = np.zeros((gdeg.size, dim))
+    np.add.at(mean, gas, f64(V[0, 0]))
+    mean /= gdeg[:, None]
+    tol = 2e-2 if dtype == "bf16" else 1e-5
+    assert np.allclose(f64(got[1][0, 0]), mean, atol=tol, rtol=tol)
+
+
 def test_timing_hooks_can_be_narrowed_to_one_kernel():
     """ckv_timing_select: only launches whose timing name starts with the prefix are bracketed."""
     _say("timing select")
