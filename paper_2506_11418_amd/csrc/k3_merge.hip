@@ -652,12 +652,25 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   else emit(std::false_type{});
 }
 
+// assign[bh][t] <- map[bh][assign[bh][t]]: four consecutive tokens per thread (one 16-byte access when
+// the rows allow it), one workgroup per piece of 1024 tokens of one sequence
 __global__ void compose_kernel(int32_t* __restrict__ assign, const int32_t* __restrict__ map, int seq0,
-                               int map_len, int64_t total) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= total) return;
-  const int64_t bh = e / seq0;
-  assign[e] = map[bh * map_len + assign[e]];
+                               int map_len, int pieces, int vec) {
+  const int bh = blockIdx.x / pieces, pc = blockIdx.x % pieces;
+  int32_t* a = assign + (int64_t)bh * seq0;
+  const int32_t* m = map + (int64_t)bh * map_len;
+  const int t = (pc * (int)blockDim.x + (int)threadIdx.x) * 4;
+  if (t >= seq0) return;
+  if (vec && t + 4 <= seq0) {
+    int4 v = *reinterpret_cast<const int4*>(a + t);
+    v.x = m[v.x];
+    v.y = m[v.y];
+    v.z = m[v.z];
+    v.w = m[v.w];
+    *reinterpret_cast<int4*>(a + t) = v;
+  } else {
+    for (int i = t; i < min(t + 4, seq0); ++i) a[i] = m[a[i]];
+  }
 }
 
 __global__ void copy_rows_kernel(const unsigned char* __restrict__ src, TensorView in,
@@ -802,10 +815,13 @@ hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int
 
 hipError_t launch_compose(int32_t* assign, const int32_t* map, int n_bh, int seq0, int map_len,
                           hipStream_t st) {
-  const int64_t total = (int64_t)n_bh * seq0;
+  if (n_bh <= 0 || seq0 <= 0) return hipSuccess;
+  const int vec = (seq0 % 4 == 0) && (reinterpret_cast<uintptr_t>(assign) % 16 == 0);
   ScopedTimer t("compose_assign", st);
-  hipLaunchKernelGGL(compose_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, assign, map,
-                     seq0, map_len, total);
+  const int pieces = (seq0 + 1023) / 1024;
+  if ((int64_t)n_bh * pieces > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(compose_kernel, dim3((unsigned)(n_bh * pieces)), dim3(256), 0, st, assign, map, seq0,
+                     map_len, pieces, vec);
   return hipGetLastError();
 }
 
