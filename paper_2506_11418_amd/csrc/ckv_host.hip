@@ -305,12 +305,18 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
   for (int j = 0; j < plan.n_rounds; ++j) {
     const int len = plan.round_len[j];
     // rounds j and j+1 in one pass when the first merges every edge and the shape has a kernel
-    const bool fuse = allow_fused && j + 1 < plan.n_rounds &&
+    // (both two-round routes skip one staging buffer, so from the second round on their result would
+    // land in the buffer their input sits in unless it goes to the caller's output: see defer_ok)
+    const bool fuse = allow_fused && j + 1 < plan.n_rounds && (j == 0 || j + 2 == plan.n_rounds) &&
                       p->n_sink == 0 && p->n_recent == 0 && curView.deg_stride == len &&
                       p->scope == CKV_SCOPE_CHUNK &&
                       fused2_supported(in->dtype, in->dim, p->chunk, len, plan.round_r[j]) &&
                       curView.stride_s <= (1 << 18) && out->stride_s <= (1 << 18);
+    // From the second round on the pair must end the schedule: its second round reads the value
+    // and degree input of its first, which then sit in the very staging buffers (same parity) that
+    // a non-final round j+1 writes.  A pair that starts at the caller's input has no such overlap.
     const bool defer_ok = allow_defer && !fuse && !have_org && j + 1 < plan.n_rounds &&
+                          (j == 0 || j + 2 == plan.n_rounds) &&
                           plan.round_r[j] == 1.0f && p->scope == CKV_SCOPE_CHUNK &&
                           (force_defer || (int64_t)n_bh * div_up(plan.round_len[j + 1], p->chunk) >= kDeferMinChunks);
     const int jo = fuse ? j + 1 : j;                 // index of the round whose output is produced

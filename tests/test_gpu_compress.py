@@ -455,6 +455,8 @@ def test_runtime_argument_errors():
     ([1.0, 1.0, 1.0], False),          # fused pair + a third separate round
     ([0.5, 1.0, 1.0], False),          # fused pair fed by a separate round (incoming degrees > 1)
     ([1.0, 0.7], True),
+    ([0.5, 1.0, 1.0, 1.0], False),     # no pair in the middle of a schedule (staging buffers alternate): the last two
+    ([1.0, 1.0, 1.0, 1.0, 0.5], False),
 ])
 def test_fused_two_round_kernel_is_bit_identical_to_separate_rounds(rounds, use_deg):
     """With CKV_ENABLE_FUSED=1, chunk 1024 / bf16 / dim 128 / length a multiple of 2048 and a first
@@ -462,7 +464,7 @@ def test_fused_two_round_kernel_is_bit_identical_to_separate_rounds(rounds, use_
     for bit (and that path is checked against the oracle above)."""
     import os
     _say(f"fused2 rounds={rounds} deg={use_deg}")
-    seq = 8192 if rounds[0] != 1.0 else 4096
+    seq = {3: 8192, 4: 16384, 5: 32768}.get(len(rounds), 4096) if len(rounds) > 3 or rounds[0] != 1.0 else 4096
     K, V, _ = kv_host(21, 3, seq, 128, "bf16", alpha=0.9, n_outlier=4)
     K, V = K.to(DEV), V.to(DEV)
     deg = None
@@ -521,6 +523,13 @@ def test_fused_kernel_on_duplicate_keys():
     ("bf16", 1, 3000, 64, 512, [0.5, 1.0, 1.0], True, 0, 0),       # a full round first, then a pair
     ("f32", 2, 1500, 64, 64, [1.0, 0.75], True, 0, 0),
     ("f32", 1, 1024, 128, 128, [1.0, 1.0], False, 0, 0),
+    # a pair in the middle of the schedule would write its result over the values it still reads
+    # (the staging buffers alternate): such rounds run in full and the pair is taken at the end
+    ("bf16", 1, 2566, 64, 1024, [0.5, 1.0, 1.0, 1.0], True, 0, 0),
+    ("bf16", 2, 1413, 128, 512, [0.5, 0.8, 1.0, 0.5], False, 0, 7),
+    ("bf16", 1, 2395, 128, 1024, [0.8, 1.0, 1.0, 0.5], False, 0, 0),
+    ("bf16", 2, 9000, 128, 256, [1.0, 1.0, 1.0, 1.0, 1.0], False, 4, 16),   # pairs (0,1) and (3,4), round 2 in full
+    ("f32", 1, 5000, 32, 128, [1.0, 1.0, 1.0, 1.0, 1.0, 0.5], True, 0, 0),
 ])
 def test_deferred_values_are_bit_identical_to_full_rounds(dtype, heads, seq, dim, chunk, rounds, use_deg, n_sink,
                                                           n_recent):

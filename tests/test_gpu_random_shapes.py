@@ -33,6 +33,17 @@ def _cases():
         scope = "head" if k % 5 == 3 else "chunk"
         use_deg = bool(k % 3 == 1)
         out.append((k, dtype, heads, seq, dim, chunk, rounds, n_sink, n_recent, scope, use_deg))
+    # longer schedules (a second stream, so the cases above stay what they were): deferred pairs
+    # after full rounds, in the middle and at the end of a schedule
+    rng = np.random.default_rng(20250612)
+    for k in range(28, 48):
+        dtype = "bf16" if k % 4 else "f32"
+        dim = int(rng.choice([64, 128])) if dtype == "bf16" else int(rng.choice([16, 32, 64, 128]))
+        chunk = int(rng.choice([4, 16, 64, 256, 512, 1024, 2048]))
+        seq = int(rng.integers(1, 4 * chunk + 40)) if chunk >= 256 else int(rng.integers(1, 1500))
+        rounds = [float(rng.choice([0.5, 0.8, 1.0, 1.0, 1.0])) for _ in range(int(rng.integers(3, 6)))]
+        out.append((k, dtype, int(rng.integers(1, 3)), seq, dim, chunk, rounds, int(rng.choice([0, 4])),
+                    int(rng.choice([0, 7])), "chunk", bool(k % 3 == 1)))
     return out
 
 
