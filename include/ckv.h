@@ -124,7 +124,12 @@ int ckv_match(const void* K, const ckv_layout* in, int32_t chunk, int32_t* dst, 
  *   assign   [batch, heads, seq] int32 or NULL: output index of the centroid each INPUT token
  *            ended up in (composition over rounds).
  *   workspace  >= plan.workspace_bytes, 256-byte aligned.
- * Every round re-chunks the current sequence with the same chunk size. */
+ * Every round re-chunks the current sequence with the same chunk size.
+ * Environment (read at every call; none of them changes a result bit): CKV_DISABLE_DEFERRED_VALUES=1
+ * makes every round write its value cache (by default a round with r = 1 that opens or closes the
+ * schedule together with its successor leaves the values to that successor, which rebuilds them
+ * from the round's input), CKV_FORCE_DEFERRED_VALUES=1 does so whatever the size,
+ * CKV_ENABLE_FUSED=1 lets the single-launch two-round kernel take the shapes it supports. */
 int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_layout* in,
                  const ckv_params* p, void* K_out, void* V_out, int32_t* deg_out,
                  const ckv_layout* out, int32_t* assign, void* workspace, size_t workspace_bytes,
