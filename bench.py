@@ -34,9 +34,9 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 # size; see profiles/bench_config3_hbm_traffic.txt for the runs and the factors.  Filled in by hand
 # from those runs: {(workload, kernel): bytes per launch averaged over the launches of one step}.
 MEASURED_TRAFFIC = {
-    ("config3", "merge_keys_bf16"): int((4227425.6 * 2.0 + 4489257.2) * 1024),
-    ("config3", "merge_origin_bf16"): int((6393183.7 * 2.0 + 4292636.6) * 1024),
-    ("config3", "match_bf16"): int((3145922.3 * 2.0 + 98304.0) * 1024),
+    ("config3", "merge_keys_bf16"): int((4227434.2 * 2.0 + 4489327.4) * 1024),
+    ("config3", "merge_origin_bf16"): int((6423693.0 * 2.0 + 4292654.6) * 1024),
+    ("config3", "match_bf16"): int((3172452.1 * 2.0 + 98304.0) * 1024),
     ("config3", "attn_partial_bf16"): int((66217.0 * 2.0 + 1040.0) * 1024),
 }
 
