@@ -638,6 +638,33 @@ def test_deferred_values_with_long_clusters(dtype, seq, dim, chunk, n_proto, rou
     assert np.allclose(f64(got[1][0, 0]), mean, atol=tol, rtol=tol)
 
 
+def test_calls_on_separate_streams_do_not_disturb_one_another():
+    """Two compressions and an attention issued on three streams at once (own outputs and
+    workspaces) give the bits of the same calls issued one after the other."""
+    _say("three streams at once")
+    jobs = []
+    for i, (heads, seq, chunk, rounds) in enumerate([(4, 16384, 1024, [1.0, 1.0]), (3, 9000, 256, [1.0, 0.5, 1.0])]):
+        K, V, _ = kv_host(71 + i, heads, seq, 128, "bf16", alpha=0.9, n_outlier=4)
+        jobs.append((K.to(DEV), V.to(DEV), chunk, rounds))
+    ref = [ckv.compress(K, V, c, rounds=r) for (K, V, c, r) in jobs]
+    q = torch.randn((1, 16, 128), generator=torch.Generator().manual_seed(5)).to(torch.bfloat16).to(DEV)
+    o_ref = ckv.decode_attn(q, ref[0][0], ref[0][1], deg=ref[0][2], out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for _ in range(3):                                  # a few times: the overlap differs from run to run
+        got = [None, None]
+        for i, (K, V, c, r) in enumerate(jobs):
+            with torch.cuda.stream(streams[i]):
+                got[i] = ckv.compress(K, V, c, rounds=r)
+        with torch.cuda.stream(streams[2]):
+            o = ckv.decode_attn(q, ref[0][0], ref[0][1], deg=ref[0][2], out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        for g, e in zip(got, ref):
+            for a, b in zip(g, e):
+                assert torch.equal(a, b)
+        assert torch.equal(o, o_ref)
+
+
 def test_timing_hooks_can_be_narrowed_to_one_kernel():
     """ckv_timing_select: only launches whose timing name starts with the prefix are bracketed."""
     _say("timing select")
