@@ -110,6 +110,54 @@ def test_strided_cache_layout():
     assert torch.equal(a, b)
 
 
+def test_decode_loop_can_be_captured_in_a_hip_graph():
+    """The library allocates nothing, synchronises nothing and clears nothing with memset, so the
+    per-layer attention calls of a decode step (and an append before them) can be recorded into a
+    HIP graph.  Every replay, with eager work and synchronisation between replays, gives the bits of
+    the eager calls."""
+    _say("attention calls in a HIP graph")
+    Ly, Hkv, G, L, D = 6, 4, 4, 3000, 128
+    K, V, _ = kv_host(61, Ly * Hkv, L + 1, D, "bf16", n_outlier=0)
+    K, V = K.reshape(Ly, Hkv, L + 1, D).to(DEV), V.reshape(Ly, Hkv, L + 1, D).to(DEV)
+    rng = np.random.default_rng(3)
+    deg = torch.from_numpy(rng.integers(1, 6, (Ly, Hkv, L + 1)).astype(np.int32)).to(DEV)
+    q = query_host(9, Ly, Hkv * G, D, "bf16").to(DEV).reshape(Ly, 1, Hkv * G, D)
+    k_new, v_new = K[:, :, L].clone(), V[:, :, L].clone()
+    ws = torch.empty(ckv.decode_attn_workspace(ckv.layout_of(K[0:1]), Hkv * G), dtype=torch.uint8, device=DEV)
+    o = torch.empty((Ly, 1, Hkv * G, D), dtype=torch.float32, device=DEV)
+
+    def step():
+        for l in range(Ly):
+            ckv.append(k_new[l:l + 1], v_new[l:l + 1], K[l:l + 1], V[l:l + 1], deg[l:l + 1], pos=L)
+            ckv.decode_attn(q[l], K[l:l + 1], V[l:l + 1], deg=deg[l:l + 1], out=o[l], workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    ref = o.clone()
+    for l in (0, Ly - 1):
+        _check(q[l], K[l:l + 1], V[l:l + 1], deg[l:l + 1], None, ref[l], ATTN_TOL, f"eager layer {l}")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                           # warm-up on the capture stream's side
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for i in range(4):
+        o.zero_()
+        K[:, :, L].zero_()                               # the captured append has to write the token again
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, ref), f"replay {i}"
+        assert torch.equal(K[:, :, L], k_new)
+        step()                                           # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(o, ref)
+
+
 def test_attn_argument_errors():
     _say("attn argument errors")
     K = torch.zeros((1, 2, 64, 128), dtype=torch.bfloat16, device=DEV)
