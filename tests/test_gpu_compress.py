@@ -665,6 +665,46 @@ def test_calls_on_separate_streams_do_not_disturb_one_another():
         assert torch.equal(o, o_ref)
 
 
+def test_compress_can_be_captured_in_a_hip_graph():
+    """A whole compression (three rounds, sinks / recents, deferred pair) recorded into a HIP graph:
+    every replay, with the outputs cleared and eager work in between, gives the eager bits."""
+    import os
+    _say("compress in a HIP graph")
+    heads, seq, chunk, rounds = 4, 8192 + 80, 512, [1.0, 1.0, 0.5]
+    K, V, _ = kv_host(81, heads, seq, 128, "bf16", alpha=0.9, n_outlier=4)
+    K, V = K.to(DEV), V.to(DEV)
+    kw = dict(rounds=rounds, n_sink=16, n_recent=64)
+    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"
+    try:
+        ref = ckv.compress(K, V, chunk, **kw)
+        torch.cuda.synchronize()
+        out = tuple(torch.zeros_like(t) for t in ref)
+        plan = ckv.plan(ckv.layout_of(K), ckv.make_params(chunk, rounds=rounds, n_sink=16, n_recent=64))
+        ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=DEV)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            ckv.compress(K, V, chunk, out=out, workspace=ws, **kw)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ckv.compress(K, V, chunk, out=out, workspace=ws, **kw)
+    finally:
+        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
+    for i in range(3):
+        for t in out:
+            t.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, a, b in zip(["K'", "V'", "deg'", "assign"], out, ref):
+            assert torch.equal(a, b), f"replay {i}: {n}"
+        ckv.compress(K, V, chunk, **kw)                  # eager work between replays
+        torch.cuda.synchronize()
+
+
 def test_timing_hooks_can_be_narrowed_to_one_kernel():
     """ckv_timing_select: only launches whose timing name starts with the prefix are bracketed."""
     _say("timing select")
