@@ -117,7 +117,8 @@ __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
   constexpr int U = kUnroll;
   __shared__ float s_m[NRG][G];
   __shared__ float s_l[NRG][G];
-  __shared__ float s_o[NRG][D];
+  constexpr int GG = (G < 4) ? G : 4;   // query heads merged per pass of the final reduction
+  __shared__ float s_o[GG][NRG][D];
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, rg = tid / LPR, piece = tid % LPR;
@@ -239,21 +240,31 @@ __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
   }
   __syncthreads();
   const int64_t pbase = (((int64_t)b * kv_heads + kvh) * n_splits + split) * G;
+  // GG heads at a time: every row group rescales its accumulators to the workgroup's maximum and
+  // parks them in LDS, then each thread sums a few (head, channel) columns over the row groups
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float M = -INFINITY;
-    for (int r2 = 0; r2 < NRG; ++r2) M = fmaxf(M, s_m[r2][g]);
-    const float f = (m[g] == -INFINITY) ? 0.f : exp2f(m[g] - M);
+  for (int g0 = 0; g0 < G; g0 += GG) {
+    if (g0 > 0) __syncthreads();
 #pragma unroll
-    for (int e = 0; e < E; ++e) s_o[rg][piece * E + e] = acc[g][e] * f;
-    __syncthreads();
-    if (tid < D) {
-      float sum = 0.f;
-      for (int r2 = 0; r2 < NRG; ++r2) sum += s_o[r2][tid];
-      o_part[(pbase + g) * D + tid] = sum;
+    for (int gg = 0; gg < GG; ++gg) {
+      const int g = g0 + gg;
+      float M = -INFINITY;
+      for (int r2 = 0; r2 < NRG; ++r2) M = fmaxf(M, s_m[r2][g]);
+      const float f = (m[g] == -INFINITY) ? 0.f : exp2f(m[g] - M);
+#pragma unroll
+      for (int e = 0; e < E; ++e) s_o[gg][rg][piece * E + e] = acc[g][e] * f;
     }
-    if (tid == 0) {
-      float L = 0.f;
+    __syncthreads();
+    for (int idx = tid; idx < GG * D; idx += kThreads) {
+      const int gg = idx / D, d = idx % D;
+      float sum = 0.f;
+      for (int r2 = 0; r2 < NRG; ++r2) sum += s_o[gg][r2][d];
+      o_part[(pbase + g0 + gg) * D + d] = sum;
+    }
+    if (tid < GG) {
+      const int g = g0 + tid;
+      float M = -INFINITY, L = 0.f;
+      for (int r2 = 0; r2 < NRG; ++r2) M = fmaxf(M, s_m[r2][g]);
       for (int r2 = 0; r2 < NRG; ++r2) {
         const float mr = s_m[r2][g];
         L += (mr == -INFINITY) ? 0.f : s_l[r2][g] * exp2f(mr - M);
@@ -261,7 +272,6 @@ __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
       ml_part[(pbase + g) * 2] = M;
       ml_part[(pbase + g) * 2 + 1] = L;
     }
-    __syncthreads();
   }
 }
 
