@@ -283,16 +283,28 @@ template <int G>
 __global__ void attn_combine_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
                                     int kv_heads, int n_splits, int dim, void* __restrict__ o, int o_dtype) {
   __shared__ float s_w[kMaxSplits];
+  __shared__ float s_l[kMaxSplits];
   __shared__ float s_red[2][4];
   const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
   const int kvh = hq / G, g = hq % G;
   const int64_t pbase = ((int64_t)b * kv_heads + kvh) * n_splits;
   const int lane = d & 63, wave = d >> 6, n_waves = blockDim.x >> 6;
+  // the first partial rows of this thread's channel are requested before anything else: they do
+  // not depend on the weights, and their latency hides behind the two reductions below
+  constexpr int kAhead = 16;
+  const bool live = d < dim;
+  const float* op = o_part + (pbase * G + g) * dim + (live ? d : 0);
+  const int64_t pitch = (int64_t)G * dim;
+  float ahead[kAhead];
+#pragma unroll
+  for (int i = 0; i < kAhead; ++i) ahead[i] = op[min(i, n_splits - 1) * pitch];   // clamped: always a valid row
+  const float2* ml = reinterpret_cast<const float2*>(ml_part);
   float mloc = -INFINITY;
   for (int s = d; s < n_splits; s += blockDim.x) {
-    const float ms = ml_part[((pbase + s) * G + g) * 2];
-    s_w[s] = ms;
-    mloc = fmaxf(mloc, ms);
+    const float2 v = ml[(pbase + s) * G + g];      // (max, sum of exponentials) of split s
+    s_w[s] = v.x;
+    s_l[s] = v.y;
+    mloc = fmaxf(mloc, v.x);
   }
 #pragma unroll
   for (int sh = 32; sh > 0; sh >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, sh));
@@ -305,7 +317,7 @@ __global__ void attn_combine_kernel(const float* __restrict__ o_part, const floa
     const float ms = s_w[s];
     const float f = (ms == -INFINITY) ? 0.f : exp2f(ms - M);
     s_w[s] = f;
-    dloc += f * ml_part[((pbase + s) * G + g) * 2 + 1];
+    dloc += f * s_l[s];
   }
 #pragma unroll
   for (int sh = 32; sh > 0; sh >>= 1) dloc += __shfl_xor(dloc, sh);
@@ -313,12 +325,17 @@ __global__ void attn_combine_kernel(const float* __restrict__ o_part, const floa
   __syncthreads();
   float den = 0.f;
   for (int w2 = 0; w2 < n_waves; ++w2) den += s_red[1][w2];
-  if (d >= dim) return;
+  if (!live) return;
   float num = 0.f;
-  const float* op = o_part + (pbase * G + g) * dim + d;
-  const int64_t pitch = (int64_t)G * dim;
-#pragma unroll 8
-  for (int s = 0; s < n_splits; ++s) num = fmaf(op[s * pitch], s_w[s], num);
+#pragma unroll
+  for (int i = 0; i < kAhead; ++i) num = fmaf(ahead[i], (i < n_splits) ? s_w[i] : 0.f, num);
+  for (int s0 = kAhead; s0 < n_splits; s0 += kAhead) {
+    float x[kAhead];
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) x[i] = op[min(s0 + i, n_splits - 1) * pitch];
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) num = fmaf(x[i], (s0 + i < n_splits) ? s_w[s0 + i] : 0.f, num);
+  }
   const float res = den > 0.f ? num / den : 0.f;
   const int64_t oi = ((int64_t)b * kv_heads * G + hq) * dim + d;
   if (o_dtype == CKV_BF16) reinterpret_cast<uint16_t*>(o)[oi] = f32_to_bf16_rne(res);
