@@ -190,7 +190,8 @@ typedef struct {
 
 /* ckv_decode_attn (Eq. 3) reading the paged cache in place.  lens [batch] int32 (device, required):
  * tokens of each sequence; max_len: host upper bound on them (sizes the split of the sequence;
- * lengths are clamped to it and to max_blocks*block_size).  deg_pool NULL = all ones (Eq. 1). */
+ * lengths are clamped to it and to max_blocks*block_size).  deg_pool NULL = all ones (Eq. 1).
+ * CKV_EUNSUPPORTED for a pool of 2^31 token rows (n_blocks*heads*block_size) or more. */
 int ckv_paged_decode_attn_workspace(const ckv_paged_layout* pl, int32_t q_heads, int32_t max_len, size_t* bytes);
 int ckv_paged_decode_attn(const void* q, int32_t q_heads, const void* K_pool, const void* V_pool,
                           const int32_t* deg_pool, const int32_t* block_table, const int32_t* lens,

@@ -486,6 +486,7 @@ int ckv_paged_decode_attn_workspace(const ckv_paged_layout* pl, int32_t q_heads,
   if (max_len <= 0 || q_heads <= 0 || q_heads % pl->heads) return CKV_ESHAPE;
   const int limit = ckv::attn_paged_span_limit(pl->block_size);
   if ((int64_t)limit * 1024 < max_len) return CKV_EUNSUPPORTED;   // more table entries per slice than the kernel holds
+  if ((int64_t)pl->n_blocks * pl->heads * pl->block_size > INT32_MAX) return CKV_EUNSUPPORTED;   // pool rows are indexed in 32 bits
   *bytes = ckv::align_up(ckv::attn_workspace_bytes(pl->batch, pl->heads, q_heads, pl->dim, max_len, limit), 256);
   return CKV_OK;
 }

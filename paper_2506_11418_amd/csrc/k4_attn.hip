@@ -124,20 +124,24 @@ __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
   const int tid = threadIdx.x, rg = tid / LPR, piece = tid % LPR;
   const int len = lens ? min(lens[b], seq) : seq;
   const int t0 = split * span, t1 = min(t0 + span, len);
-  const int64_t base = (PAGED ? 0 : (int64_t)b * kv.stride_b) + (int64_t)kvh * kv.stride_h + piece * E;
+  const int64_t base = PAGED ? piece * E : (int64_t)b * kv.stride_b + (int64_t)kvh * kv.stride_h + piece * E;
   const T* Kp = K + base;
   const T* Vp = V + base;
-  const int32_t* dseq = !deg ? nullptr : PAGED ? deg + ((int64_t)kvh << paged.shift)
-                                               : deg + ((int64_t)b * kv_heads + kvh) * kv.deg_stride;
+  const int32_t* dseq = !deg ? nullptr : PAGED ? deg : deg + ((int64_t)b * kv_heads + kvh) * kv.deg_stride;
   const int32_t* tbl = PAGED ? paged.table + (int64_t)b * paged.max_blocks : nullptr;
   const int bs_mask = (1 << paged.shift) - 1;
-  // the slice's block ids go to LDS first, so that a row's address does not wait for a second
-  // trip to memory (the host sizes the slices so that their table entries fit)
+  // the slice's blocks go to LDS first, each as the pool row ((block, head) pair times block size)
+  // its first token of this head sits in, or -1 for an entry outside the pool: a row's address then
+  // needs no second trip to memory and one add (the host sizes the slices so that their table
+  // entries fit, and refuses pools of 2^31 rows or more)
   __shared__ int32_t s_tbl[PAGED ? kMaxTableLds : 1];
   const int blk0 = t0 >> paged.shift;
   if (PAGED && t0 < t1) {
     const int n_ent = min(((t1 - 1) >> paged.shift) - blk0 + 1, kMaxTableLds);
-    for (int i = tid; i < n_ent; i += kThreads) s_tbl[i] = tbl[blk0 + i];
+    for (int i = tid; i < n_ent; i += kThreads) {
+      const int blk = tbl[blk0 + i];
+      s_tbl[i] = ((unsigned)blk < (unsigned)paged.n_blocks) ? ((blk * kv_heads + kvh) << paged.shift) : -1;
+    }
     __syncthreads();
   }
 
@@ -165,12 +169,12 @@ __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
     for (int u = 0; u < U; ++u) {
       const int tc = min(tb + u * NRG + rg, t1 - 1);   // clamp: always a valid row, masked at use
       if (PAGED) {
-        const int blk = s_tbl[min((tc >> paged.shift) - blk0, kMaxTableLds - 1)];
-        const bool in_pool = (unsigned)blk < (unsigned)paged.n_blocks;
+        const int row0 = s_tbl[min((tc >> paged.shift) - blk0, kMaxTableLds - 1)];
+        const bool in_pool = row0 >= 0;
         // row 0 when outside the pool: always a valid address, masked through the degree
-        const int64_t row = in_pool ? (((int64_t)blk * kv_heads) << paged.shift) + (tc & bs_mask) : 0;
-        st.kr[u] = Elems<T>::load_raw(Kp + row * kv.stride_s);
-        st.vr[u] = Elems<T>::load_raw(Vp + row * kv.stride_s);
+        const int row = in_pool ? row0 + (tc & bs_mask) : 0;
+        st.kr[u] = Elems<T>::load_raw(Kp + (int64_t)row * kv.stride_s);
+        st.vr[u] = Elems<T>::load_raw(Vp + (int64_t)row * kv.stride_s);
         const int d = dseq ? dseq[row] : 1;
         st.dg[u] = in_pool ? d : 0;
       } else {
