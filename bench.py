@@ -37,7 +37,7 @@ MEASURED_TRAFFIC = {
     ("config3", "merge_keys_bf16"): int((4227434.2 * 2.0 + 4489327.4) * 1024),
     ("config3", "merge_origin_bf16"): int((6423693.0 * 2.0 + 4292654.6) * 1024),
     ("config3", "match_bf16"): int((3172452.1 * 2.0 + 98304.0) * 1024),
-    ("config3", "attn_partial_bf16"): int((66173.0 * 2.0 + 1040.0) * 1024),
+    ("config3", "attn_partial_bf16"): int((66165.0 * 2.0 + 1040.0) * 1024),
 }
 
 WORKLOADS = {
