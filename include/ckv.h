@@ -16,9 +16,10 @@
  *     overlap inputs (CKV_EINVAL where the host can tell); ckv_append and the ckv_paged_* calls
  *     update the cache they are given in place, as stated with each of them;
  *   - base pointers and row strides (in bytes) of K/V tensors are multiples of 16 (CKV_EALIGN);
- *   - the library keeps no state between calls apart from the timing hooks at the end of this file
- *     (a single benchmarking thread) and a per-device note of which kernels have been set up:
- *     calls from several threads, each on its own stream and buffers, do not disturb one another.
+ *   - the library reads no environment variable and keeps no state between calls apart from the
+ *     timing hooks at the end of this file (a single benchmarking thread) and a per-device note,
+ *     taken under a lock, of which kernels have been set up: calls from several threads, each on
+ *     its own stream and buffers, do not disturb one another.
  *
  * Tensor layout ("layout"): element (b, h, t, :) of a [batch, heads, seq, dim] tensor lives at
  * base + b*stride_b + h*stride_h + t*stride_s (strides in ELEMENTS); dim is contiguous.  This
@@ -79,9 +80,16 @@ typedef struct {
                            CKV_SCOPE_HEAD  (1): the edges of all chunks of a (batch, head)
                            sequence ranked together, the floor(r*edges) best merged, ties to the
                            lower position.  Equal at r = 1.                                     */
+  uint32_t flags;       /* CKV_ROUTE_* bits; 0 = let the library choose.  They pick between kernel
+                           routes that give the same result bit for bit (see ckv_compress).     */
 } ckv_params;
 
 enum { CKV_SCOPE_CHUNK = 0, CKV_SCOPE_HEAD = 1 };
+enum {
+  CKV_ROUTE_FULL_ROUNDS = 1u,   /* every round writes its value cache                            */
+  CKV_ROUTE_DEFER_ALWAYS = 2u   /* leave values to the next round wherever that is possible,
+                                   whatever the size of the job                                  */
+};
 
 typedef struct {
   int32_t out_seq;                       /* tokens per (batch, head) after the last round        */
@@ -101,6 +109,15 @@ const char* ckv_strerror(int status);
  * L < 2 keeps all).  Lengths depend only on (seq, chunk, schedule), never on data. */
 int ckv_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan);
 
+/* Host only.  Number of A tokens (sources) of a sequence of `seq` tokens cut into chunks of `chunk`
+ * tokens (Sec. 5.2): ceil(L/2) per chunk of L tokens.  Negative status for bad arguments. */
+int32_t ckv_n_sources(int32_t seq, int32_t chunk);
+
+/* Host only.  The cache budget B = floor(R * n) of Algorithm 1 for a prompt of n tokens and cache
+ * ratio R in (0,1] (R carried as float, widened, + 1e-9 so that exact products stay exact).
+ * Negative status for bad arguments. */
+int32_t ckv_budget_tokens(float cache_ratio, int32_t n);
+
 /* Similarity + matching stage alone (Sec. 5.2; Eq. 2): for every A token its most similar B
  * token of the same chunk under cosine similarity of the keys (lowest B index on ties).
  *   dst   [batch, heads, n_src] int32: position in the sequence of the matched B token (-1 when the
@@ -109,7 +126,8 @@ int ckv_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan);
  *   score [batch, heads, n_src] fp32: cosine similarity of that edge.
  * bf16 keys: dot products of the stored values on bf16 MFMA with fp32 accumulation, inverse norms
  * in fp32 applied afterwards (keys are not re-rounded).  Supported: bf16 dim 64 or 128; fp32 dim
- * 16..128 multiple of 16. */
+ * 16, 32, 64 or 128 (plain fp32 FMA through LDS: a correctness path for small caches, not tuned
+ * against a roofline). */
 int ckv_match(const void* K, const ckv_layout* in, int32_t chunk, int32_t* dst, float* score,
               void* hip_stream);
 
@@ -125,11 +143,11 @@ int ckv_match(const void* K, const ckv_layout* in, int32_t chunk, int32_t* dst, 
  *            ended up in (composition over rounds).
  *   workspace  >= plan.workspace_bytes, 256-byte aligned.
  * Every round re-chunks the current sequence with the same chunk size.
- * Environment (read at every call; none of them changes a result bit): CKV_DISABLE_DEFERRED_VALUES=1
- * makes every round write its value cache (by default a round with r = 1 that opens or closes the
- * schedule together with its successor leaves the values to that successor, which rebuilds them
- * from the round's input), CKV_FORCE_DEFERRED_VALUES=1 does so whatever the size,
- * CKV_ENABLE_FUSED=1 lets the single-launch two-round kernel take the shapes it supports. */
+ * Routes (p->flags; none of them changes a result bit): by default a round with r = 1 that opens
+ * or closes the schedule together with its successor leaves the values to that successor, which
+ * rebuilds them from the round's input, once the job is large enough for that to pay;
+ * CKV_ROUTE_FULL_ROUNDS makes every round write its value cache, CKV_ROUTE_DEFER_ALWAYS defers
+ * whatever the size.  ckv_plan sizes the workspace for the route the same flags select. */
 int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_layout* in,
                  const ckv_params* p, void* K_out, void* V_out, int32_t* deg_out,
                  const ckv_layout* out, int32_t* assign, void* workspace, size_t workspace_bytes,
@@ -158,7 +176,15 @@ int ckv_schedule_annealed(int32_t seq, int32_t chunk, int32_t n_sink, int32_t n_
 int ckv_append(const void* k_new, const void* v_new, void* K, void* V, int32_t* deg, const ckv_layout* cache,
                int32_t* lens, int32_t pos, void* hip_stream);
 
-/* Scratch bytes ckv_decode_attn needs for this cache shape and number of query heads. */
+/* Scratch bytes ckv_decode_attn needs for this cache shape and number of query heads.
+ * Workspace contract (ckv_decode_attn and ckv_paged_decode_attn): the first 4 * batch * heads bytes
+ * are arrival counters, one int32 per (batch, KV head).  They must be ZERO when a call starts and
+ * every call leaves them zero, so zero-fill a workspace once when it is allocated; after that it
+ * serves any number of calls (of any length it is large enough for) without being touched.  Before
+ * a call with a larger batch * heads than the workspace has served since it was last zeroed, zero
+ * it again (the counters of the larger call reach into what earlier calls used as scratch).  With
+ * counters that are not zero the output is wrong; nothing waits on them, so no call can hang.
+ * Calls that share a workspace must not overlap in time. */
 int ckv_decode_attn_workspace(const ckv_layout* kv, int32_t q_heads, size_t* bytes);
 
 /* One decode step of attention over a (compressed) cache (Eq. 3; Algorithm 1 decode line):
@@ -167,7 +193,9 @@ int ckv_decode_attn_workspace(const ckv_layout* kv, int32_t q_heads, size_t* byt
  *   q [batch, q_heads, dim] contiguous, same dtype as the cache; lens [batch] int32 (each
  *   <= kv->seq; 0 gives a zero output) or NULL (= kv->seq); deg [batch, heads, kv->seq] int32
  *   (>= 1; row stride kv->deg_stride) or NULL (= 1: plain attention, Eq. 1); scale <= 0 selects 1/sqrt(dim);
- *   o [batch, q_heads, dim] contiguous in o_dtype.  Arithmetic is fp32.
+ *   o [batch, q_heads, dim] contiguous in o_dtype.  Arithmetic is fp32.  One kernel launch: the
+ *   sequence is split into slices, and the slice that finishes last for a (batch, KV head) merges
+ *   the partial results of all of them in slice order (run-to-run identical bits).
  * Supported: q_heads / kv->heads in {1,2,4,8}; bf16 dim 64/128; fp32 dim 32/64/128. */
 int ckv_decode_attn(const void* q, int32_t q_heads, const void* K, const void* V,
                     const ckv_layout* kv, const int32_t* lens, const int32_t* deg, float scale,
@@ -217,6 +245,11 @@ int ckv_paged_gather(const void* K_pool, const void* V_pool, const int32_t* deg_
 int ckv_paged_scatter(const void* K, const void* V, const int32_t* deg, const ckv_layout* in, void* K_pool,
                       void* V_pool, int32_t* deg_pool, int32_t* block_table, const ckv_paged_layout* pl,
                       int32_t old_seq, int32_t* freed, int32_t* lens, void* hip_stream);
+
+/* Host only.  Blocks per sequence that ckv_paged_scatter releases when a sequence of old_seq tokens
+ * shrinks to new_seq tokens: ceil(old_seq / bs) - ceil(new_seq / bs); negative status for bad
+ * arguments (new_seq > old_seq included). */
+int32_t ckv_paged_freed_blocks(const ckv_paged_layout* pl, int32_t old_seq, int32_t new_seq);
 
 /* ckv_compress on sequences of `seq` tokens each that live in a paged cache, written back into the
  * sequences' own first blocks (compaction), the blocks behind them released as in

@@ -35,7 +35,7 @@ class Layout(C.Structure):
 class Params(C.Structure):
     _fields_ = [("chunk", C.c_int32), ("retain_ratio", C.c_float), ("n_rounds", C.c_int32),
                 ("r", C.c_float * MAX_ROUNDS), ("n_sink", C.c_int32), ("n_recent", C.c_int32),
-                ("scope", C.c_int32)]
+                ("scope", C.c_int32), ("flags", C.c_uint32)]
 
 
 class PagedLayout(C.Structure):
@@ -68,6 +68,10 @@ def lib() -> C.CDLL:
         L.ckv_strerror.restype = C.c_char_p
         L.ckv_strerror.argtypes = [C.c_int]
         L.ckv_plan.argtypes = [C.POINTER(Layout), C.POINTER(Params), C.POINTER(PlanT)]
+        L.ckv_n_sources.argtypes = [i32, i32]
+        L.ckv_n_sources.restype = i32
+        L.ckv_budget_tokens.argtypes = [C.c_float, i32]
+        L.ckv_budget_tokens.restype = i32
         L.ckv_match.argtypes = [vp, C.POINTER(Layout), i32, vp, vp, vp]
         L.ckv_compress.argtypes = [vp, vp, vp, C.POINTER(Layout), C.POINTER(Params), vp, vp, vp,
                                    C.POINTER(Layout), vp, vp, C.c_size_t, vp]
@@ -84,6 +88,8 @@ def lib() -> C.CDLL:
         L.ckv_paged_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, PL, vp]
         L.ckv_paged_gather.argtypes = [vp, vp, vp, vp, PL, i32, vp, vp, vp, C.POINTER(Layout), vp]
         L.ckv_paged_scatter.argtypes = [vp, vp, vp, C.POINTER(Layout), vp, vp, vp, vp, PL, i32, vp, vp, vp]
+        L.ckv_paged_freed_blocks.argtypes = [PL, i32, i32]
+        L.ckv_paged_freed_blocks.restype = i32
         L.ckv_paged_compress_plan.argtypes = [PL, i32, C.POINTER(Params), C.POINTER(i32), C.POINTER(i32),
                                               C.POINTER(C.c_size_t)]
         L.ckv_paged_compress.argtypes = [vp, vp, vp, vp, vp, PL, i32, C.POINTER(Params), vp, vp, C.c_size_t, vp]
@@ -117,13 +123,16 @@ def layout_of(t: torch.Tensor, deg: Optional[torch.Tensor] = None) -> Layout:
 
 
 SCOPES = {"chunk": 0, "head": 1}
+# kernel routes with bit-identical results (ckv_params.flags): None = the library chooses
+ROUTES = {None: 0, "full_rounds": 1, "defer_always": 2}
 
 
 def make_params(chunk: int, retain_ratio: float = 1.0, rounds: Optional[Sequence[float]] = None,
-                n_sink: int = 0, n_recent: int = 0, scope: str = "chunk") -> Params:
+                n_sink: int = 0, n_recent: int = 0, scope: str = "chunk", route: Optional[str] = None) -> Params:
     p = Params()
     p.chunk, p.retain_ratio, p.n_sink, p.n_recent = chunk, retain_ratio, n_sink, n_recent
     p.scope = SCOPES[scope]
+    p.flags = ROUTES[route]
     if rounds is not None:
         if not 0 < len(rounds) <= MAX_ROUNDS:
             raise ValueError("rounds must have 1..8 entries")
@@ -161,8 +170,9 @@ def _stream():
 def match(K: torch.Tensor, chunk: int):
     """ckv_match: (dst positions int32 [B,H,n_src], scores fp32 [B,H,n_src])."""
     lay = layout_of(K)
-    s = K.shape[2]
-    n_src = (s // chunk) * (chunk // 2) + ((s % chunk) + 1) // 2
+    n_src = lib().ckv_n_sources(K.shape[2], chunk)
+    if n_src < 0:
+        raise CkvError(n_src, "ckv_n_sources")
     dst = torch.empty((K.shape[0], K.shape[1], n_src), dtype=torch.int32, device=K.device)
     score = torch.empty((K.shape[0], K.shape[1], n_src), dtype=torch.float32, device=K.device)
     st = lib().ckv_match(_ptr(K), C.byref(lay), chunk, _ptr(dst), _ptr(score), _stream())
@@ -175,17 +185,18 @@ def compress(K: torch.Tensor, V: torch.Tensor, chunk: int, retain_ratio: float =
              rounds: Optional[Sequence[float]] = None, deg: Optional[torch.Tensor] = None,
              want_assign: bool = True, out: Optional[tuple] = None,
              workspace: Optional[torch.Tensor] = None, n_sink: int = 0, n_recent: int = 0,
-             scope: str = "chunk"):
+             scope: str = "chunk", route: Optional[str] = None):
     """ckv_compress: returns (K', V', deg', assign or None).  K, V: [B,H,S,D] on the GPU.
     The first n_sink and last n_recent tokens bypass the clustering in every round.
     scope: "chunk" = top-r inside every chunk, "head" = one ranking over all chunks of a sequence.
+    route: None, "full_rounds" or "defer_always" (same result bits; see ckv_params.flags).
 
     `out` may pass preallocated (K_out, V_out, deg_out, assign) and `workspace` a uint8 tensor, so
     that a timed loop allocates nothing."""
     lay = layout_of(K, deg)
     if layout_of(V).dtype != lay.dtype or V.shape != K.shape:
         raise ValueError("K and V must have the same shape and dtype")
-    params = make_params(chunk, retain_ratio, rounds, n_sink, n_recent, scope)
+    params = make_params(chunk, retain_ratio, rounds, n_sink, n_recent, scope, route)
     pl = plan(lay, params)
     B, H, S, D = K.shape
     if out is None:
@@ -217,7 +228,8 @@ def decode_attn_workspace(lay: Layout, q_heads: int) -> int:
 def decode_attn(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, lens: Optional[torch.Tensor] = None,
                 deg: Optional[torch.Tensor] = None, scale: float = 0.0, out_dtype=None,
                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
-    """ckv_decode_attn: q [B,Hq,D], K/V [B,Hkv,L,D], lens [B] int32, deg [B,Hkv,L] int32 -> o [B,Hq,D]."""
+    """ckv_decode_attn: q [B,Hq,D], K/V [B,Hkv,L,D], lens [B] int32, deg [B,Hkv,L] int32 -> o [B,Hq,D].
+    A `workspace` passed in must have been zero-filled when it was allocated (torch.zeros)."""
     lay = layout_of(K, deg)
     if not q.is_contiguous() or q.dim() != 3 or q.dtype != K.dtype:
         raise ValueError("q must be a contiguous [batch, q_heads, dim] tensor of the cache dtype")
@@ -225,13 +237,21 @@ def decode_attn(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, lens: Optiona
     if out is None:
         out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
     if workspace is None:
-        workspace = torch.empty(decode_attn_workspace(lay, q_heads), dtype=torch.uint8, device=q.device)
+        workspace = torch.zeros(decode_attn_workspace(lay, q_heads), dtype=torch.uint8, device=q.device)
     st = lib().ckv_decode_attn(_ptr(q), q_heads, _ptr(K), _ptr(V), C.byref(lay), _ptr(lens), _ptr(deg),
                                scale, _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(),
                                _stream())
     if st != 0:
         raise CkvError(st, "ckv_decode_attn")
     return out
+
+
+def budget_tokens(cache_ratio: float, n: int) -> int:
+    """ckv_budget_tokens: Algorithm 1's cache budget B = floor(R * n)."""
+    b = lib().ckv_budget_tokens(cache_ratio, n)
+    if b < 0:
+        raise CkvError(b, "ckv_budget_tokens")
+    return b
 
 
 def schedule_annealed(seq: int, chunk: int, budget: int, r_init: float = 0.8, delta_r: float = 0.2,
@@ -289,7 +309,7 @@ def paged_decode_attn(q, K_pool, V_pool, deg_pool, block_table, lens, max_len: i
         st = lib().ckv_paged_decode_attn_workspace(C.byref(pl), q_heads, max_len, C.byref(n))
         if st != 0:
             raise CkvError(st, "ckv_paged_decode_attn_workspace")
-        workspace = torch.empty(n.value, dtype=torch.uint8, device=q.device)
+        workspace = torch.zeros(n.value, dtype=torch.uint8, device=q.device)
     st = lib().ckv_paged_decode_attn(_ptr(q), q_heads, _ptr(K_pool), _ptr(V_pool), _ptr(deg_pool), _ptr(block_table),
                                      _ptr(lens), C.byref(pl), max_len, scale, _ptr(out), _DT[out.dtype],
                                      _ptr(workspace), workspace.numel(), _stream())
@@ -329,8 +349,10 @@ def paged_scatter(K, V, deg, K_pool, V_pool, deg_pool, block_table, old_seq: int
     release the blocks behind them; returns the freed block ids [batch, n_freed]."""
     pl = paged_layout_of(K_pool, block_table)
     lay = layout_of(K, deg)
-    n_freed = -(-old_seq // pl.block_size) - (-(-K.shape[2] // pl.block_size))
-    freed = torch.empty((pl.batch, max(n_freed, 0)), dtype=torch.int32, device=K.device)
+    n_freed = lib().ckv_paged_freed_blocks(C.byref(pl), old_seq, K.shape[2])
+    if n_freed < 0:
+        raise CkvError(n_freed, "ckv_paged_freed_blocks")
+    freed = torch.empty((pl.batch, n_freed), dtype=torch.int32, device=K.device)
     st = lib().ckv_paged_scatter(_ptr(K), _ptr(V), _ptr(deg), C.byref(lay), _ptr(K_pool), _ptr(V_pool),
                                  _ptr(deg_pool), _ptr(block_table), C.byref(pl), old_seq, _ptr(freed), _ptr(lens),
                                  _stream())

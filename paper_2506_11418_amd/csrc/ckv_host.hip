@@ -1,7 +1,6 @@
 // Host driver of libckv: argument validation, the rounds schedule (Algorithm 1's loop after
 // prefill), workspace carving, kernel sequencing and optional per-kernel timing.
 #include <math.h>
-#include <stdlib.h>
 #include <string.h>
 
 #include <string>
@@ -73,28 +72,75 @@ int seq_after_round(int len, int chunk, float r, int n_sink, int n_recent, int s
   return (len - mid) + full * chunk_out(chunk, r) + chunk_out(tail, r);
 }
 
+// How each round of a schedule runs.  FULL: match + merge writing keys, values and degrees.
+// A deferred pair: when round j merges every edge (r = 1) and another round follows, round j may
+// write keys and degrees only (KEYS_ONLY) and round j+1 rebuild the value rows it needs from round
+// j's value input (ORIGIN); the intermediate value cache is then neither written nor read, and
+// the result is the same bit for bit.  A pair is taken at the start of a schedule or at its end,
+// not in between: the staging buffers alternate, so the second round of a pair that starts at round
+// j >= 1 reads value and degree input from the very buffers (same parity) a non-final round j+1
+// writes.  It pays once the second round has enough workgroups (one per chunk, each rebuilding the
+// values of 2*chunk original tokens) to fill the chip: from about 4 per CU on MI355X (measured
+// crossover at 1024 chunks); smaller jobs run every round in full unless the caller's flags say
+// otherwise.
+enum RoundMode { ROUND_FULL = 0, ROUND_KEYS_ONLY = 1, ROUND_ORIGIN = 2 };
+constexpr int64_t kDeferMinChunks = 1024;
+
+void plan_routes(const ckv_layout* in, const ckv_params* p, const ckv_plan_t* plan, RoundMode (&mode)[CKV_MAX_ROUNDS]) {
+  const int64_t n_bh = (int64_t)in->batch * in->heads;
+  const bool allow = !(p->flags & CKV_ROUTE_FULL_ROUNDS), force = (p->flags & CKV_ROUTE_DEFER_ALWAYS) != 0;
+  for (int j = 0; j < CKV_MAX_ROUNDS; ++j) mode[j] = ROUND_FULL;
+  for (int j = 0; j + 1 < plan->n_rounds; ++j) {
+    int lo, hi;
+    clusterable(plan->round_len[j], p->n_sink, p->n_recent, &lo, &hi);
+    int lo2, hi2;   // both rounds must have tokens to cluster (a cache of sinks and recents only is copied)
+    clusterable(plan->round_len[j + 1], p->n_sink, p->n_recent, &lo2, &hi2);
+    const bool pair = allow && (j == 0 || j + 2 == plan->n_rounds) && plan->round_r[j] == 1.0f &&
+                      p->scope == CKV_SCOPE_CHUNK && hi > lo && hi2 > lo2 &&
+                      (force || n_bh * div_up(plan->round_len[j + 1], p->chunk) >= kDeferMinChunks);
+    if (pair) {
+      mode[j] = ROUND_KEYS_ONLY;
+      mode[j + 1] = ROUND_ORIGIN;
+      ++j;   // the pair's second round cannot open another pair
+    }
+  }
+}
+
 struct Workspace {
   size_t dst, score, sel, lists, map, K[2], V[2], deg[2], total;
 };
 
-Workspace carve(const ckv_layout* in, const ckv_plan_t* plan, int chunk, int scope) {
+Workspace carve(const ckv_layout* in, const ckv_params* p, const ckv_plan_t* plan) {
   Workspace w{};
+  const int chunk = p->chunk;
   const size_t n_bh = (size_t)in->batch * in->heads;
   const size_t e = elem_bytes(in->dtype);
+  RoundMode mode[CKV_MAX_ROUNDS];
+  plan_routes(in, p, plan, mode);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t n_src0 = n_sources(in->seq, chunk);
   w.dst = take(n_bh * n_src0 * 4);
   w.score = take(n_bh * n_src0 * 4);
-  if (scope == CKV_SCOPE_HEAD) w.sel = take(n_bh * (size_t)div_up(in->seq, chunk) * 8);
+  if (p->scope == CKV_SCOPE_HEAD) w.sel = take(n_bh * (size_t)div_up(in->seq, chunk) * 8);
   const int inter = plan->n_rounds - 1;   // intermediate caches
   if (inter >= 1) w.map = take(n_bh * (size_t)plan->round_len[1] * 4);
   // member lists a keys-only merge hands to the next round (3 int16 per source of a chunk)
-  if (inter >= 1) w.lists = take(n_bh * (size_t)div_up(in->seq, chunk) * 3 * (chunk / 2) * 2);
+  bool any_pair = false;
+  for (int j = 0; j < plan->n_rounds; ++j) any_pair |= mode[j] == ROUND_KEYS_ONLY;
+  if (any_pair) w.lists = take(n_bh * (size_t)div_up(in->seq, chunk) * 3 * (chunk / 2) * 2);
+  // Rounds alternate between two staging caches.  A staging VALUE cache that only keys-only rounds
+  // would write holds nothing but the sink / recent rows, which those rounds still copy: without
+  // sinks and recents it is left out (at the full-model 128k shape that is 4 GiB).
   for (int k = 0; k < 2 && k < inter; ++k) {
-    const size_t len = plan->round_len[k + 1];
+    size_t len = 0;
+    bool values = false;
+    for (int j = k; j < inter; j += 2) {
+      len = len > (size_t)plan->round_len[j + 1] ? len : (size_t)plan->round_len[j + 1];
+      values |= mode[j] != ROUND_KEYS_ONLY || p->n_sink + p->n_recent > 0;
+    }
     w.K[k] = take(n_bh * len * in->dim * e);
-    w.V[k] = take(n_bh * len * in->dim * e);
+    w.V[k] = values ? take(n_bh * len * in->dim * e) : w.K[k];
     w.deg[k] = take(n_bh * len * 4);
   }
   w.total = off;
@@ -108,6 +154,8 @@ int make_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan) {
   if (p->chunk < 2 || p->chunk > 2048 || (p->chunk & 1)) return CKV_EINVAL;
   if (p->n_sink < 0 || p->n_recent < 0) return CKV_EINVAL;
   if (p->scope != CKV_SCOPE_CHUNK && p->scope != CKV_SCOPE_HEAD) return CKV_EINVAL;
+  if (p->flags & ~(uint32_t)(CKV_ROUTE_FULL_ROUNDS | CKV_ROUTE_DEFER_ALWAYS)) return CKV_EINVAL;
+  if ((p->flags & CKV_ROUTE_FULL_ROUNDS) && (p->flags & CKV_ROUTE_DEFER_ALWAYS)) return CKV_EINVAL;
   if (p->n_rounds < 0 || p->n_rounds > CKV_MAX_ROUNDS) return CKV_EINVAL;
   memset(plan, 0, sizeof(*plan));
   if (p->n_rounds > 0) {
@@ -131,7 +179,7 @@ int make_plan(const ckv_layout* in, const ckv_params* p, ckv_plan_t* plan) {
     plan->round_len[j + 1] = seq_after_round(plan->round_len[j], p->chunk, plan->round_r[j], p->n_sink, p->n_recent,
                                              p->scope);
   plan->out_seq = plan->round_len[plan->n_rounds];
-  plan->workspace_bytes = carve(in, plan, p->chunk, p->scope).total;
+  plan->workspace_bytes = carve(in, p, plan).total;
   return CKV_OK;
 }
 
@@ -273,7 +321,9 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     return hip_status(err);
   }
 
-  const Workspace w = carve(in, &plan, p->chunk, p->scope);
+  const Workspace w = carve(in, p, &plan);
+  RoundMode mode[CKV_MAX_ROUNDS];
+  plan_routes(in, p, &plan, mode);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   int32_t* dst = reinterpret_cast<int32_t*>(ws + w.dst);
   float* score = reinterpret_cast<float*>(ws + w.score);
@@ -281,50 +331,16 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
   const void* curV = V;
   const int32_t* curDeg = deg_in;
   TensorView curView = view_of(in);
-  // The single-pass two-round kernel is bit-identical to the round-by-round path but, at one
-  // workgroup per CU, currently slower on MI355X; it runs only when CKV_ENABLE_FUSED=1.
-  const char* fuse_env = getenv("CKV_ENABLE_FUSED");
-  const bool allow_fused = fuse_env && fuse_env[0] == '1';
-  // Deferred values: when round j merges every edge (r = 1) and another round follows, round j
-  // writes keys and degrees only and round j+1 rebuilds the value rows it needs from round j's
-  // value input (bit-identical; the intermediate value cache is neither written nor read).
-  // It pays once the second round has enough workgroups (one per chunk, each rebuilding the values
-  // of 2*chunk original tokens) to fill the chip: from about 4 per CU on MI355X (measured
-  // crossover at 1024 chunks); smaller jobs run every round in full.
-  // CKV_DISABLE_DEFERRED_VALUES=1 runs every round in full, CKV_FORCE_DEFERRED_VALUES=1 defers
-  // whatever the size (both used by the tests to compare the two paths).
-  const char* defer_env = getenv("CKV_DISABLE_DEFERRED_VALUES");
-  const char* force_env = getenv("CKV_FORCE_DEFERRED_VALUES");
-  const bool allow_defer = !(defer_env && defer_env[0] == '1');
-  const bool force_defer = force_env && force_env[0] == '1';
-  const int64_t kDeferMinChunks = 1024;
   int16_t* lists = reinterpret_cast<int16_t*>(ws + w.lists);
   ValueOrigin org{};
-  bool have_org = false;
   const void* edgesV = V;   // where the current cache's sink / recent value rows live
   for (int j = 0; j < plan.n_rounds; ++j) {
     const int len = plan.round_len[j];
-    // rounds j and j+1 in one pass when the first merges every edge and the shape has a kernel
-    // (both two-round routes skip one staging buffer, so from the second round on their result would
-    // land in the buffer their input sits in unless it goes to the caller's output: see defer_ok)
-    const bool fuse = allow_fused && j + 1 < plan.n_rounds && (j == 0 || j + 2 == plan.n_rounds) &&
-                      p->n_sink == 0 && p->n_recent == 0 && curView.deg_stride == len &&
-                      p->scope == CKV_SCOPE_CHUNK &&
-                      fused2_supported(in->dtype, in->dim, p->chunk, len, plan.round_r[j]) &&
-                      curView.stride_s <= (1 << 18) && out->stride_s <= (1 << 18);
-    // From the second round on the pair must end the schedule: its second round reads the value
-    // and degree input of its first, which then sit in the very staging buffers (same parity) that
-    // a non-final round j+1 writes.  A pair that starts at the caller's input has no such overlap.
-    const bool defer_ok = allow_defer && !fuse && !have_org && j + 1 < plan.n_rounds &&
-                          (j == 0 || j + 2 == plan.n_rounds) &&
-                          plan.round_r[j] == 1.0f && p->scope == CKV_SCOPE_CHUNK &&
-                          (force_defer || (int64_t)n_bh * div_up(plan.round_len[j + 1], p->chunk) >= kDeferMinChunks);
-    const int jo = fuse ? j + 1 : j;                 // index of the round whose output is produced
-    const int next = plan.round_len[jo + 1];
-    const bool last = (jo == plan.n_rounds - 1);
-    void* oK = last ? K_out : ws + w.K[jo & 1];
-    void* oV = last ? V_out : ws + w.V[jo & 1];
-    int32_t* oDeg = last ? deg_out : reinterpret_cast<int32_t*>(ws + w.deg[jo & 1]);
+    const int next = plan.round_len[j + 1];
+    const bool last = (j == plan.n_rounds - 1);
+    void* oK = last ? K_out : ws + w.K[j & 1];
+    void* oV = last ? V_out : ws + w.V[j & 1];
+    int32_t* oDeg = last ? deg_out : reinterpret_cast<int32_t*>(ws + w.deg[j & 1]);
     const TensorView oView = last ? view_of(out) : compact_view(in->heads, next, in->dim);
     const int64_t oDegStride = oView.deg_stride;
     int32_t* map = nullptr;
@@ -332,34 +348,29 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     int lo, hi;
     clusterable(len, p->n_sink, p->n_recent, &lo, &hi);
     const int mid = hi - lo;
-    const bool keys_only = defer_ok && mid > 0;
+    const bool keys_only = mode[j] == ROUND_KEYS_ONLY, from_origin = mode[j] == ROUND_ORIGIN;
     hipError_t err = hipSuccess;
-    if (fuse) {
-      err = launch_fused2(curK, curV, curDeg, curView, n_bh, len, plan.round_r[j + 1], oK, oV, oDeg, oView,
-                          oDegStride, map, s);
-    } else {
-      if (mid > 0) {   // cluster tokens [lo, hi): the same kernels on a view that starts at token lo
-        const unsigned char* mK = static_cast<const unsigned char*>(curK) + (size_t)lo * curView.stride_s * e;
-        const unsigned char* mV = static_cast<const unsigned char*>(curV) + (size_t)lo * curView.stride_s * e;
-        err = launch_match(mK, in->dtype, in->dim, curView, n_bh, mid, p->chunk, dst, score, s);
-        if (err != hipSuccess) return hip_status(err);
-        int32_t* sel = nullptr;
-        if (p->scope == CKV_SCOPE_HEAD) {
-          sel = reinterpret_cast<int32_t*>(ws + w.sel);
-          err = launch_global_select(score, n_bh, mid, p->chunk, plan.round_r[j], sel, s);
-          if (err != hipSuccess) return hip_status(err);
-        }
-        err = launch_merge(mK, mV, curDeg ? curDeg + lo : nullptr, in->dtype, in->dim, curView, n_bh, mid, p->chunk,
-                           plan.round_r[j], dst, score, static_cast<unsigned char*>(oK) + (size_t)lo * oView.stride_s * e,
-                           static_cast<unsigned char*>(oV) + (size_t)lo * oView.stride_s * e, oDeg + lo, oView,
-                           oDegStride, map ? map + lo : nullptr, curView.deg_stride, len, lo, sel,
-                           keys_only ? lists : nullptr, have_org ? &org : nullptr, s);
+    if (mid > 0) {   // cluster tokens [lo, hi): the same kernels on a view that starts at token lo
+      const unsigned char* mK = static_cast<const unsigned char*>(curK) + (size_t)lo * curView.stride_s * e;
+      const unsigned char* mV = static_cast<const unsigned char*>(curV) + (size_t)lo * curView.stride_s * e;
+      err = launch_match(mK, in->dtype, in->dim, curView, n_bh, mid, p->chunk, dst, score, s);
+      if (err != hipSuccess) return hip_status(err);
+      int32_t* sel = nullptr;
+      if (p->scope == CKV_SCOPE_HEAD) {
+        sel = reinterpret_cast<int32_t*>(ws + w.sel);
+        err = launch_global_select(score, n_bh, mid, p->chunk, plan.round_r[j], sel, s);
         if (err != hipSuccess) return hip_status(err);
       }
-      if (mid < len)   // sinks and recents (or a cache too short to cluster): straight copy
-        err = launch_edges(curK, edgesV, curDeg, curView, len, oK, oV, oDeg, oView, oDegStride, next, map,
-                           mid > 0 ? lo : len, mid > 0 ? len - hi : 0, n_bh, in->dim * e, e, s);
+      err = launch_merge(mK, mV, curDeg ? curDeg + lo : nullptr, in->dtype, in->dim, curView, n_bh, mid, p->chunk,
+                         plan.round_r[j], dst, score, static_cast<unsigned char*>(oK) + (size_t)lo * oView.stride_s * e,
+                         static_cast<unsigned char*>(oV) + (size_t)lo * oView.stride_s * e, oDeg + lo, oView,
+                         oDegStride, map ? map + lo : nullptr, curView.deg_stride, len, lo, sel,
+                         keys_only ? lists : nullptr, from_origin ? &org : nullptr, s);
+      if (err != hipSuccess) return hip_status(err);
     }
+    if (mid < len)   // sinks and recents (or a cache too short to cluster): straight copy
+      err = launch_edges(curK, edgesV, curDeg, curView, len, oK, oV, oDeg, oView, oDegStride, next, map,
+                         mid > 0 ? lo : len, mid > 0 ? len - hi : 0, n_bh, in->dim * e, e, s);
     if (err != hipSuccess) return hip_status(err);
     if (assign && j > 0) {
       err = launch_compose(assign, map, n_bh, in->seq, len, s);
@@ -368,16 +379,25 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     if (keys_only) {   // the clustered values stay where they are; the next round reads them through the lists
       org = ValueOrigin{static_cast<const unsigned char*>(curV) + (size_t)lo * curView.stride_s * e, curView,
                         curDeg ? curDeg + lo : nullptr, lists, mid, div_up(mid, p->chunk)};
-      have_org = true;
     } else {
       curV = oV;
-      have_org = false;
     }
     edgesV = oV;       // sinks and recents are copied in every round, deferred or not
     curK = oK; curDeg = oDeg; curView = oView;
-    j = jo;
   }
   return CKV_OK;
+}
+
+int32_t ckv_n_sources(int32_t seq, int32_t chunk) {
+  if (seq < 0) return CKV_ESHAPE;
+  if (chunk < 2 || chunk > 2048 || (chunk & 1)) return CKV_EINVAL;
+  return n_sources(seq, chunk);
+}
+
+int32_t ckv_budget_tokens(float cache_ratio, int32_t n) {
+  if (!(cache_ratio > 0.f && cache_ratio <= 1.f)) return CKV_EINVAL;
+  if (n < 0) return CKV_ESHAPE;
+  return (int32_t)((double)cache_ratio * (double)n + 1e-9);
 }
 
 int ckv_schedule_annealed(int32_t seq, int32_t chunk, int32_t n_sink, int32_t n_recent, int32_t scope,
@@ -570,6 +590,14 @@ int ckv_paged_scatter(const void* K, const void* V, const int32_t* deg, const ck
                                                    K_pool, V_pool, deg_pool, block_table, pl->max_blocks, shift,
                                                    pl->n_blocks, keep, old_blocks, freed, lens,
                                                    static_cast<hipStream_t>(hip_stream)));
+}
+
+int32_t ckv_paged_freed_blocks(const ckv_paged_layout* pl, int32_t old_seq, int32_t new_seq) {
+  int shift;
+  int st = check_paged(pl, &shift);
+  if (st != CKV_OK) return st;
+  if (new_seq < 0 || old_seq < new_seq || (int64_t)old_seq > (int64_t)pl->max_blocks * pl->block_size) return CKV_ESHAPE;
+  return ckv::div_up(old_seq, pl->block_size) - ckv::div_up(new_seq, pl->block_size);
 }
 
 namespace {

@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "ckv.h"
 
 namespace ckv {
@@ -95,13 +98,6 @@ hipError_t launch_edges(const void* K, const void* V, const int32_t* deg_in, Ten
                         int32_t* map_out, int n_head, int n_tail, int n_bh, int row_bytes, int elem_bytes,
                         hipStream_t st);
 
-// Two rounds in one pass (first round r = 1, bf16, dim 128, chunk 1024, seq a multiple of 2048):
-// same outputs as launch_match + launch_merge twice; map_out gets the composition of both rounds.
-bool fused2_supported(int dtype, int dim, int chunk, int seq, float r0);
-hipError_t launch_fused2(const void* K, const void* V, const int32_t* deg_in, TensorView in, int n_bh, int seq,
-                         float r1, void* K_out, void* V_out, int32_t* deg_out, TensorView out,
-                         int64_t deg_out_stride, int32_t* map_out, hipStream_t st);
-
 // assign[bh, t] = map[bh, assign[bh, t]] for t < seq0.
 hipError_t launch_compose(int32_t* assign, const int32_t* map, int n_bh, int seq0, int map_len,
                           hipStream_t st);
@@ -112,7 +108,9 @@ hipError_t launch_copy_rows(const void* src, TensorView in, void* dst, TensorVie
 hipError_t launch_fill_deg(const int32_t* deg_in, int64_t in_stride, int32_t* deg_out, int64_t out_stride, int32_t* assign,
                            int n_bh, int seq, hipStream_t st);
 
-// Decode attention: split-K partials then combine.
+// Decode attention: split along the sequence; the slice that finishes last merges the partials.
+// The workspace starts with attn_counter_bytes() of int32 arrival counters that are zero between calls.
+size_t attn_counter_bytes(int n_b, int kv_heads);
 // span_limit > 0 (paged caches): no slice may cover more tokens than that
 int attn_splits(int n_b, int kv_heads, int seq, int span_limit);
 int attn_paged_span_limit(int block_size);
@@ -142,25 +140,33 @@ hipError_t launch_paged_scatter(const void* K, const void* V, const int32_t* deg
 // ---- timing hooks ----------------------------------------------------------------------------
 // One-time set-up of a kernel that needs more than the default dynamic LDS, per device (each device
 // holds its own copy of the code object, so the limit is raised on each one that launches it).
-// `state` is the call site's own table; a concurrent first call sets the same values twice.
+// `state` is the call site's own table; first use on a device happens under its lock, later calls
+// read one atomic flag.
 constexpr int kMaxDevices = 64;
 struct KernelSetup {
-  bool done[kMaxDevices] = {};
-  int n_cu[kMaxDevices] = {};
+  std::mutex lock;
+  std::atomic<bool> done[kMaxDevices];
+  int n_cu[kMaxDevices];
+  KernelSetup() {
+    for (int i = 0; i < kMaxDevices; ++i) { done[i].store(false, std::memory_order_relaxed); n_cu[i] = 0; }
+  }
 };
 inline hipError_t kernel_setup(const void* kernel, size_t dynamic_lds, KernelSetup& state, int* n_cu = nullptr) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-  if (!state.done[dev]) {
-    int v = 0;
-    e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dynamic_lds);
-    if (e != hipSuccess) return e;
-    state.n_cu[dev] = v > 0 ? v : 256;
-    state.done[dev] = true;
+  if (!state.done[dev].load(std::memory_order_acquire)) {
+    std::lock_guard<std::mutex> g(state.lock);
+    if (!state.done[dev].load(std::memory_order_relaxed)) {
+      int v = 0;
+      e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e == hipSuccess)
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dynamic_lds);
+      if (e != hipSuccess) return e;
+      state.n_cu[dev] = v > 0 ? v : 256;
+      state.done[dev].store(true, std::memory_order_release);
+    }
   }
   if (n_cu) *n_cu = state.n_cu[dev];
   return hipSuccess;

@@ -2,8 +2,11 @@
 //   o_h = softmax(q_h K^T * scale + ln N) V,   one query token, G query heads per KV head.
 // Split along the sequence: every workgroup streams a contiguous slice of K and V once with
 // 16-byte loads (one row per group of row_bytes/16 lanes), serves all G query heads of its KV head
-// from registers, keeps an online softmax in the exp2 domain, and writes (max, sum, o) partials;
-// a second small kernel merges the partials with the usual log-sum-exp rescaling.
+// from registers, keeps an online softmax in the exp2 domain, and writes (max, sum, o) partials.
+// The slice that finishes last for a (batch, KV head) - found with one counter word per pair in
+// the workspace, which that workgroup puts back to zero - merges the partials of all slices with
+// the usual log-sum-exp rescaling, in slice order, so the result does not depend on which one that
+// is.  One launch per call; nothing in it is a memset.
 #include <type_traits>
 
 #include "ckv_internal.h"
@@ -92,6 +95,18 @@ __device__ inline uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
+// Partial results travel between workgroups that may sit on different XCDs (each with its own L2)
+// inside one launch.  They are written and read with device-scope relaxed atomic accesses, which go
+// through to the level all XCDs share, instead of plain accesses bracketed by device-scope fences:
+// such a fence writes back / invalidates a whole L2, and one per workgroup cost this kernel a
+// factor of three.
+__device__ __forceinline__ void store_shared_f32(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_shared_f32(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // 2^x for x <= 0 as the bare hardware instruction (1 ulp; results below 2^-126 come out as zero).
 // The library routine wraps it in a range fix-up for denormal results, five more instructions per
 // call, which in the streaming loop is a fifth of all vector work and buys nothing for a softmax weight.
@@ -105,6 +120,7 @@ __device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp
 // the first use (bytes in flight hide HBM latency), the logits of the kUnroll tokens share one
 // running-max update, so the accumulators are rescaled once per kUnroll tokens.
 constexpr int kUnroll = 4;
+constexpr int kMaxSplits = 1024;    // slices per sequence: the merge keeps one weight per slice and head in LDS
 constexpr int kMaxTableLds = 2048;   // block-table entries of one slice kept in LDS (paged caches)
 
 // PAGED: K, V are a block pool [n_blocks, heads, block_size, dim] (kv.stride_s = dim, kv.stride_h =
@@ -115,7 +131,8 @@ template <typename T, int D, int G, bool PAGED>
 __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
     const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V, TensorView kv, int kv_heads,
     int seq, const int32_t* __restrict__ lens, const int32_t* __restrict__ deg, float scale_log2e,
-    int n_splits, int span, float* __restrict__ o_part, float* __restrict__ ml_part, PagedView paged) {
+    int n_splits, int span, float* __restrict__ o_part, float* __restrict__ ml_part,
+    int32_t* __restrict__ arrived, void* __restrict__ o, int o_dtype, PagedView paged) {
   constexpr int E = Elems<T>::E;
   constexpr int LPR = D / E;
   constexpr int NRG = kThreads / LPR;
@@ -123,7 +140,10 @@ __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
   __shared__ float s_m[NRG][G];
   __shared__ float s_l[NRG][G];
   constexpr int GG = (G < 4) ? G : 4;   // query heads merged per pass of the final reduction
-  __shared__ float s_o[GG][NRG][D];
+  // staging rows of the workgroup's reduction; later the slice weights [G][kMaxSplits] of the merge
+  constexpr int kStageFloats = GG * NRG * D, kWeightFloats = G * kMaxSplits;
+  __shared__ float s_raw[kStageFloats > kWeightFloats ? kStageFloats : kWeightFloats];
+  float (*s_o)[NRG][D] = reinterpret_cast<float (*)[NRG][D]>(s_raw);
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, rg = tid / LPR, piece = tid % LPR;
@@ -268,7 +288,7 @@ __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
       const int gg = idx / D, d = idx % D;
       float sum = 0.f;
       for (int r2 = 0; r2 < NRG; ++r2) sum += s_o[gg][r2][d];
-      o_part[(pbase + g0 + gg) * D + d] = sum;
+      store_shared_f32(&o_part[(pbase + g0 + gg) * D + d], sum);
     }
     if (tid < GG) {
       const int g = g0 + tid;
@@ -278,77 +298,89 @@ __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
         const float mr = s_m[r2][g];
         L += (mr == -INFINITY) ? 0.f : s_l[r2][g] * exp2f(mr - M);
       }
-      ml_part[(pbase + g) * 2] = M;
-      ml_part[(pbase + g) * 2 + 1] = L;
+      store_shared_f32(&ml_part[(pbase + g) * 2], M);
+      store_shared_f32(&ml_part[(pbase + g) * 2 + 1], L);
     }
   }
-}
 
-// Merge the split partials of one (batch, query head): weights exp2(m_s - M) are computed once
-// into LDS by the first n_splits threads, then every thread owns one output channel and sums
-// over splits with independent (unrolled) loads.
-constexpr int kMaxSplits = 1024;
-template <int G>
-__global__ void attn_combine_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
-                                    int kv_heads, int n_splits, int dim, void* __restrict__ o, int o_dtype) {
-  __shared__ float s_w[kMaxSplits];
-  __shared__ float s_l[kMaxSplits];
-  __shared__ float s_red[2][4];
-  const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-  const int kvh = hq / G, g = hq % G;
-  const int64_t pbase = ((int64_t)b * kv_heads + kvh) * n_splits;
-  const int lane = d & 63, wave = d >> 6, n_waves = blockDim.x >> 6;
-  // the first partial rows of this thread's channel are requested before anything else: they do
-  // not depend on the weights, and their latency hides behind the two reductions below
-  constexpr int kAhead = 16;
-  const bool live = d < dim;
-  const float* op = o_part + (pbase * G + g) * dim + (live ? d : 0);
-  const int64_t pitch = (int64_t)G * dim;
-  float ahead[kAhead];
-#pragma unroll
-  for (int i = 0; i < kAhead; ++i) ahead[i] = op[min(i, n_splits - 1) * pitch];   // clamped: always a valid row
-  const float2* ml = reinterpret_cast<const float2*>(ml_part);
-  float mloc = -INFINITY;
-  for (int s = d; s < n_splits; s += blockDim.x) {
-    const float2 v = ml[(pbase + s) * G + g];      // (max, sum of exponentials) of split s
-    s_w[s] = v.x;
-    s_l[s] = v.y;
-    mloc = fmaxf(mloc, v.x);
-  }
-#pragma unroll
-  for (int sh = 32; sh > 0; sh >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, sh));
-  if (lane == 0) s_red[0][wave] = mloc;
+  // ---- the last slice of this (batch, KV head) to arrive merges them all ----------------------
+  // Every thread waits until its own partial stores have been acknowledged, the workgroup meets,
+  // and one thread counts the workgroup in; the workgroup that finds all others counted takes the
+  // merge.  The counter is only ever touched with device-scope atomics.
+  __shared__ int s_is_last;
+  __builtin_amdgcn_s_waitcnt(0);          // vmcnt = lgkmcnt = expcnt = 0: the stores above are complete
   __syncthreads();
-  float M = -INFINITY;
-  for (int w2 = 0; w2 < n_waves; ++w2) M = fmaxf(M, s_red[0][w2]);
-  float dloc = 0.f;
-  for (int s = d; s < n_splits; s += blockDim.x) {
-    const float ms = s_w[s];
-    const float f = (ms == -INFINITY) ? 0.f : exp2f(ms - M);
-    s_w[s] = f;
-    dloc += f * s_l[s];
-  }
-#pragma unroll
-  for (int sh = 32; sh > 0; sh >>= 1) dloc += __shfl_xor(dloc, sh);
-  if (lane == 0) s_red[1][wave] = dloc;
+  int32_t* my_count = arrived + (b * kv_heads + kvh);
+  if (tid == 0) s_is_last = (atomicAdd(my_count, 1) == n_splits - 1);
   __syncthreads();
-  float den = 0.f;
-  for (int w2 = 0; w2 < n_waves; ++w2) den += s_red[1][w2];
-  if (!live) return;
-  float num = 0.f;
+  if (!s_is_last) return;
+  // weights of the slices, per query head: a wave takes a head (two for G = 8)
+  float* s_w = s_raw;                     // [G][kMaxSplits] (the staging rows are no longer needed)
+  float* s_den = &s_l[0][0];              // [G]
+  const int lane = tid & 63, wave = tid >> 6;
+  const int64_t sbase = ((int64_t)b * kv_heads + kvh) * n_splits;
+  for (int g = wave; g < G; g += kThreads / 64) {
+    float mloc = -INFINITY;
+    for (int sp = lane; sp < n_splits; sp += 64) mloc = fmaxf(mloc, load_shared_f32(&ml_part[((sbase + sp) * G + g) * 2]));
 #pragma unroll
-  for (int i = 0; i < kAhead; ++i) num = fmaf(ahead[i], (i < n_splits) ? s_w[i] : 0.f, num);
-  for (int s0 = kAhead; s0 < n_splits; s0 += kAhead) {
-    float x[kAhead];
+    for (int sh = 32; sh > 0; sh >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, sh));
+    float dloc = 0.f;
+    for (int sp = lane; sp < n_splits; sp += 64) {
+      const float ms = load_shared_f32(&ml_part[((sbase + sp) * G + g) * 2]);       // max of slice sp
+      const float ls = load_shared_f32(&ml_part[((sbase + sp) * G + g) * 2 + 1]);   // its sum of exponentials
+      const float f = (ms == -INFINITY) ? 0.f : exp2f(ms - mloc);
+      s_w[g * kMaxSplits + sp] = f;
+      dloc += f * ls;
+    }
 #pragma unroll
-    for (int i = 0; i < kAhead; ++i) x[i] = op[min(s0 + i, n_splits - 1) * pitch];
-#pragma unroll
-    for (int i = 0; i < kAhead; ++i) num = fmaf(x[i], (s0 + i < n_splits) ? s_w[s0 + i] : 0.f, num);
+    for (int sh = 32; sh > 0; sh >>= 1) dloc += __shfl_xor(dloc, sh);
+    if (lane == 0) s_den[g] = dloc;
   }
-  const float res = den > 0.f ? num / den : 0.f;
-  const int64_t oi = ((int64_t)b * kv_heads * G + hq) * dim + d;
-  if (o_dtype == CKV_BF16) reinterpret_cast<uint16_t*>(o)[oi] = f32_to_bf16_rne(res);
-  else reinterpret_cast<float*>(o)[oi] = res;
+  __syncthreads();
+  // Every thread owns NC (head, channel) columns, consecutive threads consecutive channels (a wave's
+  // load is 256 contiguous bytes), and sums them over the slices in slice order: blocks of 32
+  // slices with all NC * 32 loads in flight, then blocks of 8, then single slices.  Which
+  // workgroup runs this never changes the order, so the bits are the same from run to run.
+  constexpr int NC = (G * D + kThreads - 1) / kThreads;
+  float num[NC];
+  const float* col[NC];
+  const float* wcol[NC];
+#pragma unroll
+  for (int k = 0; k < NC; ++k) {
+    const int c = min(tid + k * kThreads, G * D - 1);        // clamped: threads past the last column repeat it
+    num[k] = 0.f;
+    col[k] = o_part + (sbase * G + c / D) * D + c % D;
+    wcol[k] = s_w + (c / D) * kMaxSplits;
+  }
+  const int64_t pitch = (int64_t)G * D;
+  auto block = [&](int s0, auto n_c) {
+    constexpr int N = decltype(n_c)::value;
+    float x[NC][N];
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+#pragma unroll
+      for (int k = 0; k < NC; ++k) x[k][i] = load_shared_f32(col[k] + (int64_t)(s0 + i) * pitch);
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+#pragma unroll
+      for (int k = 0; k < NC; ++k) num[k] = fmaf(x[k][i], wcol[k][s0 + i], num[k]);
+  };
+  int s0 = 0;
+  for (; s0 + 32 <= n_splits; s0 += 32) block(s0, std::integral_constant<int, 32>{});
+  for (; s0 + 8 <= n_splits; s0 += 8) block(s0, std::integral_constant<int, 8>{});
+  for (; s0 < n_splits; ++s0) block(s0, std::integral_constant<int, 1>{});
+#pragma unroll
+  for (int k = 0; k < NC; ++k) {
+    const int c = tid + k * kThreads;
+    if (c < G * D) {
+      const float den = s_den[c / D];
+      const float res = den > 0.f ? num[k] / den : 0.f;
+      const int64_t oi = ((int64_t)b * kv_heads + kvh) * G * D + c;
+      if (o_dtype == CKV_BF16) reinterpret_cast<uint16_t*>(o)[oi] = f32_to_bf16_rne(res);
+      else reinterpret_cast<float*>(o)[oi] = res;
+    }
+  }
+  if (tid == 0) atomicExch(my_count, 0);  // the workspace is ready for the next call
 }
 
 template <typename T, int D, int G>
@@ -358,25 +390,22 @@ hipError_t launch_attn_t(const void* q, const void* K, const void* V, TensorView
   const int n_splits = attn_splits(n_b, kv_heads, seq, paged.table ? (kMaxTableLds << paged.shift) : 0);
   const int span = div_up(seq, n_splits);
   if (paged.table && span > (kMaxTableLds << paged.shift)) return hipErrorInvalidValue;
-  float* o_part = static_cast<float*>(workspace);
+  // workspace: arrival counters (one per (batch, KV head), zero between calls) | partial outputs | (max, sum) pairs
+  int32_t* arrived = static_cast<int32_t*>(workspace);
+  float* o_part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + attn_counter_bytes(n_b, kv_heads));
   float* ml_part = o_part + (size_t)n_b * kv_heads * n_splits * G * D;
-  {
-    ScopedTimer t(paged.table ? (sizeof(T) == 2 ? "attn_partial_paged_bf16" : "attn_partial_paged_f32")
-                              : (sizeof(T) == 2 ? "attn_partial_bf16" : "attn_partial_f32"), st);
-    if (paged.table)
-      hipLaunchKernelGGL((attn_partial_kernel<T, D, G, true>), dim3(n_splits, kv_heads, n_b), dim3(kThreads), 0,
-                         st, static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), kv,
-                         kv_heads, seq, lens, deg, scale * kLog2e, n_splits, span, o_part, ml_part, paged);
-    else
-      hipLaunchKernelGGL((attn_partial_kernel<T, D, G, false>), dim3(n_splits, kv_heads, n_b), dim3(kThreads), 0,
-                         st, static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), kv,
-                         kv_heads, seq, lens, deg, scale * kLog2e, n_splits, span, o_part, ml_part, paged);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  ScopedTimer t("attn_combine", st);
-  hipLaunchKernelGGL((attn_combine_kernel<G>), dim3(kv_heads * G, n_b), dim3(D < 64 ? 64 : D), 0, st, o_part,
-                     ml_part, kv_heads, n_splits, D, o, o_dtype);
+  ScopedTimer t(paged.table ? (sizeof(T) == 2 ? "attn_paged_bf16" : "attn_paged_f32")
+                            : (sizeof(T) == 2 ? "attn_bf16" : "attn_f32"), st);
+  if (paged.table)
+    hipLaunchKernelGGL((attn_partial_kernel<T, D, G, true>), dim3(n_splits, kv_heads, n_b), dim3(kThreads), 0,
+                       st, static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), kv,
+                       kv_heads, seq, lens, deg, scale * kLog2e, n_splits, span, o_part, ml_part, arrived, o, o_dtype,
+                       paged);
+  else
+    hipLaunchKernelGGL((attn_partial_kernel<T, D, G, false>), dim3(n_splits, kv_heads, n_b), dim3(kThreads), 0,
+                       st, static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), kv,
+                       kv_heads, seq, lens, deg, scale * kLog2e, n_splits, span, o_part, ml_part, arrived, o, o_dtype,
+                       paged);
   return hipGetLastError();
 }
 
@@ -400,20 +429,24 @@ int attn_splits(int n_b, int kv_heads, int seq, int span_limit) {
   const int64_t bh = (int64_t)n_b * kv_heads;
   int want = (int)((512 + bh - 1) / bh);
   int cap = (seq + 255) / 256;
-  if (cap > 1024) cap = 1024;   // the combine kernel keeps one weight per split in LDS
+  if (cap > kMaxSplits) cap = kMaxSplits;   // the merge keeps one weight per slice in LDS
   if (want > cap) want = cap;
   if (want < 1) want = 1;
   // paged caches: a slice's block-table entries must fit the kernel's LDS table
   if (span_limit > 0 && (seq + want - 1) / want > span_limit) want = (seq + span_limit - 1) / span_limit;
-  if (want > 1024) want = 1024;
+  if (want > kMaxSplits) want = kMaxSplits;
   return want;
 }
+
+size_t attn_counter_bytes(int n_b, int kv_heads) { return ((size_t)n_b * kv_heads * sizeof(int32_t) + 255) / 256 * 256; }
 
 int attn_paged_span_limit(int block_size) { return kMaxTableLds * block_size; }
 
 size_t attn_workspace_bytes(int n_b, int kv_heads, int q_heads, int dim, int seq, int span_limit) {
+  // one arrival counter per (batch, KV head), then partial outputs and (max, sum) pairs per
+  // (batch, query head, slice)
   const size_t rows = (size_t)n_b * q_heads * attn_splits(n_b, kv_heads, seq, span_limit);
-  return rows * (dim + 2) * sizeof(float);
+  return attn_counter_bytes(n_b, kv_heads) + rows * (dim + 2) * sizeof(float);
 }
 
 hipError_t launch_decode_attn(const void* q, int q_heads, const void* K, const void* V, int dtype, int dim,

@@ -9,7 +9,8 @@ from typing import Optional, Sequence
 
 import torch
 
-from . import append, compress, decode_attn, decode_attn_workspace, layout_of, make_params, plan, schedule_annealed
+from . import (append, budget_tokens, compress, decode_attn, decode_attn_workspace, layout_of, make_params, plan,
+               schedule_annealed)
 
 
 class OnlineCache:
@@ -23,7 +24,7 @@ class OnlineCache:
         Eq. 4 restarts with each clustering episode)."""
         B, H, n, D = K.shape
         self.chunk, self.g, self.n_sink, self.n_recent = chunk, g, n_sink, n_recent
-        self.budget = int(cache_ratio * n + 1e-9)
+        self.budget = budget_tokens(cache_ratio, n)
         self.r_decode = list(r_decode) if r_decode else [r_init]
         self.capacity = max(self.budget + g, 1)
         self.rounds_prefill = schedule_annealed(n, chunk, self.budget, r_init, delta_r, r_floor, n_sink, n_recent)
@@ -38,7 +39,7 @@ class OnlineCache:
         one_round = make_params(chunk, rounds=[1.0], n_sink=n_sink, n_recent=n_recent)
         self.ws_round = torch.empty(max(plan(layout_of(full), one_round).workspace_bytes, 256), dtype=torch.uint8,
                                     device=K.device)
-        self.ws_attn = torch.empty(decode_attn_workspace(layout_of(full), q_heads), dtype=torch.uint8,
+        self.ws_attn = torch.zeros(decode_attn_workspace(layout_of(full), q_heads), dtype=torch.uint8,
                                    device=K.device)
         cK, cV, cdeg = self.bufs[0]
         if self.rounds_prefill:

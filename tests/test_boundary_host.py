@@ -192,3 +192,47 @@ def test_entry_points_reject_null_and_misaligned_pointers_before_any_launch():
     assert L.ckv_match(z, C.byref(lay), 256, z, z, z) == -1
     assert L.ckv_match(C.c_void_p(8), C.byref(lay), 256, C.c_void_p(16), C.c_void_p(16), z) == -3
     assert L.ckv_match(C.c_void_p(16), C.byref(lay), 251, C.c_void_p(16), C.c_void_p(16), z) == -1   # odd chunk
+
+
+def test_host_helpers_for_sizes_the_binding_no_longer_computes():
+    L = ckv.lib()
+    for seq, chunk in [(0, 2), (1, 2), (1000, 64), (131072, 1024), (2049, 2048), (77, 16)]:
+        want = sum((min(chunk, seq - g0) + 1) // 2 for g0 in range(0, seq, chunk))      # ceil(L/2) per chunk (Sec. 5.2)
+        assert L.ckv_n_sources(seq, chunk) == want
+    assert L.ckv_n_sources(100, 3) == -1 and L.ckv_n_sources(-1, 4) == -2
+    # Algorithm 1: B = floor(R * n); the paper's 25% budget of its 128k prompts; exact products stay exact
+    assert ckv.budget_tokens(0.25, 131072) == 32768
+    assert ckv.budget_tokens(0.3, 10) == 3 and ckv.budget_tokens(0.6, 5) == 3 and ckv.budget_tokens(1.0, 7) == 7
+    assert ckv.budget_tokens(0.999, 1000) == 999
+    assert L.ckv_budget_tokens(0.0, 10) == -1 and L.ckv_budget_tokens(1.5, 10) == -1 and L.ckv_budget_tokens(0.5, -1) == -2
+    pl = ckv.PagedLayout(2, 8, 128, ckv.BF16, 16, 300, 1000)
+    assert L.ckv_paged_freed_blocks(C.byref(pl), 4176, 1100) == 261 - 69
+    assert L.ckv_paged_freed_blocks(C.byref(pl), 16, 16) == 0 and L.ckv_paged_freed_blocks(C.byref(pl), 17, 16) == 1
+    assert L.ckv_paged_freed_blocks(C.byref(pl), 10, 11) == -2 and L.ckv_paged_freed_blocks(C.byref(pl), 4801, 1) == -2
+
+
+def test_route_flags_size_the_workspace_and_reject_nonsense():
+    """A deferred pair at the start of the schedule without sinks / recents needs no intermediate
+    value cache: the plan for it is smaller by exactly that cache (the route flags change kernels
+    and scratch, never lengths)."""
+    lay = _lay(batch=32, heads=8, seq=131072)
+    full = ckv.plan(lay, ckv.make_params(1024, 0.25, route="full_rounds"))
+    auto = ckv.plan(lay, ckv.make_params(1024, 0.25))
+    forced = ckv.plan(lay, ckv.make_params(1024, 0.25, route="defer_always"))
+    assert full.round_len == auto.round_len == forced.round_len == [131072, 65536, 32768]
+    lists = 256 * 128 * 3 * 512 * 2
+    assert full.workspace_bytes - auto.workspace_bytes == 256 * 65536 * 128 * 2 - lists
+    assert auto.workspace_bytes == forced.workspace_bytes
+    small = _lay(seq=8192)          # 16 chunks in the second round: too small to defer unless asked to
+    assert ckv.plan(small, ckv.make_params(1024, 0.25)).workspace_bytes == \
+        ckv.plan(small, ckv.make_params(1024, 0.25, route="full_rounds")).workspace_bytes
+    assert ckv.plan(small, ckv.make_params(1024, 0.25, route="defer_always")).workspace_bytes < \
+        ckv.plan(small, ckv.make_params(1024, 0.25)).workspace_bytes
+    # sinks / recents keep the staging value cache (their rows are copied in every round)
+    with_edges = ckv.plan(lay, ckv.make_params(1024, 0.25, n_sink=16, n_recent=64))
+    assert with_edges.workspace_bytes > auto.workspace_bytes + 256 * 60000 * 128 * 2
+    p = ckv.make_params(1024, 0.25)
+    p.flags = 3
+    assert ckv.lib().ckv_plan(C.byref(lay), C.byref(p), C.byref(ckv.PlanT())) == -1
+    p.flags = 8
+    assert ckv.lib().ckv_plan(C.byref(lay), C.byref(p), C.byref(ckv.PlanT())) == -1

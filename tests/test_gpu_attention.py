@@ -123,7 +123,7 @@ def test_decode_loop_can_be_captured_in_a_hip_graph():
     deg = torch.from_numpy(rng.integers(1, 6, (Ly, Hkv, L + 1)).astype(np.int32)).to(DEV)
     q = query_host(9, Ly, Hkv * G, D, "bf16").to(DEV).reshape(Ly, 1, Hkv * G, D)
     k_new, v_new = K[:, :, L].clone(), V[:, :, L].clone()
-    ws = torch.empty(ckv.decode_attn_workspace(ckv.layout_of(K[0:1]), Hkv * G), dtype=torch.uint8, device=DEV)
+    ws = torch.zeros(ckv.decode_attn_workspace(ckv.layout_of(K[0:1]), Hkv * G), dtype=torch.uint8, device=DEV)
     o = torch.empty((Ly, 1, Hkv * G, D), dtype=torch.float32, device=DEV)
 
     def step():

@@ -12,6 +12,11 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
+def _compress(route, *args, **kw):
+    """ckv.compress on a named kernel route (the routes give the same bits)."""
+    return ckv.compress(*args, route=route, **kw)
+
+
 def _say(msg):
     print(msg, flush=True)
 
@@ -380,13 +385,8 @@ def test_large_incoming_degrees():
     d[0, 1, 2990:] = 100000
     deg = torch.from_numpy(d.astype(np.int32)).to(DEV)
     fK, fV, fdeg, _ = _run_rounds_teacher_forced(K, V, chunk, [1.0, 0.7], "large degrees", deg=deg)
-    import os
-    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"
-    try:
-        gK, gV, gdeg, _ = ckv.compress(K, V, chunk, rounds=[1.0, 0.7], deg=deg)        # deferred pair
-        torch.cuda.synchronize()
-    finally:
-        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
+    gK, gV, gdeg, _ = _compress("defer_always", K, V, chunk, rounds=[1.0, 0.7], deg=deg)        # deferred pair
+    torch.cuda.synchronize()
     assert torch.equal(gK, fK) and torch.equal(gV, fV) and torch.equal(gdeg, fdeg)
     assert int(gdeg.sum()) == int(d.sum())
 
@@ -447,68 +447,6 @@ def test_runtime_argument_errors():
     assert e.value.status == -5                                  # head_dim without a kernel
 
 
-# ---- the two-rounds-in-one-pass kernel ----------------------------------------------------------
-@pytest.mark.parametrize("rounds,use_deg", [
-    ([1.0, 1.0], False),
-    ([1.0, 0.5], False),
-    ([1.0, 0.0], False),
-    ([1.0, 1.0, 1.0], False),          # fused pair + a third separate round
-    ([0.5, 1.0, 1.0], False),          # fused pair fed by a separate round (incoming degrees > 1)
-    ([1.0, 0.7], True),
-    ([0.5, 1.0, 1.0, 1.0], False),     # no pair in the middle of a schedule (staging buffers alternate): the last two
-    ([1.0, 1.0, 1.0, 1.0, 0.5], False),
-])
-def test_fused_two_round_kernel_is_bit_identical_to_separate_rounds(rounds, use_deg):
-    """With CKV_ENABLE_FUSED=1, chunk 1024 / bf16 / dim 128 / length a multiple of 2048 and a first
-    round with r = 1 take the single-pass kernel; it must reproduce the round-by-round path bit
-    for bit (and that path is checked against the oracle above)."""
-    import os
-    _say(f"fused2 rounds={rounds} deg={use_deg}")
-    seq = {3: 8192, 4: 16384, 5: 32768}.get(len(rounds), 4096) if len(rounds) > 3 or rounds[0] != 1.0 else 4096
-    K, V, _ = kv_host(21, 3, seq, 128, "bf16", alpha=0.9, n_outlier=4)
-    K, V = K.to(DEV), V.to(DEV)
-    deg = None
-    if use_deg:
-        deg = torch.from_numpy(np.random.default_rng(1).integers(1, 6, (1, 3, seq)).astype(np.int32)).to(DEV)
-    ref = ckv.compress(K, V, 1024, rounds=rounds, deg=deg)
-    os.environ["CKV_ENABLE_FUSED"] = "1"
-    try:
-        got = ckv.compress(K, V, 1024, rounds=rounds, deg=deg)
-        # the fused kernel really ran: its name shows up in the library's kernel timing
-        ckv.timing_reset()
-        ckv.timing_enable(True)
-        ckv.compress(K, V, 1024, rounds=rounds, deg=deg)
-        torch.cuda.synchronize()
-        ckv.timing_enable(False)
-        assert "fused2_bf16" in ckv.timing_read()
-    finally:
-        del os.environ["CKV_ENABLE_FUSED"]
-    torch.cuda.synchronize()
-    names = ["K'", "V'", "deg'", "assign"]
-    for n, a, b in zip(names, got, ref):
-        assert a.shape == b.shape, n
-        assert torch.equal(a, b), f"{n} differs between the fused and the round-by-round path"
-
-
-def test_fused_kernel_on_duplicate_keys():
-    _say("fused2 duplicate keys")
-    k = torch.randn(128, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
-    K = k.repeat(1, 1, 4096, 1).contiguous().to(DEV)
-    V = torch.randn((1, 1, 4096, 128), generator=torch.Generator().manual_seed(6)).to(torch.bfloat16).to(DEV)
-    import os
-    os.environ["CKV_ENABLE_FUSED"] = "1"
-    try:
-        gK, gV, gdeg, gas = ckv.compress(K, V, 1024, retain_ratio=0.25)
-        torch.cuda.synchronize()
-    finally:
-        del os.environ["CKV_ENABLE_FUSED"]
-    assert torch.equal(gK, k.to(DEV).expand_as(gK))
-    ref = oracle.compress(f64(K[0, 0]), f64(V[0, 0]), 1024, [1.0, 1.0], "bf16")
-    assert np.array_equal(i64(gas[0, 0]), ref["assign"])
-    assert np.array_equal(i64(gdeg[0, 0]), ref["deg"])
-    assert np.array_equal(f64(gV[0, 0]), ref["V"])
-
-
 # ---- deferred values: rounds after an r = 1 round rebuild their value rows from the original cache ----
 @pytest.mark.parametrize("dtype,heads,seq,dim,chunk,rounds,use_deg,n_sink,n_recent", [
     ("bf16", 3, 8192, 128, 1024, [1.0, 1.0], False, 0, 0),
@@ -535,9 +473,8 @@ def test_deferred_values_are_bit_identical_to_full_rounds(dtype, heads, seq, dim
                                                           n_recent):
     """By default a round that merges every edge (r = 1) and is followed by another writes keys and
     degrees only, and the next round rebuilds the value rows it needs from the original values.
-    With CKV_DISABLE_DEFERRED_VALUES=1 every round runs in full; both must give the same bits (the
+    On the "full_rounds" route every round runs in full; both must give the same bits (the
     full rounds are checked against the oracle above)."""
-    import os
     _say(f"deferred values {dtype} H={heads} S={seq} D={dim} c={chunk} rounds={rounds} deg={use_deg} "
          f"n1={n_sink} n2={n_recent}")
     kw = dict(n_sink=n_sink, n_recent=n_recent)
@@ -546,28 +483,20 @@ def test_deferred_values_are_bit_identical_to_full_rounds(dtype, heads, seq, dim
     deg = None
     if use_deg:
         deg = torch.from_numpy(np.random.default_rng(2).integers(1, 7, (1, heads, seq)).astype(np.int32)).to(DEV)
-    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"      # small inputs would otherwise run every round in full
-    try:
-        ckv.timing_reset()
-        ckv.timing_enable(True)
-        got = ckv.compress(K, V, chunk, rounds=rounds, deg=deg, **kw)
-        torch.cuda.synchronize()
-        ckv.timing_enable(False)
-        names = ckv.timing_read()
-    finally:
-        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
+    ckv.timing_reset()
+    ckv.timing_enable(True)
+    got = _compress("defer_always", K, V, chunk, rounds=rounds, deg=deg, **kw)
+    torch.cuda.synchronize()
+    ckv.timing_enable(False)
+    names = ckv.timing_read()
     suffix = "bf16" if dtype == "bf16" else "f32"
     assert f"merge_keys_{suffix}" in names and f"merge_origin_{suffix}" in names      # the deferred path really ran
-    os.environ["CKV_DISABLE_DEFERRED_VALUES"] = "1"
-    try:
-        ckv.timing_reset()
-        ckv.timing_enable(True)
-        ref = ckv.compress(K, V, chunk, rounds=rounds, deg=deg, **kw)
-        torch.cuda.synchronize()
-        ckv.timing_enable(False)
-        assert f"merge_keys_{suffix}" not in ckv.timing_read()
-    finally:
-        del os.environ["CKV_DISABLE_DEFERRED_VALUES"]
+    ckv.timing_reset()
+    ckv.timing_enable(True)
+    ref = _compress("full_rounds", K, V, chunk, rounds=rounds, deg=deg, **kw)
+    torch.cuda.synchronize()
+    ckv.timing_enable(False)
+    assert f"merge_keys_{suffix}" not in ckv.timing_read()
     for n, a, b in zip(["K'", "V'", "deg'", "assign"], got, ref):
         assert a.shape == b.shape, n
         assert torch.equal(a, b), f"{n} differs between deferred and full rounds"
@@ -585,12 +514,7 @@ def test_deferred_values_with_strided_input_and_padded_output():
     oV = torch.zeros_like(oK)
     odeg = torch.zeros((B, H, out_len + 24), dtype=torch.int32, device=DEV)
     oas = torch.empty((B, H, S), dtype=torch.int32, device=DEV)
-    import os
-    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"
-    try:
-        ckv.compress(K, V, c, retain_ratio=0.25, out=(oK, oV, odeg, oas))
-    finally:
-        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
+    _compress("defer_always", K, V, c, retain_ratio=0.25, out=(oK, oV, odeg, oas))
     ref = ckv.compress(K.contiguous(), V.contiguous(), c, rounds=[1.0])
     ref = ckv.compress(ref[0], ref[1], c, rounds=[1.0], deg=ref[2])         # two full single-round calls
     torch.cuda.synchronize()
@@ -608,21 +532,12 @@ def test_deferred_values_with_long_clusters(dtype, seq, dim, chunk, n_proto, rou
     """Keys from a handful of directions: tens of tokens join one centroid in the first round and
     several such centroids merge in the second, so the origin-mode rebuild walks long member lists
     at both levels.  Same bits as the full rounds, which are also checked against the oracle."""
-    import os
     from synth.kv import prototype_kv_host
     _say(f"deferred values, long clusters {dtype} S={seq} D={dim} c={chunk} directions={n_proto} rounds={rounds}")
     K, V = prototype_kv_host(61, 2, seq, dim, dtype, n_proto)
     K, V = K.to(DEV), V.to(DEV)
-    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"
-    try:
-        got = ckv.compress(K, V, chunk, rounds=rounds)
-    finally:
-        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
-    os.environ["CKV_DISABLE_DEFERRED_VALUES"] = "1"
-    try:
-        ref = ckv.compress(K, V, chunk, rounds=rounds)
-    finally:
-        del os.environ["CKV_DISABLE_DEFERRED_VALUES"]
+    got = _compress("defer_always", K, V, chunk, rounds=rounds)
+    ref = _compress("full_rounds", K, V, chunk, rounds=rounds)
     torch.cuda.synchronize()
     for n, a, b in zip(["K'", "V'", "deg'", "assign"], got, ref):
         assert torch.equal(a, b), f"{n} differs between deferred and full rounds"
@@ -668,30 +583,26 @@ def test_calls_on_separate_streams_do_not_disturb_one_another():
 def test_compress_can_be_captured_in_a_hip_graph():
     """A whole compression (three rounds, sinks / recents, deferred pair) recorded into a HIP graph:
     every replay, with the outputs cleared and eager work in between, gives the eager bits."""
-    import os
     _say("compress in a HIP graph")
     heads, seq, chunk, rounds = 4, 8192 + 80, 512, [1.0, 1.0, 0.5]
     K, V, _ = kv_host(81, heads, seq, 128, "bf16", alpha=0.9, n_outlier=4)
     K, V = K.to(DEV), V.to(DEV)
     kw = dict(rounds=rounds, n_sink=16, n_recent=64)
-    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"
-    try:
-        ref = ckv.compress(K, V, chunk, **kw)
-        torch.cuda.synchronize()
-        out = tuple(torch.zeros_like(t) for t in ref)
-        plan = ckv.plan(ckv.layout_of(K), ckv.make_params(chunk, rounds=rounds, n_sink=16, n_recent=64))
-        ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=DEV)
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            ckv.compress(K, V, chunk, out=out, workspace=ws, **kw)
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            ckv.compress(K, V, chunk, out=out, workspace=ws, **kw)
-    finally:
-        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
+    ref = _compress("defer_always", K, V, chunk, **kw)
+    torch.cuda.synchronize()
+    out = tuple(torch.zeros_like(t) for t in ref)
+    plan = ckv.plan(ckv.layout_of(K), ckv.make_params(chunk, rounds=rounds, n_sink=16, n_recent=64,
+                                                      route="defer_always"))      # sized for the route that will run
+    ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        _compress("defer_always", K, V, chunk, out=out, workspace=ws, **kw)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        _compress("defer_always", K, V, chunk, out=out, workspace=ws, **kw)
     for i in range(3):
         for t in out:
             t.zero_()

@@ -2,7 +2,6 @@
 size class, mixed merge fractions, sinks / recents, both selection scopes, incoming degrees.  Each
 round is checked against the oracle (teacher-forced); the multi-round call must reproduce the
 rounds issued one by one bit for bit (it takes the deferred-value path where it applies)."""
-import os
 
 import numpy as np
 import pytest
@@ -15,6 +14,11 @@ from synth import kv_host
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
+
+
+def _compress(route, *args, **kw):
+    """ckv.compress on a named kernel route (the routes give the same bits)."""
+    return ckv.compress(*args, route=route, **kw)
 
 
 def _cases():
@@ -68,12 +72,8 @@ def test_random_configuration(k, dtype, heads, seq, dim, chunk, rounds, n_sink, 
                                    what=f"case {k} round {j} h{h}", scope=scope)
         curK, curV, curdeg = gK, gV, gdeg
         maps.append(gas.to(torch.int64))
-    os.environ["CKV_FORCE_DEFERRED_VALUES"] = "1"      # take the deferred-value path wherever it applies
-    try:
-        gK, gV, gdeg, gas = ckv.compress(K, V, chunk, rounds=rounds, deg=deg, **kw)
-        torch.cuda.synchronize()
-    finally:
-        del os.environ["CKV_FORCE_DEFERRED_VALUES"]
+    gK, gV, gdeg, gas = _compress("defer_always", K, V, chunk, rounds=rounds, deg=deg, **kw)
+    torch.cuda.synchronize()
     assert gK.shape[2] == oracle.round_lengths(seq, chunk, rounds, n_sink, n_recent, scope=scope)[-1]
     assert torch.equal(gK, curK) and torch.equal(gV, curV) and torch.equal(gdeg, curdeg)
     comp = maps[0]
