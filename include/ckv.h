@@ -202,6 +202,21 @@ int ckv_decode_attn(const void* q, int32_t q_heads, const void* K, const void* V
                     void* o, int32_t o_dtype, void* workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/* ckv_decode_attn without a workspace argument, for callers that cannot allocate device memory:
+ * code recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and same result bits as ckv_decode_attn; the split partials and arrival
+ * counters live in a device array of CKV_NOALLOC_SCRATCH_BYTES that is part of the library (each
+ * GPU the library runs on holds its own copy until the process ends; the first call on a device
+ * looks its address up).  The call allocates and frees nothing and records no memset.
+ * CKV_EWORKSPACE when ckv_decode_attn_workspace() for the shape exceeds CKV_NOALLOC_SCRATCH_BYTES
+ * (the Llama-3-8B decode shapes, batch 1 to 16 at 32 query heads, need about 1.1 MB).  All calls on
+ * one GPU share that one array: calls that overlap in time on the same GPU (different streams or
+ * threads) race; issue them on one stream, or otherwise order them. */
+#define CKV_NOALLOC_SCRATCH_BYTES (4u << 20)
+int ckv_decode_attn_noalloc(const void* q, int32_t q_heads, const void* K, const void* V,
+                            const ckv_layout* kv, const int32_t* lens, const int32_t* deg, float scale,
+                            void* o, int32_t o_dtype, void* hip_stream);
+
 /* ---- block-paged caches (the layout a serving engine's block manager keeps) ------------------
  * Pool: K_pool, V_pool [n_blocks, heads, block_size, dim] contiguous (inside a block the tokens of
  * one head are contiguous: block_size*dim elements per (block, head), which keeps a head's

@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
         L.ckv_decode_attn_workspace.argtypes = [C.POINTER(Layout), i32, C.POINTER(C.c_size_t)]
         L.ckv_decode_attn.argtypes = [vp, i32, vp, vp, C.POINTER(Layout), vp, vp, C.c_float, vp, i32,
                                       vp, C.c_size_t, vp]
+        L.ckv_decode_attn_noalloc.argtypes = [vp, i32, vp, vp, C.POINTER(Layout), vp, vp, C.c_float, vp, i32, vp]
         L.ckv_schedule_annealed.argtypes = [i32, i32, i32, i32, i32, i32, C.c_float, C.c_float, C.c_float,
                                             C.POINTER(Params)]
         L.ckv_append.argtypes = [vp, vp, vp, vp, vp, C.POINTER(Layout), vp, i32, vp]
@@ -243,6 +244,21 @@ def decode_attn(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, lens: Optiona
                                _stream())
     if st != 0:
         raise CkvError(st, "ckv_decode_attn")
+    return out
+
+
+def decode_attn_noalloc(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, out: torch.Tensor,
+                        lens: Optional[torch.Tensor] = None, deg: Optional[torch.Tensor] = None,
+                        scale: float = 0.0) -> torch.Tensor:
+    """ckv_decode_attn_noalloc: ckv_decode_attn with the library's own scratch array; the caller
+    passes inputs and the output tensor, nothing is allocated."""
+    lay = layout_of(K, deg)
+    if not q.is_contiguous() or q.dim() != 3 or q.dtype != K.dtype:
+        raise ValueError("q must be a contiguous [batch, q_heads, dim] tensor of the cache dtype")
+    st = lib().ckv_decode_attn_noalloc(_ptr(q), q.shape[1], _ptr(K), _ptr(V), C.byref(lay), _ptr(lens), _ptr(deg),
+                                       scale, _ptr(out), _DT[out.dtype], _stream())
+    if st != 0:
+        raise CkvError(st, "ckv_decode_attn_noalloc")
     return out
 
 
