@@ -256,7 +256,7 @@ int ckv_paged_gather(const void* K_pool, const void* V_pool, const int32_t* deg_
 /* Scatter writes tokens [0, in->seq) of every sequence into its blocks and RELEASES the blocks the
  * sequence no longer needs: with old_seq the length before, table entries
  * [ceil(in->seq / bs), ceil(old_seq / bs)) are copied to freed [batch, n_freed] (may be NULL) and
- * set to -1; lens[b] := in->seq when lens != NULL. */
+ * set to -1; lens[b] := in->seq when lens != NULL.  deg NULL writes degree 1. */
 int ckv_paged_scatter(const void* K, const void* V, const int32_t* deg, const ckv_layout* in, void* K_pool,
                       void* V_pool, int32_t* deg_pool, int32_t* block_table, const ckv_paged_layout* pl,
                       int32_t old_seq, int32_t* freed, int32_t* lens, void* hip_stream);
@@ -266,17 +266,31 @@ int ckv_paged_scatter(const void* K, const void* V, const int32_t* deg, const ck
  * arguments (new_seq > old_seq included). */
 int32_t ckv_paged_freed_blocks(const ckv_paged_layout* pl, int32_t old_seq, int32_t new_seq);
 
-/* ckv_compress on sequences of `seq` tokens each that live in a paged cache, written back into the
- * sequences' own first blocks (compaction), the blocks behind them released as in
- * ckv_paged_scatter.  Stages through the workspace: gather -> ckv_compress -> scatter, i.e. one
- * extra read and write of the cache and of the result on top of the clustering's own traffic.
- * ckv_paged_compress_plan (host only) gives the length after compression, the number of blocks
- * every sequence releases and the workspace size.  deg_pool is required (it receives the degrees). */
-int ckv_paged_compress_plan(const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, int32_t* out_seq,
-                            int32_t* n_freed, size_t* workspace_bytes);
+/* ckv_compress on sequences that live in a paged cache (the serving-engine integration: read the
+ * paged cache, compress, write the centroids back, hand the freed blocks to the block manager), with
+ * the result written into the sequences' own first blocks (compaction) and the blocks behind the new
+ * length released as in ckv_paged_scatter.
+ *   seq_lens  HOST int32 [batch] or NULL: tokens of every sequence before the call (NULL: all `seq`).
+ *             Neighbouring sequences of equal length are compressed together, so a batch sorted by
+ *             length costs few launches.
+ *   lens      DEVICE int32 [batch] or NULL: set to the new lengths on the stream.
+ *   freed     DEVICE int32 [batch, freed_stride] or NULL: the released block ids of every sequence,
+ *             padded with -1; freed_stride >= the plan's n_freed.
+ * The kernels read and write the pools through the block table: the first round's similarity and
+ * merge kernels read pages in place, and the last round writes every output whose pool no workgroup
+ * of that round still reads straight into its pages (with two or more rounds: the keys, and unless the
+ * schedule is a single deferred pair also the values and degrees); the other outputs pass through a
+ * staging tensor in the workspace and one scatter.  Nothing is gathered.  Same result bits as
+ * ckv_compress on the same tokens.  deg_pool is required (it receives the degrees).
+ * Supported: blocks of 8 tokens or more, pools of fewer than 2^31 token rows, batch <= 4096.
+ * ckv_paged_compress_plan (host only): out_seq receives the length after compression of every
+ * sequence ([batch] entries when seq_lens is given, one entry otherwise; may be NULL), n_freed the
+ * largest number of blocks a sequence releases, workspace_bytes the scratch the call needs. */
+int ckv_paged_compress_plan(const ckv_paged_layout* pl, int32_t seq, const int32_t* seq_lens, const ckv_params* p,
+                            int32_t* out_seq, int32_t* n_freed, size_t* workspace_bytes);
 int ckv_paged_compress(void* K_pool, void* V_pool, int32_t* deg_pool, int32_t* block_table, int32_t* lens,
-                       const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, int32_t* freed,
-                       void* workspace, size_t workspace_bytes, void* hip_stream);
+                       const ckv_paged_layout* pl, int32_t seq, const int32_t* seq_lens, const ckv_params* p,
+                       int32_t* freed, int32_t freed_stride, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Per-kernel timing for benchmarks.  When enabled, every kernel launch of the calling process
  * is bracketed by HIP events on its stream (a few microseconds per launch, on the host and on the

@@ -91,9 +91,10 @@ def lib() -> C.CDLL:
         L.ckv_paged_scatter.argtypes = [vp, vp, vp, C.POINTER(Layout), vp, vp, vp, vp, PL, i32, vp, vp, vp]
         L.ckv_paged_freed_blocks.argtypes = [PL, i32, i32]
         L.ckv_paged_freed_blocks.restype = i32
-        L.ckv_paged_compress_plan.argtypes = [PL, i32, C.POINTER(Params), C.POINTER(i32), C.POINTER(i32),
-                                              C.POINTER(C.c_size_t)]
-        L.ckv_paged_compress.argtypes = [vp, vp, vp, vp, vp, PL, i32, C.POINTER(Params), vp, vp, C.c_size_t, vp]
+        L.ckv_paged_compress_plan.argtypes = [PL, i32, C.POINTER(i32), C.POINTER(Params), C.POINTER(i32),
+                                              C.POINTER(i32), C.POINTER(C.c_size_t)]
+        L.ckv_paged_compress.argtypes = [vp, vp, vp, vp, vp, PL, i32, C.POINTER(i32), C.POINTER(Params), vp, i32, vp,
+                                         C.c_size_t, vp]
         L.ckv_timing_enable.argtypes = [C.c_int]
         L.ckv_timing_select.argtypes = [C.c_char_p]
         L.ckv_timing_read.argtypes = [C.POINTER(KernelTime), C.c_int]
@@ -377,30 +378,41 @@ def paged_scatter(K, V, deg, K_pool, V_pool, deg_pool, block_table, old_seq: int
     return freed
 
 
-def paged_compress_plan(pl: PagedLayout, seq: int, params: Params):
-    """(length after compression, blocks released per sequence, workspace bytes)."""
-    out_seq, n_freed, nbytes = C.c_int32(0), C.c_int32(0), C.c_size_t(0)
-    st = lib().ckv_paged_compress_plan(C.byref(pl), seq, C.byref(params), C.byref(out_seq), C.byref(n_freed),
-                                       C.byref(nbytes))
+def _host_lens(seq_lens, batch):
+    if seq_lens is None:
+        return None
+    vals = [int(x) for x in seq_lens]
+    if len(vals) != batch:
+        raise ValueError("seq_lens must have one entry per sequence")
+    return (C.c_int32 * batch)(*vals)
+
+
+def paged_compress_plan(pl: PagedLayout, seq: int, params: Params, seq_lens=None):
+    """(length after compression - a list when seq_lens is given -, most blocks a sequence releases,
+    workspace bytes).  seq_lens: host sequence of per-sequence lengths, or None (all `seq`)."""
+    hl = _host_lens(seq_lens, pl.batch)
+    out = (C.c_int32 * (pl.batch if hl is not None else 1))()
+    n_freed, nbytes = C.c_int32(0), C.c_size_t(0)
+    st = lib().ckv_paged_compress_plan(C.byref(pl), seq, hl, C.byref(params), out, C.byref(n_freed), C.byref(nbytes))
     if st != 0:
         raise CkvError(st, "ckv_paged_compress_plan")
-    return out_seq.value, n_freed.value, nbytes.value
+    return (list(out) if hl is not None else out[0]), n_freed.value, nbytes.value
 
 
 def paged_compress(K_pool, V_pool, deg_pool, block_table, seq: int, chunk: int, retain_ratio: float = 1.0,
                    rounds=None, lens=None, n_sink: int = 0, n_recent: int = 0, scope: str = "chunk",
-                   workspace=None):
+                   workspace=None, seq_lens=None, route: Optional[str] = None):
     """ckv_paged_compress: compress the sequences in place in the paged cache; returns
-    (new length, freed block ids [batch, n_freed])."""
+    (new length - a list when seq_lens is given -, freed block ids [batch, n_freed], -1 padded)."""
     pl = paged_layout_of(K_pool, block_table)
-    params = make_params(chunk, retain_ratio, rounds, n_sink, n_recent, scope)
-    out_seq, n_freed, nbytes = paged_compress_plan(pl, seq, params)
+    params = make_params(chunk, retain_ratio, rounds, n_sink, n_recent, scope, route)
+    out_seq, n_freed, nbytes = paged_compress_plan(pl, seq, params, seq_lens)
     freed = torch.empty((pl.batch, n_freed), dtype=torch.int32, device=K_pool.device)
     if workspace is None:
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=K_pool.device)
     st = lib().ckv_paged_compress(_ptr(K_pool), _ptr(V_pool), _ptr(deg_pool), _ptr(block_table), _ptr(lens),
-                                  C.byref(pl), seq, C.byref(params), _ptr(freed), _ptr(workspace),
-                                  workspace.numel(), _stream())
+                                  C.byref(pl), seq, _host_lens(seq_lens, pl.batch), C.byref(params), _ptr(freed), n_freed,
+                                  _ptr(workspace), workspace.numel(), _stream())
     if st != 0:
         raise CkvError(st, "ckv_paged_compress")
     return out_seq, freed

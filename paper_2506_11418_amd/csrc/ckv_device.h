@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ckv_internal.h"
+
 namespace ckv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -57,6 +59,31 @@ __device__ __forceinline__ float row_sum(float x) {
   if (LANES == 16)
     x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));
   return x;
+}
+
+// Block-pool rows of a workgroup's tokens.  stage_row_bases fills s_rb[i] with the pool row of the
+// first token of block (first_blk + i) of sequence b for head h (-1 for a table entry outside the
+// pool), for the blocks that hold tokens [u_first, u_last] of the sequence; paged_row then turns a
+// token into its pool row with one LDS read.  A block outside the pool reads as row 0 (always valid
+// memory, contents meaningless) and is not written.
+struct RowBases {
+  const int32_t* s_rb;
+  int blk0, shift, mask;
+  __device__ __forceinline__ int base_of(int u) const { return s_rb[(u >> shift) - blk0]; }
+  __device__ __forceinline__ int row(int u) const {            // for reads
+    const int rb = base_of(u);
+    return rb < 0 ? 0 : rb + (u & mask);
+  }
+};
+__device__ inline RowBases stage_row_bases(int32_t* s_rb, const PagedSide& pg, int b, int h, int heads, int u_first,
+                                           int u_last, int tid, int n_threads) {
+  const int blk0 = u_first >> pg.shift, n = (u_last >> pg.shift) - blk0 + 1;
+  const int32_t* row = pg.table + (int64_t)b * pg.max_blocks;
+  for (int i = tid; i < n; i += n_threads) {
+    const int blk = (blk0 + i < pg.max_blocks) ? row[blk0 + i] : -1;
+    s_rb[i] = ((unsigned)blk < (unsigned)pg.n_blocks) ? ((blk * heads + h) << pg.shift) : -1;
+  }
+  return RowBases{s_rb, blk0, pg.shift, (1 << pg.shift) - 1};
 }
 
 // Map dispatch order to logical work so that the 8 XCDs (which receive consecutive workgroup ids

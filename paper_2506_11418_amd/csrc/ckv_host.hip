@@ -215,6 +215,110 @@ void fold_launches() {
   (void)hipGetLastError();
 }
 
+
+// A paged call: the cache lives in block pools (K, V, deg_in of run_rounds are then the pools) and
+// the result goes back into the sequences' own first blocks.  Only the first round reads the pools;
+// the last round writes a pool directly when no workgroup of that round still reads it, and into a
+// staging tensor (scattered afterwards) otherwise: with a single round everything is staged; when the
+// schedule is one deferred pair the last round rebuilds its value rows from the ORIGINAL values and
+// degrees, so those two are staged while the keys, which that round takes from the first round's
+// output, go straight to their pool.
+struct PagedCall {
+  PagedSide side;            // table (at the first sequence of the call), max_blocks, shift, n_blocks; tok0 = 0
+  void *sK, *sV;             // staging tensors [batch, heads, out_seq, dim] (only those that are needed)
+  int32_t* sdeg;
+  bool stage_k, stage_v;     // out: which outputs went to staging
+};
+
+// The rounds of one compression (Algorithm 1, the loop after prefill), launches only.
+int run_rounds(const void* K, const void* V, const int32_t* deg_in, const ckv_layout* in, const ckv_params* p,
+               const ckv_plan_t* planp, void* K_out, void* V_out, int32_t* deg_out, const ckv_layout* out,
+               int32_t* assign, void* workspace, PagedCall* pc, hipStream_t s) {
+  const ckv_plan_t& plan = *planp;
+  const int n_bh = in->batch * in->heads;
+  const int e = in->dtype == CKV_BF16 ? 2 : 4;
+  const Workspace w = carve(in, p, &plan);
+  RoundMode mode[CKV_MAX_ROUNDS];
+  plan_routes(in, p, &plan, mode);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  int32_t* dst = reinterpret_cast<int32_t*>(ws + w.dst);
+  float* score = reinterpret_cast<float*>(ws + w.score);
+  const void* curK = K;
+  const void* curV = V;
+  const int32_t* curDeg = deg_in;
+  TensorView curView = view_of(in);
+  int16_t* lists = reinterpret_cast<int16_t*>(ws + w.lists);
+  ValueOrigin org{};
+  const void* edgesV = V;   // where the current cache's sink / recent value rows live
+  if (pc) {
+    pc->stage_k = plan.n_rounds == 1;
+    pc->stage_v = plan.n_rounds == 1 || (plan.n_rounds == 2 && mode[0] == ROUND_KEYS_ONLY);
+  }
+  for (int j = 0; j < plan.n_rounds; ++j) {
+    const int len = plan.round_len[j];
+    const int next = plan.round_len[j + 1];
+    const bool last = (j == plan.n_rounds - 1);
+    int lo, hi;
+    clusterable(len, p->n_sink, p->n_recent, &lo, &hi);
+    const int mid = hi - lo;
+    // which sides of this round's launches are block pools
+    PagedSide pin{}, pok{}, pov{}, pin0{}, pok0{}, pov0{};   // (…0: the same with token offset 0, for whole-sequence kernels)
+    if (pc && j == 0) { pin = pc->side; pin.tok0 = lo; pin0 = pc->side; }
+    if (pc && last && !pc->stage_k) { pok = pc->side; pok.tok0 = lo; pok0 = pc->side; }
+    if (pc && last && !pc->stage_v) { pov = pc->side; pov.tok0 = lo; pov0 = pc->side; }
+    const TensorView stView = compact_view(in->heads, next, in->dim);
+    void* oK = !last ? ws + w.K[j & 1] : !pc ? K_out : pc->stage_k ? pc->sK : const_cast<void*>(K);
+    void* oV = !last ? ws + w.V[j & 1] : !pc ? V_out : pc->stage_v ? pc->sV : const_cast<void*>(V);
+    int32_t* oDeg = !last ? reinterpret_cast<int32_t*>(ws + w.deg[j & 1])
+                    : !pc ? deg_out : pc->stage_v ? pc->sdeg : const_cast<int32_t*>(deg_in);
+    const TensorView oView = (last && !pc) ? view_of(out) : stView;
+    const int64_t oDegStride = oView.deg_stride;
+    int32_t* map = nullptr;
+    if (assign) map = (j == 0) ? assign : reinterpret_cast<int32_t*>(ws + w.map);
+    const bool keys_only = mode[j] == ROUND_KEYS_ONLY, from_origin = mode[j] == ROUND_ORIGIN;
+    hipError_t err = hipSuccess;
+    if (mid > 0) {   // cluster tokens [lo, hi): the same kernels on a view that starts at token lo
+      const bool in_pool = pin.table != nullptr;
+      const unsigned char* mK = static_cast<const unsigned char*>(curK) + (in_pool ? 0 : (size_t)lo * curView.stride_s * e);
+      const unsigned char* mV = static_cast<const unsigned char*>(curV) + (in_pool ? 0 : (size_t)lo * curView.stride_s * e);
+      const int32_t* mDeg = !curDeg ? nullptr : in_pool ? curDeg : curDeg + lo;
+      err = launch_match(mK, in->dtype, in->dim, curView, n_bh, mid, p->chunk, dst, score, s, pin);
+      if (err != hipSuccess) return hip_status(err);
+      int32_t* sel = nullptr;
+      if (p->scope == CKV_SCOPE_HEAD) {
+        sel = reinterpret_cast<int32_t*>(ws + w.sel);
+        err = launch_global_select(score, n_bh, mid, p->chunk, plan.round_r[j], sel, s);
+        if (err != hipSuccess) return hip_status(err);
+      }
+      unsigned char* moK = static_cast<unsigned char*>(oK) + (pok.table ? 0 : (size_t)lo * oView.stride_s * e);
+      unsigned char* moV = static_cast<unsigned char*>(oV) + (pov.table ? 0 : (size_t)lo * oView.stride_s * e);
+      int32_t* moDeg = pov.table ? oDeg : oDeg + lo;
+      err = launch_merge(mK, mV, mDeg, in->dtype, in->dim, curView, n_bh, mid, p->chunk, plan.round_r[j], dst, score,
+                         moK, moV, moDeg, oView, oDegStride, map ? map + lo : nullptr, curView.deg_stride, len, lo, sel,
+                         keys_only ? lists : nullptr, from_origin ? &org : nullptr, s, pin, pok, pov);
+      if (err != hipSuccess) return hip_status(err);
+    }
+    if (mid < len)   // sinks and recents (or a cache too short to cluster): straight copy
+      err = launch_edges(curK, edgesV, curDeg, curView, len, oK, oV, oDeg, oView, oDegStride, next, map,
+                         mid > 0 ? lo : len, mid > 0 ? len - hi : 0, n_bh, in->dim * e, e, s, pin0, pok0, pov0);
+    if (err != hipSuccess) return hip_status(err);
+    if (assign && j > 0) {
+      err = launch_compose(assign, map, n_bh, in->seq, len, s);
+      if (err != hipSuccess) return hip_status(err);
+    }
+    if (keys_only) {   // the clustered values stay where they are; the next round reads them through the lists
+      const bool in_pool = pin.table != nullptr;
+      org = ValueOrigin{static_cast<const unsigned char*>(curV) + (in_pool ? 0 : (size_t)lo * curView.stride_s * e), curView,
+                        !curDeg ? nullptr : in_pool ? curDeg : curDeg + lo, lists, mid, div_up(mid, p->chunk), pin};
+    } else {
+      curV = oV;
+    }
+    edgesV = oV;       // sinks and recents are copied in every round, deferred or not
+    curK = oK; curDeg = oDeg; curView = oView;
+  }
+  return CKV_OK;
+}
+
 }  // namespace
 
 bool timing_begin(const char* name, hipStream_t st) {
@@ -321,71 +425,7 @@ int ckv_compress(const void* K, const void* V, const int32_t* deg_in, const ckv_
     return hip_status(err);
   }
 
-  const Workspace w = carve(in, p, &plan);
-  RoundMode mode[CKV_MAX_ROUNDS];
-  plan_routes(in, p, &plan, mode);
-  unsigned char* ws = static_cast<unsigned char*>(workspace);
-  int32_t* dst = reinterpret_cast<int32_t*>(ws + w.dst);
-  float* score = reinterpret_cast<float*>(ws + w.score);
-  const void* curK = K;
-  const void* curV = V;
-  const int32_t* curDeg = deg_in;
-  TensorView curView = view_of(in);
-  int16_t* lists = reinterpret_cast<int16_t*>(ws + w.lists);
-  ValueOrigin org{};
-  const void* edgesV = V;   // where the current cache's sink / recent value rows live
-  for (int j = 0; j < plan.n_rounds; ++j) {
-    const int len = plan.round_len[j];
-    const int next = plan.round_len[j + 1];
-    const bool last = (j == plan.n_rounds - 1);
-    void* oK = last ? K_out : ws + w.K[j & 1];
-    void* oV = last ? V_out : ws + w.V[j & 1];
-    int32_t* oDeg = last ? deg_out : reinterpret_cast<int32_t*>(ws + w.deg[j & 1]);
-    const TensorView oView = last ? view_of(out) : compact_view(in->heads, next, in->dim);
-    const int64_t oDegStride = oView.deg_stride;
-    int32_t* map = nullptr;
-    if (assign) map = (j == 0) ? assign : reinterpret_cast<int32_t*>(ws + w.map);
-    int lo, hi;
-    clusterable(len, p->n_sink, p->n_recent, &lo, &hi);
-    const int mid = hi - lo;
-    const bool keys_only = mode[j] == ROUND_KEYS_ONLY, from_origin = mode[j] == ROUND_ORIGIN;
-    hipError_t err = hipSuccess;
-    if (mid > 0) {   // cluster tokens [lo, hi): the same kernels on a view that starts at token lo
-      const unsigned char* mK = static_cast<const unsigned char*>(curK) + (size_t)lo * curView.stride_s * e;
-      const unsigned char* mV = static_cast<const unsigned char*>(curV) + (size_t)lo * curView.stride_s * e;
-      err = launch_match(mK, in->dtype, in->dim, curView, n_bh, mid, p->chunk, dst, score, s);
-      if (err != hipSuccess) return hip_status(err);
-      int32_t* sel = nullptr;
-      if (p->scope == CKV_SCOPE_HEAD) {
-        sel = reinterpret_cast<int32_t*>(ws + w.sel);
-        err = launch_global_select(score, n_bh, mid, p->chunk, plan.round_r[j], sel, s);
-        if (err != hipSuccess) return hip_status(err);
-      }
-      err = launch_merge(mK, mV, curDeg ? curDeg + lo : nullptr, in->dtype, in->dim, curView, n_bh, mid, p->chunk,
-                         plan.round_r[j], dst, score, static_cast<unsigned char*>(oK) + (size_t)lo * oView.stride_s * e,
-                         static_cast<unsigned char*>(oV) + (size_t)lo * oView.stride_s * e, oDeg + lo, oView,
-                         oDegStride, map ? map + lo : nullptr, curView.deg_stride, len, lo, sel,
-                         keys_only ? lists : nullptr, from_origin ? &org : nullptr, s);
-      if (err != hipSuccess) return hip_status(err);
-    }
-    if (mid < len)   // sinks and recents (or a cache too short to cluster): straight copy
-      err = launch_edges(curK, edgesV, curDeg, curView, len, oK, oV, oDeg, oView, oDegStride, next, map,
-                         mid > 0 ? lo : len, mid > 0 ? len - hi : 0, n_bh, in->dim * e, e, s);
-    if (err != hipSuccess) return hip_status(err);
-    if (assign && j > 0) {
-      err = launch_compose(assign, map, n_bh, in->seq, len, s);
-      if (err != hipSuccess) return hip_status(err);
-    }
-    if (keys_only) {   // the clustered values stay where they are; the next round reads them through the lists
-      org = ValueOrigin{static_cast<const unsigned char*>(curV) + (size_t)lo * curView.stride_s * e, curView,
-                        curDeg ? curDeg + lo : nullptr, lists, mid, div_up(mid, p->chunk)};
-    } else {
-      curV = oV;
-    }
-    edgesV = oV;       // sinks and recents are copied in every round, deferred or not
-    curK = oK; curDeg = oDeg; curView = oView;
-  }
-  return CKV_OK;
+  return run_rounds(K, V, deg_in, in, p, &plan, K_out, V_out, deg_out, out, assign, workspace, nullptr, s);
 }
 
 int32_t ckv_n_sources(int32_t seq, int32_t chunk) {
@@ -588,7 +628,7 @@ int ckv_paged_scatter(const void* K, const void* V, const int32_t* deg, const ck
   const int keep = ckv::div_up(in->seq, pl->block_size), old_blocks = ckv::div_up(old_seq, pl->block_size);
   return ckv::hip_status(ckv::launch_paged_scatter(K, V, deg, ckv::view_of(in), pl->batch, pl->heads, in->seq, pl->dim * e, e,
                                                    K_pool, V_pool, deg_pool, block_table, pl->max_blocks, shift,
-                                                   pl->n_blocks, keep, old_blocks, freed, lens,
+                                                   pl->n_blocks, keep, old_blocks, freed, old_blocks - keep, lens,
                                                    static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -601,63 +641,145 @@ int32_t ckv_paged_freed_blocks(const ckv_paged_layout* pl, int32_t old_seq, int3
 }
 
 namespace {
-struct PagedWs { size_t K, V, deg, Ko, Vo, dego, inner, total; };
-int paged_plan(const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, ckv_plan_t* plan, PagedWs* w) {
-  int shift;
-  int st = check_paged(pl, &shift);
+// Workspace of a paged compression: staging for the outputs the last round cannot write in place
+// (see PagedCall), then ckv_compress's own workspace.  Sequences are processed in runs of equal
+// length, one after the other, so the sizes are those of the largest run.
+struct PagedWs { size_t sK, sV, sdeg, inner, total; };
+struct PagedRun { int b0, n, seq; };
+
+// maximal runs of neighbouring sequences with equal length
+int paged_runs(const ckv_paged_layout* pl, int32_t seq, const int32_t* seq_lens, PagedRun* runs) {
+  int n = 0;
+  for (int b = 0; b < pl->batch; ++b) {
+    const int len = seq_lens ? seq_lens[b] : seq;
+    if (n > 0 && runs[n - 1].seq == len) ++runs[n - 1].n;
+    else runs[n++] = PagedRun{b, 1, len};
+  }
+  return n;
+}
+
+ckv_paged_layout run_layout(const ckv_paged_layout* pl, const PagedRun& r) {
+  ckv_paged_layout x = *pl;
+  x.batch = r.n;
+  return x;
+}
+
+int paged_run_plan(const ckv_paged_layout* pl, const PagedRun& run, const ckv_params* p, ckv_plan_t* plan, PagedWs* w) {
+  if (run.seq <= 0 || (int64_t)run.seq > (int64_t)pl->max_blocks * pl->block_size) return CKV_ESHAPE;
+  const ckv_paged_layout rl = run_layout(pl, run);
+  const ckv_layout in = staging_layout(&rl, run.seq);
+  int st = ckv_plan(&in, p, plan);
   if (st != CKV_OK) return st;
-  if (seq <= 0 || (int64_t)seq > (int64_t)pl->max_blocks * pl->block_size) return CKV_ESHAPE;
-  const ckv_layout in = staging_layout(pl, seq);
-  st = ckv_plan(&in, p, plan);
-  if (st != CKV_OK) return st;
-  const size_t e = ckv::elem_bytes(pl->dtype), n_bh = (size_t)pl->batch * pl->heads;
+  RoundMode mode[CKV_MAX_ROUNDS];
+  plan_routes(&in, p, plan, mode);
+  const bool stage_k = plan->n_rounds == 1;
+  const bool stage_v = plan->n_rounds == 1 || (plan->n_rounds == 2 && mode[0] == ROUND_KEYS_ONLY);
+  const size_t e = ckv::elem_bytes(pl->dtype), n_bh = (size_t)run.n * pl->heads;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = ckv::align_up(off + bytes, 256); return o; };
-  w->K = take(n_bh * seq * pl->dim * e);
-  w->V = take(n_bh * seq * pl->dim * e);
-  w->deg = take(n_bh * seq * 4);
-  w->Ko = take(n_bh * plan->out_seq * pl->dim * e);
-  w->Vo = take(n_bh * plan->out_seq * pl->dim * e);
-  w->dego = take(n_bh * plan->out_seq * 4);
+  w->sK = take(stage_k ? n_bh * plan->out_seq * pl->dim * e : 0);
+  w->sV = take(stage_v ? n_bh * plan->out_seq * pl->dim * e : 0);
+  w->sdeg = take(stage_v ? n_bh * plan->out_seq * 4 : 0);
   w->inner = take(plan->workspace_bytes);
   w->total = off;
   return CKV_OK;
 }
+
+int check_paged_compress(const ckv_paged_layout* pl, int32_t seq, const int32_t* seq_lens) {
+  int shift;
+  int st = check_paged(pl, &shift);
+  if (st != CKV_OK) return st;
+  if (pl->block_size < 8) return CKV_EUNSUPPORTED;          // the kernels' block tables hold blocks of 8 tokens or more
+  if ((int64_t)pl->n_blocks * pl->heads * pl->block_size > INT32_MAX) return CKV_EUNSUPPORTED;   // pool rows are indexed in 32 bits
+  if (pl->batch > 4096) return CKV_ESHAPE;
+  if (!seq_lens && (seq <= 0 || (int64_t)seq > (int64_t)pl->max_blocks * pl->block_size)) return CKV_ESHAPE;
+  return CKV_OK;
+}
 }  // namespace
 
-int ckv_paged_compress_plan(const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, int32_t* out_seq,
-                            int32_t* n_freed, size_t* workspace_bytes) {
-  ckv_plan_t plan;
-  PagedWs w;
-  int st = paged_plan(pl, seq, p, &plan, &w);
+int ckv_paged_compress_plan(const ckv_paged_layout* pl, int32_t seq, const int32_t* seq_lens, const ckv_params* p,
+                            int32_t* out_seq, int32_t* n_freed, size_t* workspace_bytes) {
+  int st = check_paged_compress(pl, seq, seq_lens);
   if (st != CKV_OK) return st;
-  if (out_seq) *out_seq = plan.out_seq;
-  if (n_freed) *n_freed = ckv::div_up(seq, pl->block_size) - ckv::div_up(plan.out_seq, pl->block_size);
-  if (workspace_bytes) *workspace_bytes = w.total;
+  std::vector<PagedRun> runs(pl->batch);
+  const int n_runs = paged_runs(pl, seq, seq_lens, runs.data());
+  size_t need = 0;
+  int freed_max = 0;
+  for (int i = 0; i < n_runs; ++i) {
+    ckv_plan_t plan;
+    PagedWs w;
+    st = paged_run_plan(pl, runs[i], p, &plan, &w);
+    if (st != CKV_OK) return st;
+    need = w.total > need ? w.total : need;
+    const int nf = ckv::div_up(runs[i].seq, pl->block_size) - ckv::div_up(plan.out_seq, pl->block_size);
+    freed_max = nf > freed_max ? nf : freed_max;
+    if (out_seq) {
+      if (seq_lens) for (int b = 0; b < runs[i].n; ++b) out_seq[runs[i].b0 + b] = plan.out_seq;
+      else out_seq[0] = plan.out_seq;
+    }
+  }
+  if (n_freed) *n_freed = freed_max;
+  if (workspace_bytes) *workspace_bytes = need;
   return CKV_OK;
 }
 
 int ckv_paged_compress(void* K_pool, void* V_pool, int32_t* deg_pool, int32_t* block_table, int32_t* lens,
-                       const ckv_paged_layout* pl, int32_t seq, const ckv_params* p, int32_t* freed,
-                       void* workspace, size_t workspace_bytes, void* hip_stream) {
-  ckv_plan_t plan;
-  PagedWs w;
-  int st = paged_plan(pl, seq, p, &plan, &w);
+                       const ckv_paged_layout* pl, int32_t seq, const int32_t* seq_lens, const ckv_params* p,
+                       int32_t* freed, int32_t freed_stride, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = check_paged_compress(pl, seq, seq_lens);
   if (st != CKV_OK) return st;
   if (!K_pool || !V_pool || !deg_pool || !block_table || !workspace) return CKV_EINVAL;
+  if (((uintptr_t)K_pool | (uintptr_t)V_pool) % 16 || ((uintptr_t)deg_pool | (uintptr_t)block_table | (uintptr_t)freed |
+                                                        (uintptr_t)lens) % 4)
+    return CKV_EALIGN;
   if (((uintptr_t)workspace) % 256) return CKV_EALIGN;
-  if (workspace_bytes < w.total) return CKV_EWORKSPACE;
+  if (!dims_supported(pl->dtype, pl->dim)) return CKV_EUNSUPPORTED;
+  int32_t n_freed_max = 0;
+  size_t need = 0;
+  st = ckv_paged_compress_plan(pl, seq, seq_lens, p, nullptr, &n_freed_max, &need);
+  if (st != CKV_OK) return st;
+  if (workspace_bytes < need) return CKV_EWORKSPACE;
+  if (freed && freed_stride < n_freed_max) return CKV_ESHAPE;
+  int shift;
+  check_paged(pl, &shift);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
-  const ckv_layout in = staging_layout(pl, seq), out = staging_layout(pl, plan.out_seq);
-  st = ckv_paged_gather(K_pool, V_pool, deg_pool, block_table, pl, seq, ws + w.K, ws + w.V,
-                        reinterpret_cast<int32_t*>(ws + w.deg), &in, hip_stream);
-  if (st != CKV_OK) return st;
-  st = ckv_compress(ws + w.K, ws + w.V, reinterpret_cast<int32_t*>(ws + w.deg), &in, p, ws + w.Ko, ws + w.Vo,
-                    reinterpret_cast<int32_t*>(ws + w.dego), &out, nullptr, ws + w.inner, plan.workspace_bytes,
-                    hip_stream);
-  if (st != CKV_OK) return st;
-  return ckv_paged_scatter(ws + w.Ko, ws + w.Vo, reinterpret_cast<int32_t*>(ws + w.dego), &out, K_pool, V_pool,
-                           deg_pool, block_table, pl, seq, freed, lens, hip_stream);
+  std::vector<PagedRun> runs(pl->batch);
+  const int n_runs = paged_runs(pl, seq, seq_lens, runs.data());
+  const int e = ckv::elem_bytes(pl->dtype);
+  for (int i = 0; i < n_runs; ++i) {
+    const PagedRun& run = runs[i];
+    ckv_plan_t plan;
+    PagedWs w;
+    st = paged_run_plan(pl, run, p, &plan, &w);
+    if (st != CKV_OK) return st;
+    int32_t* table = block_table + (size_t)run.b0 * pl->max_blocks;
+    int32_t* run_freed = freed ? freed + (size_t)run.b0 * freed_stride : nullptr;
+    int32_t* run_lens = lens ? lens + run.b0 : nullptr;
+    const ckv_paged_layout rl = run_layout(pl, run);
+    const ckv_layout in = staging_layout(&rl, run.seq), stg = staging_layout(&rl, plan.out_seq);
+    PagedCall pc{};
+    pc.side.table = table;
+    pc.side.max_blocks = pl->max_blocks;
+    pc.side.shift = shift;
+    pc.side.n_blocks = pl->n_blocks;
+    pc.sK = ws + w.sK;
+    pc.sV = ws + w.sV;
+    pc.sdeg = reinterpret_cast<int32_t*>(ws + w.sdeg);
+    if (plan.n_rounds > 0) {
+      st = run_rounds(K_pool, V_pool, deg_pool, &in, p, &plan, nullptr, nullptr, nullptr, &stg, nullptr, ws + w.inner, &pc, s);
+      if (st != CKV_OK) return st;
+    }
+    // staged outputs into the sequences' first blocks, then the blocks behind the new length are released
+    const int keep = ckv::div_up(plan.out_seq, pl->block_size), old_blocks = ckv::div_up(run.seq, pl->block_size);
+    hipError_t err = ckv::launch_paged_scatter(
+        (plan.n_rounds > 0 && pc.stage_k) ? pc.sK : nullptr, (plan.n_rounds > 0 && pc.stage_v) ? pc.sV : nullptr,
+        (plan.n_rounds > 0 && pc.stage_v) ? pc.sdeg : nullptr, ckv::view_of(&stg), run.n, pl->heads, plan.out_seq, pl->dim * e, e,
+        K_pool, V_pool, deg_pool, table, pl->max_blocks, shift, pl->n_blocks, keep, old_blocks, run_freed, freed_stride,
+        run_lens, s);
+    if (err != hipSuccess) return ckv::hip_status(err);
+  }
+  return CKV_OK;
 }
 
 int ckv_timing_enable(int on) {

@@ -27,6 +27,16 @@ struct PagedView {
   int32_t max_blocks, shift, n_blocks;
 };
 
+// One side (the input rows, the output rows, ...) of a launch that lives in a block pool instead of
+// a strided tensor: token t of the launch's view is token tok0 + t of the sequence, and token u of
+// sequence b, head h is pool row ((table[b*max_blocks + (u >> shift)] * heads + h) << shift) +
+// (u & (block_size - 1)) of a [n_blocks, heads, block_size, dim] pool (degrees: the same row of a
+// [n_blocks, heads, block_size] pool).  table == nullptr: the side is a strided tensor.
+struct PagedSide {
+  const int32_t* table = nullptr;
+  int32_t max_blocks = 0, shift = 0, n_blocks = 0, tok0 = 0;
+};
+
 inline __host__ __device__ int div_up(int a, int b) { return (a + b - 1) / b; }
 
 // Number of A tokens (sources) in a sequence of `seq` tokens cut into chunks of `chunk` (even).
@@ -48,7 +58,7 @@ inline __host__ __device__ int chunk_out(int L, float r) {
 // ---- kernel launchers (each returns hipGetLastError() after the launch) ------------------------
 // Similarity + per-source argmax.  dst_local[bh, i] = index within the chunk's B set, score fp32.
 hipError_t launch_match(const void* K, int dtype, int dim, TensorView kv, int n_bh, int seq,
-                        int chunk, int32_t* dst_local, float* score, hipStream_t st);
+                        int chunk, int32_t* dst_local, float* score, hipStream_t st, PagedSide paged = PagedSide{});
 
 // Turn chunk-local B indices into sequence positions (for ckv_match's public output).
 hipError_t launch_dst_positions(const int32_t* dst_local, int32_t* dst_pos, int n_bh, int seq,
@@ -66,6 +76,7 @@ struct ValueOrigin {
   const int16_t* lists;   // what the first round's merge exported
   int32_t seq0;           // tokens the first round clustered
   int32_t n_chunks0;      // its chunks per sequence
+  PagedSide paged;        // V0 / deg0 are block pools (then V0, deg0 point at the pools, view0.heads = heads)
 };
 
 // Per-chunk top-r selection + degree-weighted merge + order-preserving compaction.
@@ -77,7 +88,8 @@ hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int
                         const int32_t* dst_local, const float* score, void* K_out, void* V_out,
                         int32_t* deg_out, TensorView out, int64_t deg_out_stride, int32_t* map_out,
                         int64_t deg_in_stride, int64_t map_stride, int map_offset, const int32_t* sel_table,
-                        int16_t* lists_out, const ValueOrigin* org, hipStream_t st);
+                        int16_t* lists_out, const ValueOrigin* org, hipStream_t st, PagedSide paged_in = PagedSide{},
+                        PagedSide paged_out_k = PagedSide{}, PagedSide paged_out_v = PagedSide{});
 
 // Selection over all chunks of a sequence: from the match scores, table[bh, chunk] = (edges of the
 // chunk among the sequence's floor(r * edges) best, first output row of the chunk), two int32 each.
@@ -96,7 +108,8 @@ hipError_t launch_append(const void* k_new, const void* v_new, void* K, void* V,
 hipError_t launch_edges(const void* K, const void* V, const int32_t* deg_in, TensorView in, int in_len, void* K_out,
                         void* V_out, int32_t* deg_out, TensorView out, int64_t deg_out_stride, int out_len,
                         int32_t* map_out, int n_head, int n_tail, int n_bh, int row_bytes, int elem_bytes,
-                        hipStream_t st);
+                        hipStream_t st, PagedSide paged_in = PagedSide{}, PagedSide paged_out_k = PagedSide{},
+                        PagedSide paged_out_v = PagedSide{});
 
 // assign[bh, t] = map[bh, assign[bh, t]] for t < seq0.
 hipError_t launch_compose(int32_t* assign, const int32_t* map, int n_bh, int seq0, int map_len,
@@ -131,11 +144,13 @@ hipError_t launch_paged_gather(const void* K_pool, const void* V_pool, const int
 hipError_t launch_paged_append(const void* k_new, const void* v_new, void* K_pool, void* V_pool, int32_t* deg_pool,
                                PagedView paged, int n_b, int heads, int row_bytes, int32_t* lens, hipStream_t st);
 // Scatter also releases blocks: entries [keep_blocks, old_blocks) of every table row are copied to
-// freed[b*n_freed + k] (if freed != NULL) and set to -1, and lens[b] := seq (if lens != NULL).
+// freed[b*freed_stride + k] (if freed != NULL; the rest of a row is set to -1) and set to -1, and
+// lens[b] := seq (if lens != NULL).  K, V or deg may be NULL: that tensor is then not moved.
 hipError_t launch_paged_scatter(const void* K, const void* V, const int32_t* deg, TensorView in, int n_b, int heads,
                                 int seq, int row_bytes, int elem_bytes, void* K_pool, void* V_pool,
                                 int32_t* deg_pool, int32_t* table, int max_blocks, int shift, int n_blocks,
-                                int keep_blocks, int old_blocks, int32_t* freed, int32_t* lens, hipStream_t st);
+                                int keep_blocks, int old_blocks, int32_t* freed, int freed_stride, int32_t* lens,
+                                hipStream_t st);
 
 // ---- timing hooks ----------------------------------------------------------------------------
 // One-time set-up of a kernel that needs more than the default dynamic LDS, per device (each device

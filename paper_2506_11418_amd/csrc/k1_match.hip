@@ -37,10 +37,12 @@ constexpr int kPanel = 128;                      // B rows per LDS panel
 // NW waves x 64 A rows per workgroup: 4 waves (two workgroups per CU) for chunks of up to 512 tokens,
 // 8 waves (one workgroup per CU) for larger chunks, so that the B rows of a 1024-token chunk are
 // fetched, normed and written to LDS once instead of once per 256 A rows.
-template <int D, int NW>
+// PAGED: K is a block pool and the rows are reached through a block table (see PagedSide); the pool
+// rows of the chunk's blocks are staged in LDS first.
+template <int D, int NW, bool PAGED>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
     const __bf16* __restrict__ K, TensorView kv, int seq, int chunk, int n_chunks, int a_blocks,
-    int total_work, int per_xcd, int32_t* __restrict__ dst_local, float* __restrict__ score) {
+    int total_work, int per_xcd, int32_t* __restrict__ dst_local, float* __restrict__ score, PagedSide paged) {
   constexpr int OCT = D / 8;                       // 16-byte pieces per key row
   constexpr int ROWB = D * 2;                      // bytes per row
   constexpr int KEYSHIFT = (ROWB == 256) ? 0 : 1;  // rows per 256 B of LDS = 1 << KEYSHIFT
@@ -51,6 +53,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* panel0 = smem;                                // 2 panels of kPanel rows; the A
   float* invb = reinterpret_cast<float*>(smem + PANELS_B);           // block is staged over them
+  int32_t* s_rb = reinterpret_cast<int32_t*>(invb + 2 * kPanel);     // PAGED: pool rows of the chunk's blocks
 
   const int w = xcd_remap(blockIdx.x, per_xcd);
   if (w >= total_work) return;
@@ -69,7 +72,18 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
     if (tid == 0) { dst_local[out_base] = -1; score[out_base] = 0.f; }
     return;
   }
-  const __bf16* Kseq = K + kv.seq_base(bh) + (int64_t)g0 * kv.stride_s;
+  const __bf16* Kseq = PAGED ? K : K + kv.seq_base(bh) + (int64_t)g0 * kv.stride_s;
+  RowBases rows{};
+  const int u0 = paged.tok0 + g0;              // PAGED: the chunk's first token within its sequence
+  if (PAGED) {
+    rows = stage_row_bases(s_rb, paged, bh / kv.heads, bh % kv.heads, kv.heads, u0, u0 + L - 1, tid, NW * 64);
+    __syncthreads();
+  }
+  // address of token u of the chunk (the 16-byte piece of this thread is added by the caller)
+  auto tok_ptr = [&](int u) -> const __bf16* {
+    if (PAGED) return K + (int64_t)rows.row(u0 + u) * D;
+    return Kseq + (int64_t)u * kv.stride_s;
+  };
 
   auto swz = [](int row, int piece) -> int {
     return row * ROWB + (((piece ^ (row >> KEYSHIFT)) & (OCT - 1)) << 4);
@@ -90,8 +104,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
 #pragma unroll
       for (int it = 0; it < PIECES; ++it) {
         const int j = min(pbase + r0 + it * ROWS_PER_PASS, nB - 1);
-        stage[it].u = *reinterpret_cast<const uint4*>(Bcol + j * row_pitch);
+        stage[it].u = PAGED ? *reinterpret_cast<const uint4*>(tok_ptr(2 * j + 1) + piece * 8)
+                            : *reinterpret_cast<const uint4*>(Bcol + j * row_pitch);
       }
+    } else if (PAGED) {
+#pragma unroll
+      for (int it = 0; it < PIECES; ++it)
+        stage[it].u = *reinterpret_cast<const uint4*>(tok_ptr(2 * (pbase + r0 + it * ROWS_PER_PASS) + 1) + piece * 8);
     } else {
       const __bf16* src = Bcol + (int64_t)(pbase + r0) * row_pitch;
 #pragma unroll
@@ -129,7 +148,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
 #pragma unroll
     for (int it = 0; it < APIECES; ++it) {
       const int a = min(a0 + r0 + it * ROWS_PER_PASS, nA - 1);
-      xa[it].u = *reinterpret_cast<const uint4*>(Kseq + (int64_t)(2 * a) * kv.stride_s + piece * 8);
+      xa[it].u = *reinterpret_cast<const uint4*>(tok_ptr(2 * a) + piece * 8);
     }
     load_panel(p_first * kPanel);
     if (a0 + ABLOCK > nA) {
@@ -529,12 +548,15 @@ __global__ __launch_bounds__(kStreamThreads, 1) void match_stream_bf16_kernel(
 // ---- fp32 keys: plain FMA, LDS tiles; a correctness path, not a roofline one -------------------
 constexpr int kF32ARows = 64, kF32BRows = 32, kF32MaxD = 128;
 
+constexpr int kF32MaxBlocks = 2048 / 8 + 2;   // block-table entries of a chunk (paged input: blocks of 8 tokens or more)
+template <bool PAGED>
 __global__ __launch_bounds__(kThreads) void match_f32_kernel(
     const float* __restrict__ K, TensorView kv, int dim, int seq, int chunk, int n_chunks,
-    int a_blocks, int32_t* __restrict__ dst_local, float* __restrict__ score) {
+    int a_blocks, int32_t* __restrict__ dst_local, float* __restrict__ score, PagedSide paged) {
   __shared__ float As[kF32ARows][kF32MaxD + 1];
   __shared__ float Bs[kF32BRows][kF32MaxD + 1];
   __shared__ float inva[kF32ARows], invb[kF32BRows];
+  __shared__ int32_t s_rb[PAGED ? kF32MaxBlocks : 1];
   const int w = blockIdx.x;
   const int ab = w % a_blocks, g = (w / a_blocks) % n_chunks, bh = w / (a_blocks * n_chunks);
   const int g0 = g * chunk, L = min(chunk, seq - g0);
@@ -547,10 +569,20 @@ __global__ __launch_bounds__(kThreads) void match_f32_kernel(
     if (tid == 0) { dst_local[out_base] = -1; score[out_base] = 0.f; }
     return;
   }
-  const float* Kseq = K + kv.seq_base(bh) + (int64_t)g0 * kv.stride_s;
+  const float* Kseq = PAGED ? K : K + kv.seq_base(bh) + (int64_t)g0 * kv.stride_s;
+  RowBases rows{};
+  const int u0 = paged.tok0 + g0;
+  if (PAGED) {
+    rows = stage_row_bases(s_rb, paged, bh / kv.heads, bh % kv.heads, kv.heads, u0, u0 + L - 1, tid, kThreads);
+    __syncthreads();
+  }
+  auto tok_ptr = [&](int u) -> const float* {
+    if (PAGED) return K + (int64_t)rows.row(u0 + u) * dim;
+    return Kseq + (int64_t)u * kv.stride_s;
+  };
   for (int e = tid; e < kF32ARows * dim; e += kThreads) {
     const int row = e / dim, k = e % dim, a = a0 + row;
-    As[row][k] = (a < nA) ? Kseq[(int64_t)(2 * a) * kv.stride_s + k] : 0.f;
+    As[row][k] = (a < nA) ? tok_ptr(2 * a)[k] : 0.f;
   }
   __syncthreads();
   if (tid < kF32ARows) {
@@ -565,7 +597,7 @@ __global__ __launch_bounds__(kThreads) void match_f32_kernel(
     __syncthreads();
     for (int e = tid; e < kF32BRows * dim; e += kThreads) {
       const int row = e / dim, k = e % dim, j = pbase + row;
-      Bs[row][k] = (j < nB) ? Kseq[(int64_t)(2 * j + 1) * kv.stride_s + k] : 0.f;
+      Bs[row][k] = (j < nB) ? tok_ptr(2 * j + 1)[k] : 0.f;
     }
     __syncthreads();
     if (tid < kF32BRows) {
@@ -612,13 +644,15 @@ __global__ void dst_positions_kernel(const int32_t* __restrict__ dst_local, int3
   dst_pos[e] = (j < 0) ? -1 : g * chunk + 2 * j + 1;
 }
 
-template <int D, int NW>
+template <int D, int NW, bool PAGED>
 hipError_t launch_match_bf16_nw(const void* K, TensorView kv, int n_bh, int seq, int chunk,
-                                int32_t* dst_local, float* score, hipStream_t st) {
+                                int32_t* dst_local, float* score, hipStream_t st, PagedSide paged) {
   constexpr int ABLOCK = NW * kRowsPerWave;
-  constexpr size_t lds = (size_t)(ABLOCK > 2 * kPanel ? ABLOCK : 2 * kPanel) * D * 2 + 2 * kPanel * sizeof(float);
+  // staging area + inverse norms of two panels (+ PAGED: the pool rows of a chunk's blocks, 8 tokens or more each)
+  constexpr size_t lds = (size_t)(ABLOCK > 2 * kPanel ? ABLOCK : 2 * kPanel) * D * 2 + 2 * kPanel * sizeof(float) +
+                         (PAGED ? (2048 / 8 + 2) * sizeof(int32_t) : 0);
   static KernelSetup setup;
-  if (hipError_t e = kernel_setup(reinterpret_cast<const void*>(&match_bf16_kernel<D, NW>), lds, setup); e != hipSuccess)
+  if (hipError_t e = kernel_setup(reinterpret_cast<const void*>(&match_bf16_kernel<D, NW, PAGED>), lds, setup); e != hipSuccess)
     return e;
   const int n_chunks = div_up(seq, chunk);
   const int a_blocks = div_up(chunk / 2, ABLOCK);
@@ -626,9 +660,9 @@ hipError_t launch_match_bf16_nw(const void* K, TensorView kv, int n_bh, int seq,
   if (total > (1 << 30)) return hipErrorInvalidValue;
   const int per_xcd = div_up((int)total, 8);
   ScopedTimer t("match_bf16", st);
-  hipLaunchKernelGGL((match_bf16_kernel<D, NW>), dim3(per_xcd * 8), dim3(NW * 64), lds, st,
+  hipLaunchKernelGGL((match_bf16_kernel<D, NW, PAGED>), dim3(per_xcd * 8), dim3(NW * 64), lds, st,
                      static_cast<const __bf16*>(K), kv, seq, chunk, n_chunks, a_blocks, (int)total,
-                     per_xcd, dst_local, score);
+                     per_xcd, dst_local, score, paged);
   return hipGetLastError();
 }
 
@@ -654,21 +688,27 @@ hipError_t launch_match_stream(const void* K, TensorView kv, int n_bh, int seq, 
 
 template <int D>
 hipError_t launch_match_bf16(const void* K, TensorView kv, int n_bh, int seq, int chunk,
-                             int32_t* dst_local, float* score, hipStream_t st) {
-  if (chunk > 512) return launch_match_bf16_nw<D, 8>(K, kv, n_bh, seq, chunk, dst_local, score, st);
-  return launch_match_bf16_nw<D, 4>(K, kv, n_bh, seq, chunk, dst_local, score, st);
+                             int32_t* dst_local, float* score, hipStream_t st, PagedSide paged) {
+  if (paged.table) {
+    if (chunk > 512) return launch_match_bf16_nw<D, 8, true>(K, kv, n_bh, seq, chunk, dst_local, score, st, paged);
+    return launch_match_bf16_nw<D, 4, true>(K, kv, n_bh, seq, chunk, dst_local, score, st, paged);
+  }
+  if (chunk > 512) return launch_match_bf16_nw<D, 8, false>(K, kv, n_bh, seq, chunk, dst_local, score, st, paged);
+  return launch_match_bf16_nw<D, 4, false>(K, kv, n_bh, seq, chunk, dst_local, score, st, paged);
 }
 
 }  // namespace
 
 hipError_t launch_match(const void* K, int dtype, int dim, TensorView kv, int n_bh, int seq,
-                        int chunk, int32_t* dst_local, float* score, hipStream_t st) {
+                        int chunk, int32_t* dst_local, float* score, hipStream_t st, PagedSide paged) {
+  if (paged.table && paged.shift < 3) return hipErrorInvalidValue;   // the kernels' LDS tables hold blocks of 8 tokens or more
   if (dtype == CKV_BF16) {
-    if (dim == 128 && (chunk == 1024 || chunk == 2048) && seq % chunk == 0 && seq > 0 && kv.stride_s <= (1 << 22))
+    // (the persistent streaming kernel walks memory with fixed pitches: strided tensors only)
+    if (!paged.table && dim == 128 && (chunk == 1024 || chunk == 2048) && seq % chunk == 0 && seq > 0 && kv.stride_s <= (1 << 22))
       return chunk == 1024 ? launch_match_stream<16>(K, kv, n_bh, seq, dst_local, score, st)
                            : launch_match_stream<32>(K, kv, n_bh, seq, dst_local, score, st);
-    if (dim == 128) return launch_match_bf16<128>(K, kv, n_bh, seq, chunk, dst_local, score, st);
-    if (dim == 64) return launch_match_bf16<64>(K, kv, n_bh, seq, chunk, dst_local, score, st);
+    if (dim == 128) return launch_match_bf16<128>(K, kv, n_bh, seq, chunk, dst_local, score, st, paged);
+    if (dim == 64) return launch_match_bf16<64>(K, kv, n_bh, seq, chunk, dst_local, score, st, paged);
     return hipErrorInvalidValue;
   }
   if (dim > kF32MaxD) return hipErrorInvalidValue;
@@ -677,9 +717,12 @@ hipError_t launch_match(const void* K, int dtype, int dim, TensorView kv, int n_
   const int64_t total = (int64_t)n_bh * n_chunks * a_blocks;
   if (total > (1 << 30)) return hipErrorInvalidValue;
   ScopedTimer t("match_f32", st);
-  hipLaunchKernelGGL(match_f32_kernel, dim3((int)total), dim3(kThreads), 0, st,
-                     static_cast<const float*>(K), kv, dim, seq, chunk, n_chunks, a_blocks, dst_local,
-                     score);
+  if (paged.table)
+    hipLaunchKernelGGL(match_f32_kernel<true>, dim3((int)total), dim3(kThreads), 0, st,
+                       static_cast<const float*>(K), kv, dim, seq, chunk, n_chunks, a_blocks, dst_local, score, paged);
+  else
+    hipLaunchKernelGGL(match_f32_kernel<false>, dim3((int)total), dim3(kThreads), 0, st,
+                       static_cast<const float*>(K), kv, dim, seq, chunk, n_chunks, a_blocks, dst_local, score, paged);
   return hipGetLastError();
 }
 

@@ -93,14 +93,19 @@ constexpr int kRowsInFlightOrigin = 2;   // ... when every value row is itself r
 //                 rounding the first round would have used, so the results are bit-identical.
 enum { kMergeFull = 0, kMergeKeys = 1, kMergeOrigin = 2 };
 
-template <typename T, int D, int MODE, int MH>   // MH: capacity of the per-chunk LDS arrays (|A| = |B| <= MH)
+// PAGED: some side of the launch lives in a block pool (PagedSide): the input rows (K, V, deg_in),
+// the original values of kMergeOrigin (org.paged), the output keys (out_k_paged) or the output values
+// and degrees (out_v_paged), each decided by its table pointer / flag at run time; the pool rows of the
+// blocks a workgroup touches are staged in LDS (blocks of 8 tokens or more).
+template <typename T, int D, int MODE, int MH, bool PAGED>   // MH: capacity of the per-chunk LDS arrays (|A| = |B| <= MH)
 __global__ __launch_bounds__(kThreads) void merge_kernel(
     const T* __restrict__ K, const T* __restrict__ V, const int32_t* __restrict__ deg_in, TensorView in,
     int seq, int chunk, int n_chunks, float r, const int32_t* __restrict__ dst_local,
     const float* __restrict__ score, T* __restrict__ K_out, T* __restrict__ V_out,
     int32_t* __restrict__ deg_out, TensorView out, int64_t deg_out_stride, int32_t* __restrict__ map_out,
     int64_t deg_in_stride, int64_t map_stride, int map_offset, const int2* __restrict__ sel_table,
-    int16_t* __restrict__ lists_out, ValueOrigin org, int parts) {
+    int16_t* __restrict__ lists_out, ValueOrigin org, int parts, PagedSide pin, PagedSide pout, int out_k_paged,
+    int out_v_paged) {
   constexpr int E = Row<T>::E;
   constexpr int LPR = D / E;                 // lanes per row
   constexpr int NRG = kThreads / LPR;        // row groups per workgroup
@@ -123,6 +128,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   // value rows of its own token and of its first merged source come from)
   constexpr bool DESC = (MODE == kMergeOrigin) && (MH <= 512);
   __shared__ uint2 s_desc[DESC ? 3 * 2 * MH : 1];
+  __shared__ int32_t s_rb_in[PAGED ? 2 * MH / 8 + 2 : 1];
+  __shared__ int32_t s_rb_org[(PAGED && MODE == kMergeOrigin) ? 4 * MH / 8 + 2 : 1];
+  __shared__ int32_t s_rb_out[PAGED ? 2 * MH / 8 + 2 : 1];
 
   // `parts` workgroups share a chunk when the launch would otherwise leave most of the chip idle:
   // each repeats the (cheap) bookkeeping and emits every parts-th group of output rows.
@@ -144,6 +152,21 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     out_base = g * chunk_out(chunk, r);
   }
   const int n_out = L - m;
+  RowBases rb_in{}, rb_org{}, rb_out{};
+  const bool in_paged = PAGED && pin.table != nullptr;
+  const bool org_paged = PAGED && MODE == kMergeOrigin && org.paged.table != nullptr;
+  const bool ok_paged = PAGED && out_k_paged, ov_paged = PAGED && out_v_paged;
+  if (PAGED) {   // (the barriers of the bookkeeping below come before the first use)
+    const int b = bh / in.heads, h = bh % in.heads;
+    if (in_paged && L > 0) rb_in = stage_row_bases(s_rb_in, pin, b, h, in.heads, pin.tok0 + g0, pin.tok0 + g0 + L - 1, tid, kThreads);
+    if (org_paged) {
+      const int t_lo = 2 * g * chunk, t_hi = min(org.seq0, t_lo + 2 * chunk);
+      if (t_hi > t_lo)
+        rb_org = stage_row_bases(s_rb_org, org.paged, b, h, in.heads, org.paged.tok0 + t_lo, org.paged.tok0 + t_hi - 1, tid, kThreads);
+    }
+    if ((ok_paged || ov_paged) && n_out > 0)
+      rb_out = stage_row_bases(s_rb_out, pout, b, h, in.heads, pout.tok0 + out_base, pout.tok0 + out_base + n_out - 1, tid, kThreads);
+  }
   const int n_src = n_sources(seq, chunk);
   const int64_t src_base = (int64_t)bh * n_src + (int64_t)g * (chunk >> 1);
   const int nA_pad = (nA + 7) & ~7;
@@ -337,18 +360,40 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   // ---- emit rows: every row group works on U output rows at once; the loads of their own rows
   // and of their first merged source are all in flight before anything is consumed ---------------
   const int rg = tid / LPR, piece = tid % LPR;
-  const T* Kin = K + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E;
-  const T* Vin = (MODE == kMergeFull) ? V + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E : nullptr;
-  T* Ko = K_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
-  T* Vo = (MODE == kMergeKeys) ? nullptr : V_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
-  const int32_t* dseq = deg_in ? deg_in + (int64_t)bh * deg_in_stride + g0 : nullptr;
-  int32_t* dout = deg_out + (int64_t)bh * deg_out_stride + out_base;
+  const T* Kin = in_paged ? K + piece * E : K + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E;
+  const T* Vin = (MODE != kMergeFull) ? nullptr
+                 : in_paged ? V + piece * E : V + in.seq_base(bh) + (int64_t)g0 * in.stride_s + piece * E;
+  T* Ko = ok_paged ? K_out + piece * E : K_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
+  T* Vo = (MODE == kMergeKeys) ? nullptr
+          : ov_paged ? V_out + piece * E : V_out + out.seq_base(bh) + (int64_t)out_base * out.stride_s + piece * E;
+  const int32_t* dseq = !deg_in ? nullptr : in_paged ? deg_in : deg_in + (int64_t)bh * deg_in_stride + g0;
+  int32_t* dout = ov_paged ? deg_out : deg_out + (int64_t)bh * deg_out_stride + out_base;
+  // element offset of input row u / output row o of this chunk from Kin, Vin / Ko, Vo, and the index
+  // of their degrees in dseq / dout.  An output row whose block lies outside the pool is not written.
+  const int u_in0 = pin.tok0 + g0, u_out0 = pout.tok0 + out_base;
+  auto in_off = [&](int u) -> int64_t { return in_paged ? (int64_t)rb_in.row(u_in0 + u) * D : (int64_t)u * in.stride_s; };
+  auto in_deg = [&](int u) -> int { return in_paged ? dseq[rb_in.row(u_in0 + u)] : dseq[u]; };
+  auto ok_off = [&](int o) -> int64_t { return ok_paged ? (int64_t)rb_out.row(u_out0 + o) * D : (int64_t)o * out.stride_s; };
+  auto ov_off = [&](int o) -> int64_t { return ov_paged ? (int64_t)rb_out.row(u_out0 + o) * D : (int64_t)o * out.stride_s; };
+  auto out_ok = [&](int o) -> bool { return !(ok_paged || ov_paged) || rb_out.base_of(u_out0 + o) >= 0; };
+  auto put_deg = [&](int o, int d) {
+    if (ov_paged) dout[rb_out.row(u_out0 + o)] = d;
+    else dout[o] = d;
+  };
 
   // The value row of input row p of this chunk.  kMergeFull: a load.  kMergeOrigin: the previous
   // round's centroid p, rebuilt: p is B token j of previous-round chunk 2g+h (a one-token tail chunk
   // kept its only token); its own row and its first member are loaded at once, the rest on demand.
-  const T* V0p = (MODE == kMergeOrigin) ? static_cast<const T*>(org.V0) + org.view0.seq_base(bh) + piece * E : nullptr;
-  const int32_t* d0p = (MODE == kMergeOrigin && org.deg0) ? org.deg0 + (int64_t)bh * org.view0.deg_stride : nullptr;
+  const T* V0p = (MODE != kMergeOrigin) ? nullptr
+                 : org_paged ? static_cast<const T*>(org.V0) + piece * E
+                             : static_cast<const T*>(org.V0) + org.view0.seq_base(bh) + piece * E;
+  const int32_t* d0p = (MODE == kMergeOrigin && org.deg0)
+                           ? (org_paged ? org.deg0 : org.deg0 + (int64_t)bh * org.view0.deg_stride) : nullptr;
+  // original value row / degree of token t of the first round's clustered range
+  auto v0_off = [&](int t) -> int64_t {
+    return org_paged ? (int64_t)rb_org.row(org.paged.tok0 + t) * D : (int64_t)t * org.view0.stride_s;
+  };
+  auto d0_at = [&](int t) -> int { return org_paged ? d0p[rb_org.row(org.paged.tok0 + t)] : d0p[t]; };
   constexpr int kEager = 1;   // members of a previous-round cluster loaded together with its own row
   struct VLoad {
     Raw b, m[kEager];
@@ -359,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   auto v_issue = [&](int p) -> VLoad {
     VLoad x;
     if (MODE == kMergeFull) {
-      x.b = Row<T>::load_raw(Vin + (int64_t)p * in.stride_s);
+      x.b = Row<T>::load_raw(Vin + in_off(p));
       x.n = 0;
     } else if (MODE == kMergeOrigin) {
       const int h = (p >= half) ? 1 : 0, jj = p - h * half;
@@ -368,14 +413,14 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       const int tb = x.base + (single ? 0 : 2 * jj + 1);
       x.n = single ? 0 : (int)s0_cnt[h][jj];
       x.mem = &s0_mem[h][s0_start[h][jj]];
-      x.b = Row<T>::load_raw(V0p + (int64_t)tb * org.view0.stride_s);
-      x.db = d0p ? d0p[tb] : 1;
+      x.b = Row<T>::load_raw(V0p + v0_off(tb));
+      x.db = d0p ? d0_at(tb) : 1;
 #pragma unroll
       for (int q = 0; q < kEager; ++q) {
         if (q < x.n) {
           const int ta = x.base + 2 * (int)x.mem[q];
-          x.m[q] = Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s);
-          x.dm[q] = d0p ? d0p[ta] : 1;
+          x.m[q] = Row<T>::load_raw(V0p + v0_off(ta));
+          x.dm[q] = d0p ? d0_at(ta) : 1;
         }
       }
     }
@@ -390,12 +435,12 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       x.base = t0 + ((tb_rel >= chunk) ? chunk : 0);
       x.n = (int)(w.y & 0xffffu);
       x.mem = &s0_mem[0][0] + (w.y >> 16);
-      x.b = Row<T>::load_raw(V0p + (int64_t)tb * org.view0.stride_s);
-      x.db = d0p ? d0p[tb] : 1;
+      x.b = Row<T>::load_raw(V0p + v0_off(tb));
+      x.db = d0p ? d0_at(tb) : 1;
       static_assert(kEager == 1, "one resolved member per cluster");
       if (x.n > 0) {
-        x.m[0] = Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s);
-        x.dm[0] = d0p ? d0p[ta] : 1;
+        x.m[0] = Row<T>::load_raw(V0p + v0_off(ta));
+        x.dm[0] = d0p ? d0_at(ta) : 1;
       }
     }
     return x;
@@ -416,8 +461,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       }
     for (int q = kEager; q < x.n; ++q) {
       const int ta = x.base + 2 * (int)x.mem[q];
-      const int da = d0p ? d0p[ta] : 1;
-      Row<T>::template fma_into<WIDE>(a, Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s), da);
+      const int da = d0p ? d0_at(ta) : 1;
+      Row<T>::template fma_into<WIDE>(a, Row<T>::load_raw(V0p + v0_off(ta)), da);
       nd += da;
     }
     return Row<T>::div_raw(a, nd);
@@ -473,8 +518,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       x.tok[u] = w.tok[u];
       x.nmem[u] = w.nmem[u];
       x.first[u] = w.first[u];
-      x.kb[u] = Row<T>::load_raw(Kin + (int64_t)w.tok[u] * in.stride_s);
-      x.km[u] = Row<T>::load_raw(Kin + (int64_t)w.mem0[u] * in.stride_s);
+      x.kb[u] = Row<T>::load_raw(Kin + in_off(w.tok[u]));
+      x.km[u] = Row<T>::load_raw(Kin + in_off(w.mem0[u]));
       if constexpr (DESC) {
         x.vb[u] = v_issue_resolved(w.wb[u]);
         x.vm[u] = v_issue_resolved(w.wm[u]);
@@ -482,8 +527,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
         x.vb[u] = v_issue(w.tok[u]);
         x.vm[u] = v_issue(w.mem0[u]);
       }
-      x.du[u] = dseq ? dseq[w.tok[u]] : 1;
-      x.dm[u] = dseq ? dseq[w.mem0[u]] : 1;
+      x.du[u] = dseq ? in_deg(w.tok[u]) : 1;
+      x.dm[u] = dseq ? in_deg(w.mem0[u]) : 1;
     }
     return x;
   };
@@ -494,10 +539,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     for (int u = 0; u < U; ++u) {
       if (!x.valid[u]) continue;
       const int o = x.ob + u * NRG + rg;
+      if (PAGED && !out_ok(o)) continue;
       if (x.nmem[u] == 0) {  // untouched token: bit copy
-        Row<T>::store_raw(Ko + (int64_t)o * out.stride_s, x.kb[u]);
-        if constexpr (MODE != kMergeKeys) Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, v_finish(wide_c, x.vb[u]));
-        if (piece == 0) dout[o] = x.du[u];
+        Row<T>::store_raw(Ko + ok_off(o), x.kb[u]);
+        if constexpr (MODE != kMergeKeys) Row<T>::store_raw(Vo + ov_off(o), v_finish(wide_c, x.vb[u]));
+        if (piece == 0) put_deg(o, x.du[u]);
         continue;
       }
       Acc ak[E], av[E];
@@ -512,15 +558,15 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       int ndeg = x.du[u] + x.dm[u];
       for (int q = 1; q < x.nmem[u]; ++q) {
         const int ua = 2 * (int)s_members[x.first[u] + q];
-        const int da = dseq ? dseq[ua] : 1;
-        const Raw kx = Row<T>::load_raw(Kin + (int64_t)ua * in.stride_s);
+        const int da = dseq ? in_deg(ua) : 1;
+        const Raw kx = Row<T>::load_raw(Kin + in_off(ua));
         Row<T>::template fma_into<WIDE>(ak, kx, da);
         if constexpr (MODE != kMergeKeys) Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, v_issue(ua)), da);
         ndeg += da;
       }
-      Row<T>::store_div(Ko + (int64_t)o * out.stride_s, ak, ndeg);
-      if constexpr (MODE != kMergeKeys) Row<T>::store_div(Vo + (int64_t)o * out.stride_s, av, ndeg);
-      if (piece == 0) dout[o] = ndeg;
+      Row<T>::store_div(Ko + ok_off(o), ak, ndeg);
+      if constexpr (MODE != kMergeKeys) Row<T>::store_div(Vo + ov_off(o), av, ndeg);
+      if (piece == 0) put_deg(o, ndeg);
     }
   };
   // kMergeOrigin: the same sums in the same order as v_finish, for several clusters in lock step.
@@ -554,8 +600,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       for (int c = 0; c < C; ++c)
         if (q < n[c]) {
           const int ta = cl[c].base + 2 * (int)cl[c].mem[q];
-          r[c] = Row<T>::load_raw(V0p + (int64_t)ta * org.view0.stride_s);
-          d[c] = d0p ? d0p[ta] : 1;
+          r[c] = Row<T>::load_raw(V0p + v0_off(ta));
+          d[c] = d0p ? d0_at(ta) : 1;
         }
 #pragma unroll
       for (int c = 0; c < C; ++c)
@@ -584,10 +630,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       for (int u = 0; u < U; ++u) {
         if (!x.valid[u]) continue;
         const int o = x.ob + u * NRG + rg;
+        if (PAGED && !out_ok(o)) continue;
         if (x.nmem[u] == 0) {  // untouched token: bit copy of the key; its value row is one cluster
-          Row<T>::store_raw(Ko + (int64_t)o * out.stride_s, x.kb[u]);
-          Row<T>::store_raw(Vo + (int64_t)o * out.stride_s, vr[2 * u]);
-          if (piece == 0) dout[o] = x.du[u];
+          Row<T>::store_raw(Ko + ok_off(o), x.kb[u]);
+          Row<T>::store_raw(Vo + ov_off(o), vr[2 * u]);
+          if (piece == 0) put_deg(o, x.du[u]);
           continue;
         }
         Acc ak[E], av[E];
@@ -600,15 +647,15 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
         int ndeg = x.du[u] + x.dm[u];
         for (int q = 1; q < x.nmem[u]; ++q) {
           const int ua = 2 * (int)s_members[x.first[u] + q];
-          const int da = dseq ? dseq[ua] : 1;
-          const Raw kx = Row<T>::load_raw(Kin + (int64_t)ua * in.stride_s);
+          const int da = dseq ? in_deg(ua) : 1;
+          const Raw kx = Row<T>::load_raw(Kin + in_off(ua));
           Row<T>::template fma_into<WIDE>(ak, kx, da);
           Row<T>::template fma_into<WIDE>(av, v_finish(wide_c, v_issue(ua)), da);
           ndeg += da;
         }
-        Row<T>::store_div(Ko + (int64_t)o * out.stride_s, ak, ndeg);
-        Row<T>::store_div(Vo + (int64_t)o * out.stride_s, av, ndeg);
-        if (piece == 0) dout[o] = ndeg;
+        Row<T>::store_div(Ko + ok_off(o), ak, ndeg);
+        Row<T>::store_div(Vo + ov_off(o), av, ndeg);
+        if (piece == 0) put_deg(o, ndeg);
       }
     }
   };
@@ -640,11 +687,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   {
     int big = 0;
     if (deg_in) {
-      for (int u = tid; u < L; u += kThreads) big |= dseq[u] > 256;
+      for (int u = tid; u < L; u += kThreads) big |= in_deg(u) > 256;
     }
     if (MODE == kMergeOrigin && d0p) {
       const int t_lo = 2 * g * chunk, t_hi = min(org.seq0, t_lo + 2 * chunk);
-      for (int t = t_lo + tid; t < t_hi; t += kThreads) big |= d0p[t] > 256;
+      for (int t = t_lo + tid; t < t_hi; t += kThreads) big |= d0_at(t) > 256;
     }
     wide = __syncthreads_or(big) != 0;
   }
@@ -695,7 +742,7 @@ __global__ void edges_kernel(const unsigned char* __restrict__ K, const unsigned
                              unsigned char* __restrict__ K_out, unsigned char* __restrict__ V_out,
                              int32_t* __restrict__ deg_out, TensorView out, int64_t deg_out_stride, int out_len,
                              int32_t* __restrict__ map_out, int n_head, int n_tail, int pieces_per_row,
-                             int elem_bytes, int64_t total) {
+                             int elem_bytes, int64_t total, PagedSide pin, PagedSide pok, PagedSide pov) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= total) return;
   const int piece = (int)(e % pieces_per_row);
@@ -704,12 +751,30 @@ __global__ void edges_kernel(const unsigned char* __restrict__ K, const unsigned
   const int k = (int)(row % n_edge), bh = (int)(row / n_edge);
   const int t_in = k < n_head ? k : in_len - n_tail + (k - n_head);
   const int t_out = k < n_head ? k : out_len - n_tail + (k - n_head);
-  const int64_t so = (in.seq_base(bh) + (int64_t)t_in * in.stride_s) * elem_bytes + piece * 16;
+  const int b = bh / in.heads, h = bh % in.heads;
+  // pool row of token u of this (batch, head) through a side's block table; -1 outside the pool
+  auto pool_row = [&](const PagedSide& pg, int u) -> int64_t {
+    const int blk = ((u >> pg.shift) < pg.max_blocks) ? pg.table[(int64_t)b * pg.max_blocks + (u >> pg.shift)] : -1;
+    if ((unsigned)blk >= (unsigned)pg.n_blocks) return -1;
+    return (((int64_t)blk * in.heads + h) << pg.shift) + (u & ((1 << pg.shift) - 1));
+  };
+  const int64_t row_bytes = (int64_t)pieces_per_row * 16;
+  int64_t ri = 0, rk = 0, rv = 0;
+  if (pin.table) ri = pool_row(pin, pin.tok0 + t_in);
+  if (pok.table) rk = pool_row(pok, pok.tok0 + t_out);
+  if (pov.table) rv = pool_row(pov, pov.tok0 + t_out);
+  if (ri < 0) ri = 0;                      // a block outside the pool reads as row 0 and is not written
+  const int64_t so = pin.table ? ri * row_bytes + piece * 16
+                               : (in.seq_base(bh) + (int64_t)t_in * in.stride_s) * elem_bytes + piece * 16;
   const int64_t dof = (out.seq_base(bh) + (int64_t)t_out * out.stride_s) * elem_bytes + piece * 16;
-  *reinterpret_cast<uint4*>(K_out + dof) = *reinterpret_cast<const uint4*>(K + so);
-  *reinterpret_cast<uint4*>(V_out + dof) = *reinterpret_cast<const uint4*>(V + so);
+  const int64_t dk = pok.table ? rk * row_bytes + piece * 16 : dof;
+  const int64_t dv = pov.table ? rv * row_bytes + piece * 16 : dof;
+  if (rk >= 0) *reinterpret_cast<uint4*>(K_out + dk) = *reinterpret_cast<const uint4*>(K + so);
+  if (rv >= 0) *reinterpret_cast<uint4*>(V_out + dv) = *reinterpret_cast<const uint4*>(V + so);
   if (piece == 0) {
-    deg_out[(int64_t)bh * deg_out_stride + t_out] = deg_in ? deg_in[(int64_t)bh * in.deg_stride + t_in] : 1;
+    const int d = !deg_in ? 1 : pin.table ? deg_in[ri] : deg_in[(int64_t)bh * in.deg_stride + t_in];
+    if (pov.table) { if (rv >= 0) deg_out[rv] = d; }
+    else deg_out[(int64_t)bh * deg_out_stride + t_out] = d;
     if (map_out) map_out[(int64_t)bh * in_len + t_in] = t_out;
   }
 }
@@ -754,7 +819,7 @@ hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, T
                           void* K_out, void* V_out, int32_t* deg_out, TensorView out,
                           int64_t deg_out_stride, int32_t* map_out, int64_t deg_in_stride, int64_t map_stride,
                           int map_offset, const int32_t* sel_table, int16_t* lists_out, const ValueOrigin* org,
-                          hipStream_t st) {
+                          hipStream_t st, PagedSide pin, PagedSide pok, PagedSide pov) {
   const int n_chunks = div_up(seq, chunk);
   const int64_t total = (int64_t)n_bh * n_chunks;
   if (total > (1 << 30)) return hipErrorInvalidValue;
@@ -762,17 +827,29 @@ hipError_t launch_merge_t(const void* K, const void* V, const int32_t* deg_in, T
   // small launches: split every chunk's rows over several workgroups, aiming at 4 workgroups per CU
   int parts = 1;
   while (parts < 8 && total * parts < 1024) parts *= 2;
-#define CKV_LAUNCH_MH(MODE, MH)                                                                               \
-  hipLaunchKernelGGL((merge_kernel<T, D, MODE, MH>), dim3((int)(total * parts)), dim3(kThreads), 0, st,      \
+  // any side in a block pool: the kernel variant that stages block tables (blocks of 8 tokens or more)
+  const bool any_paged = pin.table || pok.table || pov.table || o.paged.table;
+  if (any_paged && ((pin.table && pin.shift < 3) || (pok.table && pok.shift < 3) || (pov.table && pov.shift < 3) ||
+                    (o.paged.table && o.paged.shift < 3)))
+    return hipErrorInvalidValue;
+  const PagedSide pout = pok.table ? pok : pov;
+#define CKV_LAUNCH_MH(MODE, MH, PG)                                                                           \
+  hipLaunchKernelGGL((merge_kernel<T, D, MODE, MH, PG>), dim3((int)(total * parts)), dim3(kThreads), 0, st,  \
                      static_cast<const T*>(K), static_cast<const T*>(V), deg_in, in, seq, chunk, n_chunks, r, \
                      dst_local, score, static_cast<T*>(K_out), static_cast<T*>(V_out), deg_out, out,          \
                      deg_out_stride, map_out, deg_in_stride, map_stride, map_offset,                          \
-                     reinterpret_cast<const int2*>(sel_table), lists_out, o, parts)
+                     reinterpret_cast<const int2*>(sel_table), lists_out, o, parts, pin, pout,                \
+                     pok.table != nullptr, pov.table != nullptr)
   // smaller LDS arrays for chunks of up to 1024 tokens: more workgroups per CU
-#define CKV_LAUNCH(MODE)                                       \
-  do {                                                         \
-    if (chunk <= kMaxHalf) CKV_LAUNCH_MH(MODE, kMaxHalf / 2);  \
-    else CKV_LAUNCH_MH(MODE, kMaxHalf);                        \
+#define CKV_LAUNCH(MODE)                                                    \
+  do {                                                                      \
+    if (any_paged) {                                                        \
+      if (chunk <= kMaxHalf) CKV_LAUNCH_MH(MODE, kMaxHalf / 2, true);       \
+      else CKV_LAUNCH_MH(MODE, kMaxHalf, true);                             \
+    } else {                                                                \
+      if (chunk <= kMaxHalf) CKV_LAUNCH_MH(MODE, kMaxHalf / 2, false);      \
+      else CKV_LAUNCH_MH(MODE, kMaxHalf, false);                            \
+    }                                                                       \
   } while (0)
   if (org) {
     ScopedTimer t(sizeof(T) == 2 ? "merge_origin_bf16" : "merge_origin_f32", st);
@@ -795,11 +872,12 @@ hipError_t launch_merge(const void* K, const void* V, const int32_t* deg_in, int
                         const int32_t* dst_local, const float* score, void* K_out, void* V_out,
                         int32_t* deg_out, TensorView out, int64_t deg_out_stride, int32_t* map_out,
                         int64_t deg_in_stride, int64_t map_stride, int map_offset, const int32_t* sel_table,
-                        int16_t* lists_out, const ValueOrigin* org, hipStream_t st) {
+                        int16_t* lists_out, const ValueOrigin* org, hipStream_t st, PagedSide paged_in,
+                        PagedSide paged_out_k, PagedSide paged_out_v) {
 #define CKV_MERGE(T, DD)                                                                             \
   return launch_merge_t<T, DD>(K, V, deg_in, in, n_bh, seq, chunk, r, dst_local, score, K_out, V_out, \
                                deg_out, out, deg_out_stride, map_out, deg_in_stride, map_stride, map_offset, \
-                               sel_table, lists_out, org, st)
+                               sel_table, lists_out, org, st, paged_in, paged_out_k, paged_out_v)
   if (dtype == CKV_BF16) {
     if (dim == 128) CKV_MERGE(__bf16, 128);
     if (dim == 64) CKV_MERGE(__bf16, 64);
@@ -839,7 +917,7 @@ hipError_t launch_copy_rows(const void* src, TensorView in, void* dst, TensorVie
 hipError_t launch_edges(const void* K, const void* V, const int32_t* deg_in, TensorView in, int in_len, void* K_out,
                         void* V_out, int32_t* deg_out, TensorView out, int64_t deg_out_stride, int out_len,
                         int32_t* map_out, int n_head, int n_tail, int n_bh, int row_bytes, int elem_bytes,
-                        hipStream_t st) {
+                        hipStream_t st, PagedSide paged_in, PagedSide paged_out_k, PagedSide paged_out_v) {
   const int ppr = row_bytes / 16;
   const int64_t total = (int64_t)n_bh * (n_head + n_tail) * ppr;
   if (total == 0) return hipSuccess;
@@ -847,7 +925,8 @@ hipError_t launch_edges(const void* K, const void* V, const int32_t* deg_in, Ten
   hipLaunchKernelGGL(edges_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                      static_cast<const unsigned char*>(K), static_cast<const unsigned char*>(V), deg_in, in, in_len,
                      static_cast<unsigned char*>(K_out), static_cast<unsigned char*>(V_out), deg_out, out,
-                     deg_out_stride, out_len, map_out, n_head, n_tail, ppr, elem_bytes, total);
+                     deg_out_stride, out_len, map_out, n_head, n_tail, ppr, elem_bytes, total, paged_in, paged_out_k,
+                     paged_out_v);
   return hipGetLastError();
 }
 

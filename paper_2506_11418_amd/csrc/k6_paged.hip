@@ -34,9 +34,9 @@ __global__ void paged_move_kernel(unsigned char* __restrict__ K_pool, unsigned c
   const int64_t doff = ((int64_t)b * heads + h) * view.deg_stride + t;
   if (TO_POOL) {
     if (!in_pool) return;
-    stg16_stream(K_pool + poff, *reinterpret_cast<const uint4*>(K + toff));
-    stg16_stream(V_pool + poff, *reinterpret_cast<const uint4*>(V + toff));
-    if (piece == 0 && deg_pool) deg_pool[row] = deg ? deg[doff] : 1;
+    if (K) stg16_stream(K_pool + poff, *reinterpret_cast<const uint4*>(K + toff));
+    if (V) stg16_stream(V_pool + poff, *reinterpret_cast<const uint4*>(V + toff));
+    if (piece == 0 && deg_pool && (deg || K)) deg_pool[row] = deg ? deg[doff] : 1;
   } else {
     const uint4 zero = make_uint4(0, 0, 0, 0);
     *reinterpret_cast<uint4*>(K + toff) = in_pool ? ldg16_stream(K_pool + poff) : zero;
@@ -78,15 +78,20 @@ __global__ void paged_bump_lens_kernel(int32_t* __restrict__ lens, const int32_t
 }
 
 __global__ void paged_release_kernel(int32_t* __restrict__ table, int max_blocks, int n_b, int keep_blocks,
-                                     int old_blocks, int32_t* __restrict__ freed, int32_t* __restrict__ lens,
-                                     int seq) {
+                                     int old_blocks, int32_t* __restrict__ freed, int freed_stride,
+                                     int32_t* __restrict__ lens, int seq) {
   const int n_freed = old_blocks - keep_blocks;
+  const int width = freed_stride > n_freed ? freed_stride : n_freed;   // per sequence: released entries, then padding
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e < n_b * n_freed) {
-    const int b = e / n_freed, k = e % n_freed;
-    int32_t* slot = table + (int64_t)b * max_blocks + keep_blocks + k;
-    if (freed) freed[e] = *slot;
-    *slot = -1;
+  if (width > 0 && e < n_b * width) {
+    const int b = e / width, k = e % width;
+    if (k < n_freed) {
+      int32_t* slot = table + (int64_t)b * max_blocks + keep_blocks + k;
+      if (freed) freed[(int64_t)b * freed_stride + k] = *slot;
+      *slot = -1;
+    } else if (freed) {
+      freed[(int64_t)b * freed_stride + k] = -1;
+    }
   }
   if (lens && e < n_b) lens[e] = seq;
 }
@@ -130,10 +135,11 @@ hipError_t launch_paged_append(const void* k_new, const void* v_new, void* K_poo
 hipError_t launch_paged_scatter(const void* K, const void* V, const int32_t* deg, TensorView in, int n_b, int heads,
                                 int seq, int row_bytes, int elem_bytes, void* K_pool, void* V_pool,
                                 int32_t* deg_pool, int32_t* table, int max_blocks, int shift, int n_blocks,
-                                int keep_blocks, int old_blocks, int32_t* freed, int32_t* lens, hipStream_t st) {
+                                int keep_blocks, int old_blocks, int32_t* freed, int freed_stride, int32_t* lens,
+                                hipStream_t st) {
   const int ppr = row_bytes / 16;
   const int64_t total = (int64_t)n_b * heads * seq * ppr;
-  if (total > 0) {
+  if (total > 0 && (K || V || deg)) {
     ScopedTimer t("paged_scatter", st);
     hipLaunchKernelGGL(paged_move_kernel<true>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        static_cast<unsigned char*>(K_pool), static_cast<unsigned char*>(V_pool), deg_pool, table,
@@ -144,12 +150,14 @@ hipError_t launch_paged_scatter(const void* K, const void* V, const int32_t* deg
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  const int work = n_b * (old_blocks - keep_blocks);
+  const int n_freed = old_blocks - keep_blocks;
+  const int width = (freed && freed_stride > n_freed) ? freed_stride : n_freed;
+  const int work = n_b * width;
   const int n = work > n_b ? work : n_b;
   if (n <= 0) return hipSuccess;
   ScopedTimer t("paged_release", st);
   hipLaunchKernelGGL(paged_release_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, table, max_blocks,
-                     n_b, keep_blocks, old_blocks, freed, lens, seq);
+                     n_b, keep_blocks, old_blocks, freed, freed ? freed_stride : 0, lens, seq);
   return hipGetLastError();
 }
 

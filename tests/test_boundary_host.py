@@ -113,15 +113,35 @@ def test_plan_with_selection_over_the_whole_sequence(seq, chunk, rounds, n_sink,
 def test_paged_plan_and_argument_checks():
     L = ckv.lib()
     pl = ckv.PagedLayout(2, 8, 128, ckv.BF16, 16, 300, 1000)
-    out_seq, n_freed, nbytes = ckv.paged_compress_plan(pl, 4096 + 80, ckv.make_params(256, 0.25, n_sink=16, n_recent=64))
+    par = ckv.make_params(256, 0.25, n_sink=16, n_recent=64)
+    out_seq, n_freed, nbytes = ckv.paged_compress_plan(pl, 4096 + 80, par)
     assert out_seq == round_lengths(4176, 256, [1.0, 1.0], 16, 64)[-1]
     assert n_freed == -(-4176 // 16) - (-(-out_seq // 16))
-    # staging: the gathered cache and the result, K and V, plus degrees, plus ckv_compress's own workspace
-    assert nbytes >= 2 * 8 * (4176 + out_seq) * (2 * 128 * 2 + 4)
+    # nothing is gathered: the scratch is ckv_compress's own workspace plus, for this two-round schedule that
+    # stays below the size where values are deferred, no staging at all (the last round writes the pages directly)
+    inner = ckv.plan(_lay(batch=2, heads=8, seq=4176), par).workspace_bytes
+    assert inner <= nbytes < inner + 4096
+    # a single round reads the pools while it writes: keys, values and degrees of the result are staged
+    one = ckv.make_params(256, rounds=[0.5])
+    o1, _, n1 = ckv.paged_compress_plan(pl, 4176, one)
+    assert n1 >= ckv.plan(_lay(batch=2, heads=8, seq=4176), one).workspace_bytes + 2 * 8 * o1 * (2 * 128 * 2 + 4)
+    # one deferred pair: the last round still reads the original values and degrees, the keys go straight to the pages
+    dp = ckv.make_params(256, 0.25, route="defer_always")
+    o2, _, n2 = ckv.paged_compress_plan(pl, 4096, dp)
+    base = ckv.plan(_lay(batch=2, heads=8, seq=4096), dp).workspace_bytes
+    assert base + 2 * 8 * o2 * (128 * 2 + 4) <= n2 < base + 2 * 8 * o2 * (128 * 2 + 4) + 4096
+    # per-sequence lengths: lengths after compression per sequence, the most blocks any sequence releases
+    outs, nf, _ = ckv.paged_compress_plan(pl, 0, ckv.make_params(256, 0.5), seq_lens=[4096, 1000])
+    assert outs == [round_lengths(4096, 256, [1.0])[-1], round_lengths(1000, 256, [1.0])[-1]]
+    assert nf == 256 - 128
     z, a = C.c_void_p(0), C.c_void_p(4096)
     bad = ckv.PagedLayout(2, 8, 128, ckv.BF16, 24, 300, 1000)              # block size not a power of two
-    assert L.ckv_paged_compress_plan(C.byref(bad), 4096, C.byref(ckv.make_params(256, 0.5)), None, None, None) == -2
-    assert L.ckv_paged_compress_plan(C.byref(pl), 16 * 300 + 1, C.byref(ckv.make_params(256, 0.5)), None, None, None) == -2
+    assert L.ckv_paged_compress_plan(C.byref(bad), 4096, None, C.byref(ckv.make_params(256, 0.5)), None, None, None) == -2
+    assert L.ckv_paged_compress_plan(C.byref(pl), 16 * 300 + 1, None, C.byref(ckv.make_params(256, 0.5)), None, None, None) == -2
+    small = ckv.PagedLayout(2, 8, 128, ckv.BF16, 4, 3000, 4000)            # blocks under 8 tokens: no kernel
+    assert L.ckv_paged_compress_plan(C.byref(small), 4096, None, C.byref(ckv.make_params(256, 0.5)), None, None, None) == -5
+    two = (C.c_int32 * 2)(4096, 0)                                         # an empty sequence
+    assert L.ckv_paged_compress_plan(C.byref(pl), 0, two, C.byref(ckv.make_params(256, 0.5)), None, None, None) == -2
     n = C.c_size_t(0)
     assert L.ckv_paged_decode_attn_workspace(C.byref(pl), 32, 4096, C.byref(n)) == 0 and n.value > 0
     assert L.ckv_paged_decode_attn_workspace(C.byref(pl), 30, 4096, C.byref(n)) == -2
@@ -132,7 +152,9 @@ def test_paged_plan_and_argument_checks():
     lay = _lay(batch=2, heads=8, seq=512)
     assert L.ckv_paged_gather(a, a, z, a, C.byref(pl), 1024, a, a, z, C.byref(lay), z) == -2                 # seq > out->seq
     assert L.ckv_paged_scatter(a, a, z, C.byref(lay), a, a, z, a, C.byref(pl), 100, z, z, z) == -2           # old_seq < seq
-    assert L.ckv_paged_compress(a, a, z, a, z, C.byref(pl), 4096, C.byref(ckv.make_params(256, 0.5)), z, a, 1 << 30, z) == -1
+    assert L.ckv_paged_compress(a, a, z, a, z, C.byref(pl), 4096, None, C.byref(ckv.make_params(256, 0.5)), z, 0, a, 1 << 30, z) == -1
+    assert L.ckv_paged_compress(a, a, a, a, z, C.byref(pl), 4096, None, C.byref(ckv.make_params(256, 0.5)), z, 0, a, 1 << 10, z) == -4
+    assert L.ckv_paged_compress(a, a, a, a, z, C.byref(pl), 4096, None, C.byref(ckv.make_params(256, 0.5)), a, 10, a, 1 << 30, z) == -2   # freed rows too short
 
 
 def test_plan_workspace_grows_with_rounds():
