@@ -156,40 +156,60 @@ def test_serving_decode_batch16_with_appended_tokens():
         assert_rows_close(f64(o_full[b]), ref_full, ATTN_TOL, f"uncompressed b{b}")
 
 
-# ---- extreme context: 1M tokens, chunk 2048 ------------------------------------------------------
-def test_extreme_context_chunk2048():
-    """Two KV heads of a 1 048 576-token cache (alpha 0.95), chunk 2048, retain 25%.  Invariants on
-    everything; a 65536-token prefix (closed under both rounds: 16 round-1 chunks) is checked round
-    by round against the oracle and must equal the big call's prefix bit for bit; then one decode
-    step over the 262144 centroids."""
-    _say("extreme context: 1M tokens, chunk 2048")
-    H, S, C = 2, 1048576, 2048
+# ---- extreme context: 1M tokens x 32 layers, chunk 2048, layer-streamed ---------------------------
+def test_extreme_context_chunk2048_streamed_over_32_layers():
+    """The 1 048 576-token workload as bench.py runs it: 32 layers generated and compressed one after
+    the other (one ckv_compress call per layer: 8 KV heads, alpha 0.95, chunk 2048, retain 25%), the
+    compressed layers kept (32 GiB), then one decode step over all of them.  Invariants on every
+    (layer, head); on sampled (layer, head) pairs spread over the run a 65536-token prefix (closed
+    under both rounds: 16 round-1 chunks) is checked round by round against the oracle and must equal
+    the big call's prefix bit for bit; the decode output of sampled layers is checked against the
+    oracle over all 262144 centroids."""
+    _say("extreme context: 1M tokens x 32 layers, chunk 2048, layer-streamed")
+    Ly, H, S, C = 32, HEADS, 1048576, 2048
+    L2, P = S // 4, 65536
+    samples = {0: [1], 9: [6], 20: [3], 31: [0, 7]}
     K = torch.empty((1, H, S, DIM), dtype=torch.bfloat16, device=DEV)
     V = torch.empty_like(K)
-    kv_device(555, H, S, DIM, "bf16", 0.95, 4, layer=0, device=DEV, out_k=K[0], out_v=V[0])
-    cK, cV, cdeg, assign = ckv.compress(K, V, C, retain_ratio=RHO)
-    torch.cuda.synchronize()
-    L2 = S // 4
-    assert cK.shape == (1, H, L2, DIM)
-    assert torch.equal(cdeg.sum(dim=-1), torch.full((1, H), S, dtype=torch.int64, device=DEV))
-    counts = torch.zeros((H, L2), dtype=torch.int32, device=DEV)
-    counts.scatter_add_(1, assign[0].to(torch.int64), torch.ones((H, S), dtype=torch.int32, device=DEV))
-    assert torch.equal(counts, cdeg[0])
-    P = 65536
-    h = 1
-    curK, curV, curdeg = K[:, h:h + 1, :P].contiguous(), V[:, h:h + 1, :P].contiguous(), None
-    for j, r in enumerate([1.0, 1.0]):
-        gK, gV, gdeg, gas = ckv.compress(curK, curV, C, rounds=[r], deg=curdeg)
+    cK = torch.empty((Ly, H, L2, DIM), dtype=torch.bfloat16, device=DEV)
+    cV = torch.empty_like(cK)
+    cdeg = torch.empty((Ly, H, L2), dtype=torch.int32, device=DEV)
+    assign = torch.empty((1, H, S), dtype=torch.int32, device=DEV)
+    plan = ckv.plan(ckv.layout_of(K), ckv.make_params(C, RHO))
+    assert plan.out_seq == L2
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=DEV)
+    ones = torch.ones((H, S), dtype=torch.int32, device=DEV)
+    for l in range(Ly):
+        kv_device(555, H, S, DIM, "bf16", 0.95, 4, layer=l, device=DEV, out_k=K[0], out_v=V[0])
+        ckv.compress(K, V, C, retain_ratio=RHO, out=(cK[l:l + 1], cV[l:l + 1], cdeg[l:l + 1], assign), workspace=ws)
         torch.cuda.synchronize()
-        d_in = np.ones(curK.shape[2], dtype=np.int64) if curdeg is None else i64(curdeg[0, 0])
-        check_round(f64(curK[0, 0]), f64(curV[0, 0]), d_in, C, r, "bf16", f64(gK[0, 0]), f64(gV[0, 0]),
-                    i64(gdeg[0, 0]), i64(gas[0, 0]), what=f"1M prefix round {j}")
-        curK, curV, curdeg = gK, gV, gdeg
-    assert torch.equal(cK[0, h, :P // 4], curK[0, 0]) and torch.equal(cV[0, h, :P // 4], curV[0, 0])
-    assert torch.equal(cdeg[0, h, :P // 4], curdeg[0, 0])
+        assert torch.equal(cdeg[l].sum(dim=-1), torch.full((H,), S, dtype=torch.int64, device=DEV)), f"layer {l}"
+        counts = torch.zeros((H, L2), dtype=torch.int32, device=DEV)
+        counts.scatter_add_(1, assign[0].to(torch.int64), ones)
+        assert torch.equal(counts, cdeg[l]), f"layer {l}: degrees do not count the assigned tokens"
+        for h in samples.get(l, []):
+            _say(f"  oracle check of layer {l} head {h} (prefix of {P} tokens)")
+            curK, curV, curdeg = K[:, h:h + 1, :P].contiguous(), V[:, h:h + 1, :P].contiguous(), None
+            for j, r in enumerate([1.0, 1.0]):
+                gK, gV, gdeg, gas = ckv.compress(curK, curV, C, rounds=[r], deg=curdeg)
+                torch.cuda.synchronize()
+                d_in = np.ones(curK.shape[2], dtype=np.int64) if curdeg is None else i64(curdeg[0, 0])
+                check_round(f64(curK[0, 0]), f64(curV[0, 0]), d_in, C, r, "bf16", f64(gK[0, 0]), f64(gV[0, 0]),
+                            i64(gdeg[0, 0]), i64(gas[0, 0]), what=f"1M L{l}H{h} prefix round {j}")
+                curK, curV, curdeg = gK, gV, gdeg
+            assert torch.equal(cK[l, h, :P // 4], curK[0, 0]) and torch.equal(cV[l, h, :P // 4], curV[0, 0])
+            assert torch.equal(cdeg[l, h, :P // 4], curdeg[0, 0])
+    del K, V, assign, ws, ones
+    assert bool(torch.isfinite(cK.float().sum())) and bool(torch.isfinite(cV.float().sum()))
+    # one decode step over the 32 compressed layers, as the benchmark issues it
     gen = torch.Generator(device=DEV).manual_seed(11)
-    q = torch.randn((1, H * 4, DIM), generator=gen, device=DEV).to(torch.bfloat16)
-    o = ckv.decode_attn(q, cK, cV, deg=cdeg, out_dtype=torch.float32)
+    q = torch.randn((Ly, 1, QHEADS, DIM), generator=gen, device=DEV).to(torch.bfloat16)
+    o = torch.empty((Ly, 1, QHEADS, DIM), dtype=torch.float32, device=DEV)
+    attn_ws = torch.zeros(ckv.decode_attn_workspace(ckv.layout_of(cK[0:1]), QHEADS), dtype=torch.uint8, device=DEV)
+    for l in range(Ly):
+        ckv.decode_attn(q[l], cK[l:l + 1], cV[l:l + 1], deg=cdeg[l:l + 1], out=o[l], workspace=attn_ws)
     torch.cuda.synchronize()
-    ref = oracle.app_attn(f64(q[0]), f64(cK[0]), f64(cV[0]), i64(cdeg[0]))
-    assert_rows_close(f64(o[0]), ref, ATTN_TOL, "1M decode")
+    for l in (3, 31):
+        _say(f"  oracle attention over compressed layer {l}")
+        ref = oracle.app_attn(f64(q[l, 0]), f64(cK[l]), f64(cV[l]), i64(cdeg[l]))
+        assert_rows_close(f64(o[l, 0]), ref, ATTN_TOL, f"1M decode layer {l}")
