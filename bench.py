@@ -44,9 +44,10 @@ METRIC = "KV tokens compressed/sec + decode-attn HBM GB/s (fraction of MI355X pe
 # in profiles/bench_config3_hbm_traffic.txt.  {(workload, kernel): bytes per launch averaged over the
 # launches of one step}.  A kernel without an entry reports null.
 RECORDED_TRAFFIC = {
-    ("config3", "merge_keys_bf16"): int((4227434.2 * 2.0 + 4489327.4) * 1024),
-    ("config3", "merge_origin_bf16"): int((6423693.0 * 2.0 + 4292654.6) * 1024),
-    ("config3", "match_bf16"): int((3172452.1 * 2.0 + 98304.0) * 1024),
+    ("config3", "merge_keys_bf16"): int((4227475.6 * 2.0 + 4489354.7) * 1024),
+    ("config3", "merge_origin_bf16"): int((6426238.5 * 2.0 + 4292656.4) * 1024),
+    ("config3", "match_bf16"): int((3172450.7 * 2.0 + 98304.0) * 1024),
+    ("config3", "attn_bf16"): int((66704.0 * 2.0 + 1080.3) * 1024),
 }
 TRAFFIC_SOURCE = "profiles/bench_config3_hbm_traffic.txt"
 
@@ -181,6 +182,20 @@ def roofline_of(ckv, workload, run_steps, n_steps, work, n_profile=2):
     return secs, roofline, kernels
 
 
+def mfma_ceiling(ckv):
+    """The bf16 MFMA rate this chip sustains when nothing but MFMA instructions run (the library's
+    measurement kernel: pseudo-random operands, one workgroup per CU), in TFLOP/s.  Context for the
+    similarity kernel's fraction of the nominal peak; not part of any step."""
+    out = {}
+    for name, mode, waves in (("registers_8_waves", 0, 8), ("registers_4_waves", 0, 4), ("lds_operand_per_2_mfma_8_waves", 1, 8),
+                              ("lds_operand_per_4_mfma_4_waves", 2, 4)):
+        tf = ckv.mfma_ceiling(mode, waves, 10000) / 1e12
+        out[name] = {"TFLOPs": round(tf, 1), "frac_of_nominal_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    out["what"] = ("bf16 MFMA 32x32x16 only, every CU busy, operands in registers or one fragment read from LDS per 2 / 4 "
+                   "MFMAs; the chip lowers its clock under this load, so the nominal 2500 TFLOP/s is not reached by any kernel")
+    return out
+
+
 def blas_threads():
     try:
         from threadpoolctl import threadpool_info
@@ -308,6 +323,11 @@ def run_prefill(args, cfg):
     context = None
     if args.stage == "all" and not args.no_context:
         context = context_figures(ckv, cfg, sets, assign, ws, gen, dev)
+    if args.stage in ("all", "match") and not args.no_context:
+        context = dict(context or {}, mfma_ceiling_measured=mfma_ceiling(ckv))
+        best = max(v["TFLOPs"] for v in context["mfma_ceiling_measured"].values() if isinstance(v, dict))
+        if "match_bf16" in kernels and "achieved" in kernels["match_bf16"]:
+            kernels["match_bf16"]["frac_of_measured_mfma_ceiling"] = round(kernels["match_bf16"]["achieved"] / best, 4)
 
     out = base_line(args, cfg, S / (ms_per_step * 1e-3), ms_per_step,
                     {"rounds": plan.round_r, "compressed_len": L2})

@@ -310,6 +310,18 @@ int ckv_timing_select(const char* prefix);
 int ckv_timing_reset(void);
 int ckv_timing_read(ckv_kernel_time* out, int max);
 
+/* Measurement aid for benchmarks (not part of the method): launches, once, a kernel that does
+ * nothing but bf16 MFMA 32x32x16 instructions on every CU - `waves_per_cu` (4 or 8) waves, each with
+ * independent accumulator chains, `iters` rounds of 8 k-steps, operands holding pseudo-random finite
+ * values - and stores in *flops the floating-point operations it performs; timed through the timing
+ * hooks below (kernel name "mfma_ceiling") it gives the MFMA rate this chip sustains under its own
+ * power management, the practical ceiling the similarity stage is to be read against beside the
+ * nominal 2.5 PFLOP/s.  mode 0: operands in registers; 1: one operand fragment read from LDS per
+ * 2 MFMAs (the similarity kernel's ratio); 2: per 4 MFMAs (waves_per_cu 4 only).
+ * scratch: device, 256-byte aligned, >= 65536 + CUs * 2048 bytes (1 MiB is enough). */
+int ckv_bench_mfma_ceiling(int32_t mode, int32_t waves_per_cu, int32_t iters, void* scratch, size_t scratch_bytes,
+                           double* flops, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -95,6 +95,7 @@ def lib() -> C.CDLL:
                                               C.POINTER(i32), C.POINTER(C.c_size_t)]
         L.ckv_paged_compress.argtypes = [vp, vp, vp, vp, vp, PL, i32, C.POINTER(i32), C.POINTER(Params), vp, i32, vp,
                                          C.c_size_t, vp]
+        L.ckv_bench_mfma_ceiling.argtypes = [i32, i32, i32, vp, C.c_size_t, C.POINTER(C.c_double), vp]
         L.ckv_timing_enable.argtypes = [C.c_int]
         L.ckv_timing_select.argtypes = [C.c_char_p]
         L.ckv_timing_read.argtypes = [C.POINTER(KernelTime), C.c_int]
@@ -416,6 +417,27 @@ def paged_compress(K_pool, V_pool, deg_pool, block_table, seq: int, chunk: int, 
     if st != 0:
         raise CkvError(st, "ckv_paged_compress")
     return out_seq, freed
+
+
+def mfma_ceiling(mode: int, waves_per_cu: int, iters: int = 20000) -> float:
+    """ckv_bench_mfma_ceiling timed through the library's hooks: sustained bf16 MFMA rate in FLOP/s."""
+    scratch = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    flops = C.c_double(0.0)
+    for it, n in enumerate((max(iters // 10, 1), iters)):      # a short warm-up launch, then the timed one
+        if it == 1:
+            timing_select("mfma_ceiling")
+            timing_reset()
+            timing_enable(True)
+        st = lib().ckv_bench_mfma_ceiling(mode, waves_per_cu, n, _ptr(scratch), scratch.numel(), C.byref(flops), _stream())
+        if st != 0:
+            timing_enable(False)
+            timing_select(None)
+            raise CkvError(st, "ckv_bench_mfma_ceiling")
+        torch.cuda.synchronize()
+    timing_enable(False)
+    t = timing_read()
+    timing_select(None)
+    return flops.value / (t["mfma_ceiling"][0] * 1e-3)
 
 
 def timing_enable(on: bool) -> None:

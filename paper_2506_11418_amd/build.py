@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libckv.so")
-SOURCES = ["ckv_host.hip", "k1_match.hip", "k2_select.hip", "k3_merge.hip", "k4_attn.hip", "k6_paged.hip", "ckv_noalloc.hip"]
+SOURCES = ["ckv_host.hip", "k1_match.hip", "k2_select.hip", "k3_merge.hip", "k4_attn.hip", "k6_paged.hip", "k7_mfma_ceiling.hip", "ckv_noalloc.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
