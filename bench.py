@@ -239,7 +239,7 @@ def run_prefill(args, cfg):
     q = torch.randn((Ly, 1, Hq, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
 
     lay = ckv.layout_of(sets[0][0])
-    params = ckv.make_params(cfg["chunk"], cfg["retain"])
+    params = ckv.make_params(cfg["chunk"], cfg["retain"], route=args.route)
     plan = ckv.plan(lay, params)
     L2 = plan.out_seq
     K_out = torch.empty((Ly, H, L2, D), dtype=torch.bfloat16, device=dev)
@@ -267,7 +267,7 @@ def run_prefill(args, cfg):
             ckv.compress(K, V, cfg["chunk"], retain_ratio=1.0, out=(K_copy, V_copy, deg_copy, assign), workspace=ws)
         elif args.stage != "decode" or i == 0:
             ckv.compress(K, V, cfg["chunk"], retain_ratio=cfg["retain"], out=(K_out, V_out, deg_out, assign),
-                         workspace=ws)
+                         workspace=ws, route=args.route)
         if timed:
             ev[3 * i + 1].record()
         if args.stage in ("all", "decode"):
@@ -661,6 +661,8 @@ def main():
     ap.add_argument("--no-context", action="store_true",
                     help="skip the context figures (profiling runs: only the step's own launches)")
     ap.add_argument("--seed", type=int, default=2024)
+    ap.add_argument("--route", default=None, choices=["full_rounds", "defer_always"],
+                    help="config3 only: force one of the library's bit-identical kernel routes (default: the library chooses)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists).",
