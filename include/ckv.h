@@ -207,9 +207,12 @@ int ckv_decode_attn(const void* q, int32_t q_heads, const void* K, const void* V
  * arguments, same kernels and same result bits as ckv_decode_attn; the split partials and arrival
  * counters live in a device array of CKV_NOALLOC_SCRATCH_BYTES that is part of the library (each
  * GPU the library runs on holds its own copy until the process ends; the first call on a device
- * looks its address up).  The call allocates and frees nothing and records no memset.
- * CKV_EWORKSPACE when ckv_decode_attn_workspace() for the shape exceeds CKV_NOALLOC_SCRATCH_BYTES
- * (the Llama-3-8B decode shapes, batch 1 to 16 at 32 query heads, need about 1.1 MB).  All calls on
+ * looks its address up).  The call allocates and frees nothing and launches nothing but the
+ * attention kernel: the arrival counters keep the array's first 64 KiB to themselves (zero when the
+ * library is loaded, left at zero by every call), the partials use the rest.
+ * CKV_EWORKSPACE when batch * kv->heads exceeds 16384 or the partials (ckv_decode_attn_workspace()
+ * minus its counters) exceed CKV_NOALLOC_SCRATCH_BYTES - 64 KiB (the Llama-3-8B decode shapes,
+ * batch 1 to 16 at 32 query heads, need about 1.1 MB).  All calls on
  * one GPU share that one array: calls that overlap in time on the same GPU (different streams or
  * threads) race; issue them on one stream, or otherwise order them. */
 #define CKV_NOALLOC_SCRATCH_BYTES (4u << 20)

@@ -122,7 +122,9 @@ hipError_t launch_fill_deg(const int32_t* deg_in, int64_t in_stride, int32_t* de
                            int n_bh, int seq, hipStream_t st);
 
 // Decode attention: split along the sequence; the slice that finishes last merges the partials.
-// The workspace starts with attn_counter_bytes() of int32 arrival counters that are zero between calls.
+// The workspace starts with attn_counter_bytes() of int32 arrival counters that are zero between calls
+// (launch_decode_attn with counters != NULL keeps them there instead and uses the whole workspace for
+// the partial results).
 size_t attn_counter_bytes(int n_b, int kv_heads);
 // span_limit > 0 (paged caches): no slice may cover more tokens than that
 int attn_splits(int n_b, int kv_heads, int seq, int span_limit);
@@ -131,7 +133,8 @@ size_t attn_workspace_bytes(int n_b, int kv_heads, int q_heads, int dim, int seq
 hipError_t launch_decode_attn(const void* q, int q_heads, const void* K, const void* V, int dtype,
                               int dim, TensorView kv, int n_b, int kv_heads, int seq,
                               const int32_t* lens, const int32_t* deg, float scale, void* o,
-                              int o_dtype, void* workspace, PagedView paged, hipStream_t st);
+                              int o_dtype, void* workspace, PagedView paged, hipStream_t st,
+                              int32_t* counters = nullptr);
 
 // Block pool <-> strided tensors.  pool: [n_blocks, heads, block_size, dim] (deg pool
 // [n_blocks, heads, block_size]); the first `seq` tokens of every sequence are moved.  Gather writes

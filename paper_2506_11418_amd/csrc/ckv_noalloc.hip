@@ -12,20 +12,18 @@ namespace ckv {
 namespace {
 
 // In host code this name is only a handle for hipGetSymbolAddress: the array's device address is
-// looked up once per device and kept in g_scratch[].
+// looked up once per device and kept in g_scratch[].  Layout: kCounterBytes of arrival counters (one
+// int32 per (batch, KV head)), then the split partials.  The counters have a place of their own,
+// whatever the shape of a call: they are zero when the code object is loaded, every call leaves the
+// ones it used at zero again (the merging workgroup resets them), and no call's partials ever reach
+// them, so nothing has to be cleared between calls of different shapes, nor by a recorded graph
+// that is replayed after calls of other shapes.
+constexpr size_t kCounterBytes = 64 * 1024;
+static_assert(kCounterBytes % 256 == 0 && kCounterBytes < CKV_NOALLOC_SCRATCH_BYTES, "scratch layout");
 static __device__ __align__(256) unsigned char scratch[CKV_NOALLOC_SCRATCH_BYTES];
 
-struct DeviceScratch {
-  void* ptr = nullptr;          // device address of `scratch` on this device
-  size_t counters_zero = 0;     // leading bytes known to hold zeroed arrival counters
-};
 std::mutex g_lock;
-DeviceScratch g_scratch[kMaxDevices];
-
-__global__ void zero_words_kernel(int32_t* p, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0;
-}
+void* g_scratch[kMaxDevices];   // device address of `scratch` per device, NULL until its first call
 
 }  // namespace
 }  // namespace ckv
@@ -38,7 +36,8 @@ extern "C" int ckv_decode_attn_noalloc(const void* q, int32_t q_heads, const voi
   size_t need = 0;
   int st = ckv_decode_attn_workspace(kv, q_heads, &need);   // validates the layout and q_heads
   if (st != CKV_OK) return st;
-  if (need > CKV_NOALLOC_SCRATCH_BYTES) return CKV_EWORKSPACE;
+  const size_t counters = attn_counter_bytes(kv->batch, kv->heads);
+  if (counters > kCounterBytes || need - counters > CKV_NOALLOC_SCRATCH_BYTES - kCounterBytes) return CKV_EWORKSPACE;
   if (!q || !K || !V || !o) return CKV_EINVAL;
   if (o_dtype != CKV_F32 && o_dtype != CKV_BF16) return CKV_EINVAL;
   if (((uintptr_t)q) % 16 || ((uintptr_t)K) % 16 || ((uintptr_t)V) % 16 || ((uintptr_t)o) % 4 ||
@@ -54,34 +53,21 @@ extern "C" int ckv_decode_attn_noalloc(const void* q, int32_t q_heads, const voi
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return CKV_EHIP; }
   if (dev < 0 || dev >= kMaxDevices) return CKV_EUNSUPPORTED;
-  void* ws = nullptr;
+  unsigned char* base = nullptr;
   {
     std::lock_guard<std::mutex> g(g_lock);
-    DeviceScratch& d = g_scratch[dev];
-    if (!d.ptr) {   // first call on this device: its own copy of the array, at its own address
+    if (!g_scratch[dev]) {   // first call on this device: its own copy of the array, at its own address
       void* p = nullptr;
       if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return CKV_EHIP; }
-      d.ptr = p;
-      d.counters_zero = 0;
+      g_scratch[dev] = p;
     }
-    ws = d.ptr;
-    // The arrival counters sit at the start of the scratch and are zero again after every call; a
-    // call with more (batch, KV head) pairs than the one before reaches into what that one used
-    // for partial results, so its counters are cleared first (a fill kernel on the caller's stream,
-    // not a memset: the call may be under graph capture).
-    const size_t cb = attn_counter_bytes(kv->batch, kv->heads);
-    if (cb > d.counters_zero) {
-      const int n = (int)(cb / sizeof(int32_t));
-      hipLaunchKernelGGL(zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, s, static_cast<int32_t*>(ws), n);
-      if (hipGetLastError() != hipSuccess) return CKV_EHIP;
-    }
-    d.counters_zero = cb;
+    base = static_cast<unsigned char*>(g_scratch[dev]);
   }
   hipError_t e = launch_decode_attn(q, q_heads, K, V, kv->dtype, kv->dim,
                                     TensorView{kv->stride_b, kv->stride_h, kv->stride_s, kv->heads,
                                                kv->deg_stride ? kv->deg_stride : (int64_t)kv->seq},
-                                    kv->batch, kv->heads, kv->seq, lens, deg, scale, o, o_dtype, ws,
-                                    PagedView{nullptr, 0, 0, 0}, s);
+                                    kv->batch, kv->heads, kv->seq, lens, deg, scale, o, o_dtype, base + kCounterBytes,
+                                    PagedView{nullptr, 0, 0, 0}, s, reinterpret_cast<int32_t*>(base));
   if (e == hipSuccess) return CKV_OK;
   (void)hipGetLastError();
   return (e == hipErrorInvalidValue) ? CKV_EUNSUPPORTED : CKV_EHIP;

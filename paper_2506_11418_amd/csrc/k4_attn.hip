@@ -386,13 +386,15 @@ __global__ __launch_bounds__(kThreads, G <= 4 ? 3 : 2) void attn_partial_kernel(
 template <typename T, int D, int G>
 hipError_t launch_attn_t(const void* q, const void* K, const void* V, TensorView kv, int n_b, int kv_heads,
                          int seq, const int32_t* lens, const int32_t* deg, float scale, void* o, int o_dtype,
-                         void* workspace, PagedView paged, hipStream_t st) {
+                         void* workspace, int32_t* counters, PagedView paged, hipStream_t st) {
   const int n_splits = attn_splits(n_b, kv_heads, seq, paged.table ? (kMaxTableLds << paged.shift) : 0);
   const int span = div_up(seq, n_splits);
   if (paged.table && span > (kMaxTableLds << paged.shift)) return hipErrorInvalidValue;
-  // workspace: arrival counters (one per (batch, KV head), zero between calls) | partial outputs | (max, sum) pairs
-  int32_t* arrived = static_cast<int32_t*>(workspace);
-  float* o_part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + attn_counter_bytes(n_b, kv_heads));
+  // workspace: arrival counters (one per (batch, KV head), zero between calls) | partial outputs | (max, sum) pairs;
+  // with counters kept elsewhere the partial outputs start the workspace
+  int32_t* arrived = counters ? counters : static_cast<int32_t*>(workspace);
+  float* o_part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) +
+                                           (counters ? 0 : attn_counter_bytes(n_b, kv_heads)));
   float* ml_part = o_part + (size_t)n_b * kv_heads * n_splits * G * D;
   ScopedTimer t(paged.table ? (sizeof(T) == 2 ? "attn_paged_bf16" : "attn_paged_f32")
                             : (sizeof(T) == 2 ? "attn_bf16" : "attn_f32"), st);
@@ -412,12 +414,12 @@ hipError_t launch_attn_t(const void* q, const void* K, const void* V, TensorView
 template <typename T, int D>
 hipError_t launch_attn_g(int G, const void* q, const void* K, const void* V, TensorView kv, int n_b,
                          int kv_heads, int seq, const int32_t* lens, const int32_t* deg, float scale, void* o,
-                         int o_dtype, void* workspace, PagedView paged, hipStream_t st) {
+                         int o_dtype, void* workspace, int32_t* counters, PagedView paged, hipStream_t st) {
   switch (G) {
-    case 1: return launch_attn_t<T, D, 1>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st);
-    case 2: return launch_attn_t<T, D, 2>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st);
-    case 4: return launch_attn_t<T, D, 4>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st);
-    case 8: return launch_attn_t<T, D, 8>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st);
+    case 1: return launch_attn_t<T, D, 1>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, counters, paged, st);
+    case 2: return launch_attn_t<T, D, 2>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, counters, paged, st);
+    case 4: return launch_attn_t<T, D, 4>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, counters, paged, st);
+    case 8: return launch_attn_t<T, D, 8>(q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, counters, paged, st);
   }
   return hipErrorInvalidValue;
 }
@@ -452,10 +454,10 @@ size_t attn_workspace_bytes(int n_b, int kv_heads, int q_heads, int dim, int seq
 hipError_t launch_decode_attn(const void* q, int q_heads, const void* K, const void* V, int dtype, int dim,
                               TensorView kv, int n_b, int kv_heads, int seq, const int32_t* lens,
                               const int32_t* deg, float scale, void* o, int o_dtype, void* workspace,
-                              PagedView paged, hipStream_t st) {
+                              PagedView paged, hipStream_t st, int32_t* counters) {
   const int G = q_heads / kv_heads;
 #define CKV_ATTN(T, DD) \
-  return launch_attn_g<T, DD>(G, q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, paged, st)
+  return launch_attn_g<T, DD>(G, q, K, V, kv, n_b, kv_heads, seq, lens, deg, scale, o, o_dtype, workspace, counters, paged, st)
   if (dtype == CKV_BF16) {
     if (dim == 128) CKV_ATTN(__bf16, 128);
     if (dim == 64) CKV_ATTN(__bf16, 64);

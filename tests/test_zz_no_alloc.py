@@ -1,7 +1,7 @@
 """GPU check of ckv_decode_attn_noalloc (the entry point for callers that cannot allocate): through
 the C ABI, against ckv_decode_attn on the same inputs, on calls in a row that share the library's
 scratch array - the second with a smaller input, the third with more (batch, head) pairs than any
-before (its arrival counters reach into what the earlier calls used for partial results)."""
+before - and on a recorded call replayed after calls of other shapes."""
 import ctypes as C
 
 import numpy as np
@@ -51,6 +51,35 @@ def test_noalloc_entry_point_matches_the_workspace_entry_point():
     assert torch.equal(again, outs[1])
 
 
+def test_noalloc_call_recorded_in_a_graph_replays_after_calls_of_other_shapes():
+    """The entry point launches one kernel and keeps no host state that depends on the calls made
+    so far, so a call recorded into a HIP graph gives the eager bits on every replay, whatever
+    shapes ran on the shared scratch in between."""
+    print("no-alloc attention: recorded call replayed between eager calls of other shapes", flush=True)
+    q, K, V, deg, lens = _case(11, 2, 8, 4, 3000, 128)
+    others = [_case(12, 6, 8, 4, 900, 128), _case(13, 1, 2, 4, 5000, 128)]
+    ref = ckv.decode_attn(q, K, V, lens=lens, deg=deg, out_dtype=torch.float32)
+    o = torch.zeros_like(ref)
+    ckv.decode_attn_noalloc(q, K, V, o, lens=lens, deg=deg)            # first use outside the capture (address lookup)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            ckv.decode_attn_noalloc(q, K, V, o, lens=lens, deg=deg)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        oq, oK, oV, odeg, olens = others[rep % 2]
+        oo = torch.empty(oq.shape, dtype=torch.float32, device=DEV)
+        ckv.decode_attn_noalloc(oq, oK, oV, oo, lens=olens, deg=odeg)   # eager, another shape, same scratch
+        torch.cuda.synchronize()
+        assert torch.equal(oo, ckv.decode_attn(oq, oK, oV, lens=olens, deg=odeg, out_dtype=torch.float32))
+        o.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, ref), f"replay {rep}"
+
+
 def test_noalloc_entry_point_rejects_what_its_scratch_cannot_hold():
     L = ckv.lib()
     a = C.c_void_p(4096)
@@ -59,6 +88,10 @@ def test_noalloc_entry_point_rejects_what_its_scratch_cannot_hold():
     assert L.ckv_decode_attn_workspace(C.byref(big), 64, C.byref(need)) == 0
     assert need.value > (4 << 20)               # 256 sequences x 64 query heads: more than the array holds
     assert L.ckv_decode_attn_noalloc(a, 64, a, a, C.byref(big), None, None, 0.0, a, 0, None) == -4
+    many = ckv.Layout(2500, 8, 64, 32, 8 * 64 * 32, 64 * 32, 32, ckv.F32, 0)
+    assert L.ckv_decode_attn_workspace(C.byref(many), 8, C.byref(need)) == 0
+    assert need.value < (4 << 20) - (64 << 10)  # the partials would fit, the 20000 arrival counters do not
+    assert L.ckv_decode_attn_noalloc(a, 8, a, a, C.byref(many), None, None, 0.0, a, 0, None) == -4
     ok = ckv.Layout(1, 8, 8192, 128, 8 * 8192 * 128, 8192 * 128, 128, ckv.BF16, 0)
     assert L.ckv_decode_attn_noalloc(None, 32, a, a, C.byref(ok), None, None, 0.0, a, 0, None) == -1
     assert L.ckv_decode_attn_noalloc(a, 32, C.c_void_p(4100), a, C.byref(ok), None, None, 0.0, a, 0, None) == -3
