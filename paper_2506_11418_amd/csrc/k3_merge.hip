@@ -781,26 +781,27 @@ __global__ void edges_kernel(const unsigned char* __restrict__ K, const unsigned
 
 // Cache update of a decode step (Algorithm 1, decoding part): the new token of every (batch, head)
 // goes to row lens[b] (or `pos`) with degree 1.  A sequence already at capacity is left alone.
+// One workgroup per sequence: all of its threads read lens[b], meet, write the rows of all heads, and
+// one of them then advances lens[b] - no other workgroup reads or writes that entry, so the update
+// needs no launch of its own.
 __global__ void append_kernel(const unsigned char* __restrict__ k_new, const unsigned char* __restrict__ v_new,
                               unsigned char* __restrict__ K, unsigned char* __restrict__ V,
                               int32_t* __restrict__ deg, TensorView cache, int capacity,
-                              const int32_t* __restrict__ lens, int pos, int pieces_per_row, int elem_bytes,
-                              int total) {
-  const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= total) return;
-  const int piece = e % pieces_per_row, bh = e / pieces_per_row;
-  const int t = lens ? lens[bh / cache.heads] : pos;
-  if (t < 0 || t >= capacity) return;
-  const int64_t so = ((int64_t)bh * pieces_per_row + piece) * 16;
-  const int64_t dof = (cache.seq_base(bh) + (int64_t)t * cache.stride_s) * elem_bytes + piece * 16;
-  *reinterpret_cast<uint4*>(K + dof) = *reinterpret_cast<const uint4*>(k_new + so);
-  *reinterpret_cast<uint4*>(V + dof) = *reinterpret_cast<const uint4*>(v_new + so);
-  if (piece == 0 && deg) deg[(int64_t)bh * cache.deg_stride + t] = 1;
-}
-
-__global__ void bump_lens_kernel(int32_t* __restrict__ lens, int batch, int capacity) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < batch && lens[b] >= 0 && lens[b] < capacity) lens[b] += 1;
+                              int32_t* __restrict__ lens, int pos, int pieces_per_row, int elem_bytes) {
+  const int b = blockIdx.x;
+  const int t = lens ? lens[b] : pos;
+  __syncthreads();
+  if (t < 0 || t >= capacity) return;      // the same for every thread of the workgroup
+  const int per_seq = cache.heads * pieces_per_row;
+  for (int e = threadIdx.x; e < per_seq; e += blockDim.x) {
+    const int piece = e % pieces_per_row, bh = b * cache.heads + e / pieces_per_row;
+    const int64_t so = ((int64_t)bh * pieces_per_row + piece) * 16;
+    const int64_t dof = (cache.seq_base(bh) + (int64_t)t * cache.stride_s) * elem_bytes + piece * 16;
+    *reinterpret_cast<uint4*>(K + dof) = *reinterpret_cast<const uint4*>(k_new + so);
+    *reinterpret_cast<uint4*>(V + dof) = *reinterpret_cast<const uint4*>(v_new + so);
+    if (piece == 0 && deg) deg[(int64_t)bh * cache.deg_stride + t] = 1;
+  }
+  if (lens && threadIdx.x == 0) lens[b] = t + 1;
 }
 
 __global__ void fill_deg_kernel(const int32_t* __restrict__ deg_in, int64_t in_stride, int32_t* __restrict__ deg_out,
@@ -934,18 +935,11 @@ hipError_t launch_append(const void* k_new, const void* v_new, void* K, void* V,
                          int batch, int capacity, int32_t* lens, int pos, int row_bytes, int elem_bytes,
                          hipStream_t st) {
   const int ppr = row_bytes / 16;
-  const int total = batch * cache.heads * ppr;
-  {
-    ScopedTimer t("append", st);
-    hipLaunchKernelGGL(append_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const unsigned char*>(k_new), static_cast<const unsigned char*>(v_new),
-                       static_cast<unsigned char*>(K), static_cast<unsigned char*>(V), deg, cache, capacity, lens,
-                       pos, ppr, elem_bytes, total);
-    hipError_t err = hipGetLastError();
-    if (err != hipSuccess || !lens) return err;
-  }
-  ScopedTimer t("append_bump_lens", st);
-  hipLaunchKernelGGL(bump_lens_kernel, dim3((unsigned)((batch + 255) / 256)), dim3(256), 0, st, lens, batch, capacity);
+  ScopedTimer t("append", st);
+  hipLaunchKernelGGL(append_kernel, dim3((unsigned)batch), dim3(256), 0, st,
+                     static_cast<const unsigned char*>(k_new), static_cast<const unsigned char*>(v_new),
+                     static_cast<unsigned char*>(K), static_cast<unsigned char*>(V), deg, cache, capacity, lens,
+                     pos, ppr, elem_bytes);
   return hipGetLastError();
 }
 

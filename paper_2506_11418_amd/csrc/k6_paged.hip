@@ -46,35 +46,30 @@ __global__ void paged_move_kernel(unsigned char* __restrict__ K_pool, unsigned c
 }
 
 // Decode-step cache update on pages: the new token of sequence b goes to position lens[b] of every
-// head (degree 1).  A sequence whose next position has no valid block is left alone (ok[b] = 0).
+// head (degree 1).  A sequence whose next position has no valid block is left alone.  One workgroup
+// per sequence, which also advances lens[b] once all of its threads have read it.
 __global__ void paged_append_kernel(const unsigned char* __restrict__ k_new, const unsigned char* __restrict__ v_new,
                                     unsigned char* __restrict__ K_pool, unsigned char* __restrict__ V_pool,
                                     int32_t* __restrict__ deg_pool, const int32_t* __restrict__ table, int max_blocks,
-                                    int shift, int n_blocks, int heads, const int32_t* __restrict__ lens,
-                                    int pieces_per_row, int total) {
-  const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= total) return;
-  const int piece = e % pieces_per_row, bh = e / pieces_per_row;
-  const int b = bh / heads, h = bh % heads;
+                                    int shift, int n_blocks, int heads, int32_t* __restrict__ lens,
+                                    int pieces_per_row) {
+  const int b = blockIdx.x;
   const int t = lens[b];
-  if (t < 0 || (t >> shift) >= max_blocks) return;
+  __syncthreads();
+  if (t < 0 || (t >> shift) >= max_blocks) return;       // the same for every thread of the workgroup
   const int blk = table[(int64_t)b * max_blocks + (t >> shift)];
   if ((unsigned)blk >= (unsigned)n_blocks) return;
-  const int64_t row = (((int64_t)blk * heads + h) << shift) + (t & ((1 << shift) - 1));
-  const int64_t so = ((int64_t)bh * pieces_per_row + piece) * 16;
-  const int64_t poff = (row * pieces_per_row + piece) * 16;
-  *reinterpret_cast<uint4*>(K_pool + poff) = *reinterpret_cast<const uint4*>(k_new + so);
-  *reinterpret_cast<uint4*>(V_pool + poff) = *reinterpret_cast<const uint4*>(v_new + so);
-  if (piece == 0 && deg_pool) deg_pool[row] = 1;
-}
-
-__global__ void paged_bump_lens_kernel(int32_t* __restrict__ lens, const int32_t* __restrict__ table, int max_blocks,
-                                       int shift, int n_blocks, int batch) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= batch) return;
-  const int t = lens[b];
-  if (t < 0 || (t >> shift) >= max_blocks) return;
-  if ((unsigned)table[(int64_t)b * max_blocks + (t >> shift)] < (unsigned)n_blocks) lens[b] = t + 1;
+  const int per_seq = heads * pieces_per_row;
+  for (int e = threadIdx.x; e < per_seq; e += blockDim.x) {
+    const int piece = e % pieces_per_row, h = e / pieces_per_row;
+    const int64_t row = (((int64_t)blk * heads + h) << shift) + (t & ((1 << shift) - 1));
+    const int64_t so = (((int64_t)b * heads + h) * pieces_per_row + piece) * 16;
+    const int64_t poff = (row * pieces_per_row + piece) * 16;
+    *reinterpret_cast<uint4*>(K_pool + poff) = *reinterpret_cast<const uint4*>(k_new + so);
+    *reinterpret_cast<uint4*>(V_pool + poff) = *reinterpret_cast<const uint4*>(v_new + so);
+    if (piece == 0 && deg_pool) deg_pool[row] = 1;
+  }
+  if (threadIdx.x == 0) lens[b] = t + 1;
 }
 
 __global__ void paged_release_kernel(int32_t* __restrict__ table, int max_blocks, int n_b, int keep_blocks,
@@ -116,19 +111,11 @@ hipError_t launch_paged_gather(const void* K_pool, const void* V_pool, const int
 hipError_t launch_paged_append(const void* k_new, const void* v_new, void* K_pool, void* V_pool, int32_t* deg_pool,
                                PagedView paged, int n_b, int heads, int row_bytes, int32_t* lens, hipStream_t st) {
   const int ppr = row_bytes / 16;
-  const int total = n_b * heads * ppr;
-  {
-    ScopedTimer t("paged_append", st);
-    hipLaunchKernelGGL(paged_append_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const unsigned char*>(k_new), static_cast<const unsigned char*>(v_new),
-                       static_cast<unsigned char*>(K_pool), static_cast<unsigned char*>(V_pool), deg_pool, paged.table,
-                       paged.max_blocks, paged.shift, paged.n_blocks, heads, lens, ppr, total);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  ScopedTimer t("paged_append_bump_lens", st);
-  hipLaunchKernelGGL(paged_bump_lens_kernel, dim3((unsigned)((n_b + 255) / 256)), dim3(256), 0, st, lens, paged.table,
-                     paged.max_blocks, paged.shift, paged.n_blocks, n_b);
+  ScopedTimer t("paged_append", st);
+  hipLaunchKernelGGL(paged_append_kernel, dim3((unsigned)n_b), dim3(256), 0, st,
+                     static_cast<const unsigned char*>(k_new), static_cast<const unsigned char*>(v_new),
+                     static_cast<unsigned char*>(K_pool), static_cast<unsigned char*>(V_pool), deg_pool, paged.table,
+                     paged.max_blocks, paged.shift, paged.n_blocks, heads, lens, ppr);
   return hipGetLastError();
 }
 
