@@ -286,10 +286,11 @@ __device__ __forceinline__ void fma_bf16x8_t(float* acc, const uint4& u, int w) 
       acc[2 * i + 1] = fmaf(fw, __uint_as_float(x[i] & 0xffff0000u), acc[2 * i + 1]);
     }
   } else {
-    // The weight's bits stay out of the compiler's sight: a weight known at compile time (a literal 1)
-    // would be encoded as an inline constant, which the packed instruction does not read as (w, 0).
+    // A weight known at compile time (a literal 1) would be encoded as an inline constant, which the
+    // packed instruction does not read as (w, 0): such a weight is hidden from the compiler.  (The
+    // test is resolved after inlining; a run-time weight compiles as if it were not there.)
     uint32_t wb = __float_as_uint((float)w);
-    asm volatile("" : "+v"(wb));
+    if (__builtin_constant_p(wb)) asm volatile("" : "+v"(wb));
     const bf16x2 w_lo = __builtin_bit_cast(bf16x2, wb >> 16), w_hi = __builtin_bit_cast(bf16x2, wb & 0xffff0000u);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
