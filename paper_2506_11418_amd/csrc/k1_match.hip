@@ -4,7 +4,7 @@
 // For every A token i:  j*(i) = argmax_j  k_i.k_j / (|k_i||k_j|)  (lowest j on ties) and that
 // maximum.  The |A| x |B| similarity matrix lives only in MFMA accumulators.
 //
-// Two bf16 kernels.  Common to both: 64 A rows per wave held as MFMA operands in registers; the
+// Three bf16 kernels.  Common to all: 64 A rows per wave held as MFMA operands in registers; the
 // MFMA computes S^T (B index on the M side) so that a lane's 16 accumulators of a 32x32 tile all
 // belong to ONE A row (no cross-lane step until the very end); inverse norms come from the same
 // bytes (v_dot2 on the packed pairs): the B rows' while they are staged into LDS, the A rows'
@@ -15,6 +15,7 @@
 // panel).  Blocks made of full tiles fold tile q into the running maxima while the MFMAs of tile
 // q+1 run; ragged blocks take the maximum first and resolve the index only for tiles that raise
 // some lane's maximum.
+//   match_small_bf16_kernel (whole chunks of 64, 128 or 256 tokens): several chunks per workgroup, see below.
 //   match_stream_bf16_kernel (dim 128, whole chunks of 1024 or 2048 tokens): persistent, see below.
 #include <type_traits>
 #include <utility>
@@ -41,7 +42,7 @@ constexpr int kPanel = 128;                      // B rows per LDS panel
 // rows of the chunk's blocks are staged in LDS first.
 template <int D, int NW, bool PAGED>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
-    const __bf16* __restrict__ K, TensorView kv, int seq, int chunk, int n_chunks, int a_blocks,
+    const __bf16* __restrict__ K, TensorView kv, int seq, int chunk, int n_chunks, int g_first, int a_blocks,
     int total_work, int per_xcd, int32_t* __restrict__ dst_local, float* __restrict__ score, PagedSide paged) {
   constexpr int OCT = D / 8;                       // 16-byte pieces per key row
   constexpr int ROWB = D * 2;                      // bytes per row
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
   const int w = xcd_remap(blockIdx.x, per_xcd);
   if (w >= total_work) return;
   const int ab = w % a_blocks;
-  const int g = (w / a_blocks) % n_chunks;
+  const int g = g_first + (w / a_blocks) % n_chunks;     // the launch covers chunks g_first .. g_first + n_chunks - 1
   const int bh = w / (a_blocks * n_chunks);
   const int g0 = g * chunk;
   const int L = min(chunk, seq - g0);
@@ -314,6 +315,111 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void match_bf16_kernel(
         dst_local[out_base + a] = j;
         score[out_base + a] = b * my_inva[rt];
       }
+    }
+  }
+}
+
+// ---- whole chunks of 64, 128 or 256 tokens (the sizes of the paper's chunk ablation, Sec. 6.4) ----
+// A workgroup of match_bf16_kernel owns one chunk; at these sizes it would stage a 128-row panel
+// and keep four waves around a block of 32 to 128 rows.  Here a workgroup takes 512 consecutive
+// tokens of a sequence, that is 8, 4 or 2 whole chunks: their 256 A rows go through LDS into the
+// waves' operand registers, their 256 B rows are normed and parked in LDS in one go, and every
+// 32-row tile of A rows is multiplied with the B tiles of its own chunk only (1, 2 or 4 of them).
+// Same operand order, same norms and the same fold as match_bf16_kernel: same bits.
+constexpr int kSmallTokens = 512;
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void match_small_bf16_kernel(
+    const __bf16* __restrict__ K, TensorView kv, int seq, int chunk, int n_full, int blocks_per_seq, int total_work,
+    int per_xcd, int32_t* __restrict__ dst_local, float* __restrict__ score) {
+  constexpr int OCT = D / 8, ROWB = D * 2, KEYSHIFT = (ROWB == 256) ? 0 : 1, KSTEPS = D / 16;
+  constexpr int ROWS = kSmallTokens / 2;           // A rows = B rows of a full block
+  constexpr int ROWS_PER_PASS = kThreads / OCT, PIECES = ROWS / ROWS_PER_PASS;
+  static_assert(ROWS_PER_PASS % (OCT << KEYSHIFT) == 0, "swizzle period");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* rows_lds = smem;                                 // ROWS rows: first the A rows, then the B rows
+  float* invb = reinterpret_cast<float*>(smem + ROWS * ROWB);     // 1/|k_j| of the B rows
+
+  const int w = xcd_remap(blockIdx.x, per_xcd);
+  if (w >= total_work) return;
+  const int sb = w % blocks_per_seq, bh = w / blocks_per_seq;
+  const int t0 = sb * kSmallTokens;
+  const int nrows = min(kSmallTokens, n_full * chunk - t0) >> 1;  // whole chunks only: a multiple of chunk / 2 >= 32
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int piece = tid % OCT, r0 = tid / OCT;
+  const __bf16* Kblk = K + kv.seq_base(bh) + (int64_t)t0 * kv.stride_s + piece * 8;
+  auto swz = [](int row, int pc) -> int { return row * ROWB + (((pc ^ (row >> KEYSHIFT)) & (OCT - 1)) << 4); };
+  const int lds_piece0 = swz(r0, piece);
+
+  // all loads of the block before the first use; rows past the block's end re-read its last row and are zeroed
+  Piece xa[PIECES], xb[PIECES];
+#pragma unroll
+  for (int it = 0; it < PIECES; ++it) {
+    const int r = min(r0 + it * ROWS_PER_PASS, nrows - 1);
+    xa[it].u = *reinterpret_cast<const uint4*>(Kblk + (int64_t)(2 * r) * kv.stride_s);
+  }
+#pragma unroll
+  for (int it = 0; it < PIECES; ++it) {
+    const int r = min(r0 + it * ROWS_PER_PASS, nrows - 1);
+    xb[it].u = *reinterpret_cast<const uint4*>(Kblk + (int64_t)(2 * r + 1) * kv.stride_s);
+  }
+#pragma unroll
+  for (int it = 0; it < PIECES; ++it) {
+    if (r0 + it * ROWS_PER_PASS >= nrows) xa[it].u = make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(rows_lds + lds_piece0 + it * ROWS_PER_PASS * ROWB) = xa[it].u;
+  }
+  __syncthreads();
+  bf16x8 afrag[2][KSTEPS];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    const int row = wave * kRowsPerWave + rt * 32 + col;
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) afrag[rt][s] = *reinterpret_cast<const bf16x8*>(rows_lds + swz(row, 2 * s + half));
+  }
+  const float my_inva[2] = {inv_norm_of_operand_row<KSTEPS>(afrag[0]), inv_norm_of_operand_row<KSTEPS>(afrag[1])};
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < PIECES; ++it) {
+    if (r0 + it * ROWS_PER_PASS >= nrows) xb[it].u = make_uint4(0, 0, 0, 0);
+    const float ss = row_sum<OCT>(sumsq8(xb[it]));
+    *reinterpret_cast<uint4*>(rows_lds + lds_piece0 + it * ROWS_PER_PASS * ROWB) = xb[it].u;
+    if (piece == 0) invb[r0 + it * ROWS_PER_PASS] = inv_norm(ss);
+  }
+  __syncthreads();
+
+  int boff[KSTEPS];
+#pragma unroll
+  for (int s = 0; s < KSTEPS; ++s) boff[s] = swz(col, 2 * s + half);
+  const int tiles_per_chunk = chunk >> 6;          // B tiles (= A tiles) of a chunk: 1, 2 or 4
+  const int n_src = n_sources(seq, chunk);
+  const int64_t out_base = (int64_t)bh * n_src + (t0 >> 1);   // whole chunks before this block: source index = token / 2
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    const int tile = 2 * wave + rt;                // this wave's A tile within the block
+    if (tile * 32 >= nrows) break;                 // (uniform over the wave)
+    const int first = (tile / tiles_per_chunk) * tiles_per_chunk;   // first B tile of the A tile's chunk
+    float best = -INFINITY;
+    int bestj = 0;
+    for (int tt = 0; tt < tiles_per_chunk; ++tt) {
+      const unsigned char* pb = rows_lds + (first + tt) * 32 * ROWB;
+      f32x16 acc = {0};
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(pb + boff[s]), afrag[rt][s], acc, 0, 0, 0);
+      f32x4 ib[4];
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd)
+        ib[qd] = *reinterpret_cast<const f32x4*>(invb + (first + tt) * 32 + 4 * half + 8 * qd);
+      tile_argmax<false>(acc, ib, tt * 32, half, 32, best, bestj);
+    }
+    const float ob = __shfl_xor(best, 32);
+    const int oj = __shfl_xor(bestj, 32);
+    if (ob > best || (ob == best && oj < bestj)) { best = ob; bestj = oj; }
+    if (half == 0) {
+      const int a = tile * 32 + col;
+      dst_local[out_base + a] = bestj;
+      score[out_base + a] = best * my_inva[rt];
     }
   }
 }
@@ -646,7 +752,7 @@ __global__ void dst_positions_kernel(const int32_t* __restrict__ dst_local, int3
 
 template <int D, int NW, bool PAGED>
 hipError_t launch_match_bf16_nw(const void* K, TensorView kv, int n_bh, int seq, int chunk,
-                                int32_t* dst_local, float* score, hipStream_t st, PagedSide paged) {
+                                int32_t* dst_local, float* score, hipStream_t st, PagedSide paged, int g_first = 0) {
   constexpr int ABLOCK = NW * kRowsPerWave;
   // staging area + inverse norms of two panels (+ PAGED: the pool rows of a chunk's blocks, 8 tokens or more each)
   constexpr size_t lds = (size_t)(ABLOCK > 2 * kPanel ? ABLOCK : 2 * kPanel) * D * 2 + 2 * kPanel * sizeof(float) +
@@ -654,16 +760,41 @@ hipError_t launch_match_bf16_nw(const void* K, TensorView kv, int n_bh, int seq,
   static KernelSetup setup;
   if (hipError_t e = kernel_setup(reinterpret_cast<const void*>(&match_bf16_kernel<D, NW, PAGED>), lds, setup); e != hipSuccess)
     return e;
-  const int n_chunks = div_up(seq, chunk);
+  const int n_chunks = div_up(seq, chunk) - g_first;     // chunks g_first .. last
   const int a_blocks = div_up(chunk / 2, ABLOCK);
   const int64_t total = (int64_t)n_bh * n_chunks * a_blocks;
   if (total > (1 << 30)) return hipErrorInvalidValue;
   const int per_xcd = div_up((int)total, 8);
   ScopedTimer t("match_bf16", st);
   hipLaunchKernelGGL((match_bf16_kernel<D, NW, PAGED>), dim3(per_xcd * 8), dim3(NW * 64), lds, st,
-                     static_cast<const __bf16*>(K), kv, seq, chunk, n_chunks, a_blocks, (int)total,
+                     static_cast<const __bf16*>(K), kv, seq, chunk, n_chunks, g_first, a_blocks, (int)total,
                      per_xcd, dst_local, score, paged);
   return hipGetLastError();
+}
+
+// Chunks of 64, 128 or 256 tokens: the whole chunks of every sequence in blocks of 512 tokens, then the
+// ragged tail chunk (if any) with the one-chunk-per-workgroup kernel.
+template <int D>
+hipError_t launch_match_small(const void* K, TensorView kv, int n_bh, int seq, int chunk, int32_t* dst_local,
+                              float* score, hipStream_t st) {
+  constexpr size_t lds = (size_t)(kSmallTokens / 2) * D * 2 + (kSmallTokens / 2) * sizeof(float);
+  static KernelSetup setup;
+  if (hipError_t e = kernel_setup(reinterpret_cast<const void*>(&match_small_bf16_kernel<D>), lds, setup); e != hipSuccess)
+    return e;
+  const int n_full = seq / chunk;
+  const int blocks_per_seq = div_up(n_full * chunk, kSmallTokens);
+  const int64_t total = (int64_t)n_bh * blocks_per_seq;
+  if (total > (1 << 30)) return hipErrorInvalidValue;
+  const int per_xcd = div_up((int)total, 8);
+  {
+    ScopedTimer t("match_bf16", st);
+    hipLaunchKernelGGL((match_small_bf16_kernel<D>), dim3(per_xcd * 8), dim3(kThreads), lds, st,
+                       static_cast<const __bf16*>(K), kv, seq, chunk, n_full, blocks_per_seq, (int)total, per_xcd,
+                       dst_local, score);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  }
+  if (seq % chunk == 0) return hipSuccess;
+  return launch_match_bf16_nw<D, 4, false>(K, kv, n_bh, seq, chunk, dst_local, score, st, PagedSide{}, n_full);
 }
 
 // Whole 1024- or 2048-token chunks of 128-dim keys: the persistent kernel, one workgroup per CU.
@@ -694,6 +825,8 @@ hipError_t launch_match_bf16(const void* K, TensorView kv, int n_bh, int seq, in
     return launch_match_bf16_nw<D, 4, true>(K, kv, n_bh, seq, chunk, dst_local, score, st, paged);
   }
   if (chunk > 512) return launch_match_bf16_nw<D, 8, false>(K, kv, n_bh, seq, chunk, dst_local, score, st, paged);
+  if ((chunk == 64 || chunk == 128 || chunk == 256) && seq >= chunk)
+    return launch_match_small<D>(K, kv, n_bh, seq, chunk, dst_local, score, st);
   return launch_match_bf16_nw<D, 4, false>(K, kv, n_bh, seq, chunk, dst_local, score, st, paged);
 }
 

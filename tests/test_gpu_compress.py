@@ -97,6 +97,42 @@ def test_match_bf16_shapes(heads, seq, dim, chunk):
         check_match(f64(K[0, h]), chunk, i64(dst[0, h]), f64(score[0, h]), f"h{h}")
 
 
+# ---- chunks of 64, 128 and 256 tokens (the paper's chunk ablation): several chunks per workgroup ----
+@pytest.mark.parametrize("batch,heads,seq,dim,chunk,layout", [
+    (1, 2, 2048, 128, 64, "bhsd"),       # four full blocks of 512 tokens per sequence
+    (2, 3, 1600, 128, 128, "bshd"),      # last block holds one chunk only; token-major storage, two batches
+    (1, 2, 3000, 128, 256, "bhsd"),      # 11 whole chunks (the last block holds one) + a tail chunk of 184 tokens
+    (1, 3, 1000, 64, 64, "bhsd"),        # head_dim 64; 15 whole chunks + a tail of 40
+    (1, 2, 833, 64, 256, "bhsd"),        # head_dim 64; 3 whole chunks + an odd tail of 65
+    (1, 1, 64, 128, 64, "bhsd"),         # exactly one chunk
+    (1, 2, 191, 128, 128, "bhsd"),       # one whole chunk + a tail of 63
+])
+def test_match_small_chunk_kernel_bf16(batch, heads, seq, dim, chunk, layout):
+    """Whole chunks go through the kernel that packs 512 tokens (8, 4 or 2 chunks) into a workgroup,
+    a ragged tail chunk through the one-chunk-per-workgroup kernel; both write one result array."""
+    _say(f"match small chunks B={batch} H={heads} S={seq} D={dim} c={chunk} {layout}")
+    Ks = [kv_host(41 + b, heads, seq, dim, "bf16", alpha=0.9, n_outlier=4 if dim == 128 else 0)[0] for b in range(batch)]
+    K = torch.cat(Ks, dim=0)
+    if seq >= 200:
+        K[0, 0, 6] = 0                                         # a zero A key and a zero B key
+        K[0, 0, 9] = 0
+        K[0, -1, chunk:chunk + chunk // 2] = K[0, -1, chunk + 1]   # equal maxima: the lowest index must win
+    if layout == "bshd":
+        Kd = K.permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+    else:
+        Kd = K.to(DEV)
+    dst, score = ckv.match(Kd, chunk)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        for h in range(heads):
+            check_match(f64(K[b, h]), chunk, i64(dst[b, h]), f64(score[b, h]), f"b{b} h{h}")
+    if seq >= 200:                                             # the tie: every source of that stretch picks its chunk's first B token
+        g0 = chunk
+        srcs = [t for t in range(g0, g0 + chunk // 2, 2)]
+        got = i64(dst[0, heads - 1])[[t // 2 for t in srcs]]
+        assert np.all(got == g0 + 1), got
+
+
 # ---- the persistent kernel for whole 1024- or 2048-token chunks of 128-dim bf16 keys --------------
 @pytest.mark.parametrize("batch,heads,seq,layout,chunk", [
     (1, 5, 1024, "bhsd", 1024),        # one chunk per sequence: every item starts a new sequence
