@@ -48,6 +48,17 @@ def _cases():
         rounds = [float(rng.choice([0.5, 0.8, 1.0, 1.0, 1.0])) for _ in range(int(rng.integers(3, 6)))]
         out.append((k, dtype, int(rng.integers(1, 3)), seq, dim, chunk, rounds, int(rng.choice([0, 4])),
                     int(rng.choice([0, 7])), "chunk", bool(k % 3 == 1)))
+    # chunk sizes between the kernels' size classes (a third stream): 128 goes to the small-chunk similarity
+    # kernel like 64 and 256, 32 / 96 / 384 to the one-chunk-per-workgroup kernel
+    rng = np.random.default_rng(20250613)
+    for k in range(48, 62):
+        dtype = "bf16" if k % 5 else "f32"
+        dim = int(rng.choice([64, 128])) if dtype == "bf16" else int(rng.choice([32, 64]))
+        chunk = int(rng.choice([32, 96, 128, 128, 384]))
+        seq = int(rng.integers(chunk, 2600))
+        rounds = [float(rng.choice([0.25, 0.5, 0.8, 1.0, 1.0])) for _ in range(int(rng.integers(1, 4)))]
+        out.append((k, dtype, int(rng.integers(1, 4)), seq, dim, chunk, rounds, int(rng.choice([0, 16])),
+                    int(rng.choice([0, 64])), "head" if k % 7 == 3 else "chunk", bool(k % 3 == 1)))
     return out
 
 
