@@ -124,6 +124,41 @@ def test_128k_layer_with_sinks_recents_annealed_schedule_and_whole_sequence_sele
         assert torch.equal(cK[0, h], curK[0, 0]) and torch.equal(cdeg[0, h], curdeg[0, 0])
 
 
+def test_128k_layer_with_the_papers_own_hyper_parameters():
+    """One layer (8 KV heads x 131072 tokens) with the settings of Sec. 6.1: chunk 256, 16 sinks, 64
+    recents, merge fractions annealed from 0.8 by 0.2 (Eq. 4; the schedule's floor, which the paper
+    leaves open, at 0.2) down to the 25% budget - six rounds, whole chunks through the several-
+    chunks-per-workgroup similarity kernel, a ragged tail chunk through the other one.  Invariants
+    on every head; one head round by round against the oracle, and the one call must equal the
+    rounds issued one by one."""
+    _say("128k layer: chunk 256, sinks/recents, six annealed rounds")
+    n1, n2, chunk = 16, 64, 256
+    rounds = ckv.schedule_annealed(SEQ, chunk, SEQ // 4, 0.8, 0.2, 0.2, n1, n2)
+    assert [round(float(r), 3) for r in rounds] == [0.8, 0.6, 0.4, 0.2, 0.2, 0.2]
+    K = torch.empty((1, HEADS, SEQ, DIM), dtype=torch.bfloat16, device=DEV)
+    V = torch.empty_like(K)
+    kv_device(909, HEADS, SEQ, DIM, "bf16", 0.9, 4, layer=0, device=DEV, out_k=K[0], out_v=V[0])
+    cK, cV, cdeg, assign = ckv.compress(K, V, chunk, rounds=rounds, n_sink=n1, n_recent=n2)
+    torch.cuda.synchronize()
+    out_len = oracle.round_lengths(SEQ, chunk, rounds, n1, n2)[-1]
+    assert out_len <= SEQ // 4 and cK.shape == (1, HEADS, out_len, DIM)
+    assert torch.equal(cdeg.sum(dim=-1), torch.full((1, HEADS), SEQ, dtype=torch.int64, device=DEV))
+    assert torch.equal(cK[:, :, :n1], K[:, :, :n1]) and torch.equal(cV[:, :, -n2:], V[:, :, -n2:])
+    counts = torch.zeros((HEADS, out_len), dtype=torch.int32, device=DEV)
+    counts.scatter_add_(1, assign[0].to(torch.int64), torch.ones((HEADS, SEQ), dtype=torch.int32, device=DEV))
+    assert torch.equal(counts, cdeg[0])
+    h = 5
+    curK, curV, curdeg = K[:, h:h + 1].contiguous(), V[:, h:h + 1].contiguous(), None
+    for j, r in enumerate(rounds):
+        gK, gV, gdeg, gas = ckv.compress(curK, curV, chunk, rounds=[r], deg=curdeg, n_sink=n1, n_recent=n2)
+        torch.cuda.synchronize()
+        d_in = np.ones(curK.shape[2], dtype=np.int64) if curdeg is None else i64(curdeg[0, 0])
+        check_round_with_edges(f64(curK[0, 0]), f64(curV[0, 0]), d_in, chunk, r, "bf16", n1, n2, f64(gK[0, 0]),
+                               f64(gV[0, 0]), i64(gdeg[0, 0]), i64(gas[0, 0]), what=f"head {h} round {j}")
+        curK, curV, curdeg = gK, gV, gdeg
+    assert torch.equal(cK[0, h], curK[0, 0]) and torch.equal(cV[0, h], curV[0, 0]) and torch.equal(cdeg[0, h], curdeg[0, 0])
+
+
 # ---- serving decode shape (batch 16, pre-compressed caches, appended tokens) --------------------
 def test_serving_decode_batch16_with_appended_tokens():
     """16 sequences of 32768 tokens compressed to 25%, a few decoded tokens appended with degree 1
